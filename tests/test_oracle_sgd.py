@@ -1,0 +1,99 @@
+"""Pins for the oracle's quantized SGD-with-momentum step (Sec. 3.1 "Front-end interface";
+Sec. 1 footnote 1 for the fp32 master copy)."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import qsim_ref as R
+from paper_1910_04540_amd import workloads as W
+from helpers import (RN_EVEN, STOCHASTIC, SATURATE, SUBNORMAL, assert_bit_equal, f32_to_fraction,
+                     round_fraction_to_f32)
+
+IDENT = R.Format(0, 0, 0, 0, 0)
+
+
+def test_identity_formats_give_textbook_sgd_with_one_rounding_per_fma():
+    """With every format the identity the step is v' = fl(mu*v + g), w' = fl(w - lr*v'), each a
+    single correctly rounded operation: checked in exact rational arithmetic."""
+    n = 400
+    w, g, m = W.sgd_state(n)
+    lr, mu = np.float32(0.1), np.float32(0.9)
+    w2, wq, m2 = R.quant_sgd_step(w, g, m, lr, mu, IDENT, IDENT, IDENT)
+    for i in range(n):
+        v = round_fraction_to_f32(f32_to_fraction(mu) * f32_to_fraction(m[i]) + f32_to_fraction(g[i]))
+        assert m2[i] == v
+        wi = round_fraction_to_f32(f32_to_fraction(w[i]) - f32_to_fraction(lr) * f32_to_fraction(v))
+        assert w2[i] == wi
+    assert_bit_equal(wq, w2, "identity weight format copies the master weights")
+    # a product that is not representable shows a fused operation differs from two roundings
+    a = np.float32(1.0 + 2.0 ** -12)
+    two_step = np.float32(np.float32(a * a) + np.float32(-1.0))
+    one_step = round_fraction_to_f32(f32_to_fraction(a) ** 2 - 1)
+    assert two_step != one_step
+    w2, _, m2 = R.quant_sgd_step(np.zeros(1, np.float32), np.array([-1.0], np.float32), np.array([a], np.float32),
+                                 0.0, a, IDENT, IDENT, IDENT)
+    assert m2[0] == one_step
+
+
+@pytest.mark.parametrize("fg,fm,fw", [
+    (R.Format(1, 5, 2, STOCHASTIC, SATURATE | SUBNORMAL), R.Format(2, 16, 12, STOCHASTIC, SATURATE), R.Format(3, 8, 256, RN_EVEN, 0)),
+    (R.Format(2, 8, 10, RN_EVEN, SATURATE), R.Format(1, 8, 7, RN_EVEN, SATURATE), R.Format(1, 5, 10, STOCHASTIC, SATURATE | SUBNORMAL)),
+    (R.Format(3, 8, 64, STOCHASTIC, 0), R.Format(3, 12, 1024, STOCHASTIC, 0), R.Format(3, 6, 4, STOCHASTIC, 0)),
+    (IDENT, R.Format(2, 16, 12, STOCHASTIC, SATURATE), R.Format(2, 8, 6, STOCHASTIC, SATURATE)),
+])
+@pytest.mark.parametrize("n", [2048, 1000])
+def test_step_is_the_composition_of_the_pinned_quantizers(fg, fm, fw, n):
+    """The step equals: quantize the gradient array, one fma, quantize, one fma, quantize, built
+    from the array quantizers pinned elsewhere.  Random words: role 0/1/2, same seed and stream."""
+    w, g, m = W.sgd_state(n)
+    lr, mu, seed, stream = np.float32(0.1), np.float32(0.9), 1234, 3
+
+    def q(x, f, role):
+        if f.kind == 0:
+            return x.copy()
+        words = None
+        if f.rounding == STOCHASTIC:
+            words = R.random_words(seed, stream, role, x.size)
+        out = np.empty_like(x)
+        if f.kind == 3:
+            for c0 in range(0, x.size, f.b):
+                blk = x[c0:c0 + f.b]
+                e_s = int(R.block_exponents(blk, 1, 1, blk.size)[0])
+                for i, v in enumerate(blk):
+                    out[c0 + i] = R.fixed_scalar(v, f.a, f.a - 2 - e_s, f.rounding, SATURATE | (f.flags & 4),
+                                                 int(words[c0 + i]) if words is not None else 0)
+            return out
+        fn = R.float_scalar if f.kind == 1 else R.fixed_scalar
+        for i, v in enumerate(x):
+            out[i] = fn(v, f.a, f.b, f.rounding, f.flags, int(words[i]) if words is not None else 0)
+        return out
+
+    def fma(a, b, c):
+        return np.array([round_fraction_to_f32(f32_to_fraction(a) * f32_to_fraction(bi) + f32_to_fraction(ci))
+                         for bi, ci in zip(b, c)], dtype=np.float32)
+
+    gq = q(g, fg, 0)
+    v = q(fma(mu, m, gq), fm, 1)
+    wn = fma(-lr, v, w)
+    wq_want = q(wn, fw, 2)
+    w2, wq, m2 = R.quant_sgd_step(w, g, m, lr, mu, fg, fm, fw, seed, stream)
+    assert_bit_equal(m2, v, "momentum")
+    assert_bit_equal(w2, wn, "master weights")
+    assert_bit_equal(wq, wq_want, "quantized weights")
+    w3, none, m3 = R.quant_sgd_step(w, g, m, lr, mu, fg, fm, fw, seed, stream, want_wq=False)
+    assert none is None
+    assert_bit_equal(w3, w2, "w without w_q") and assert_bit_equal(m3, m2, "mom without w_q")
+
+
+def test_validation():
+    w, g, m = W.sgd_state(64)
+    bad = [R.Format(4, 0, 0, 0, 0), R.Format(1, 9, 2, 0, 0), R.Format(2, 30, 2, 0, 0), R.Format(3, 8, 100, 0, 0),
+           R.Format(3, 8, 2048, 0, 0), R.Format(3, 1, 64, 0, 0), R.Format(2, 8, 6, 0, 16)]
+    for f in bad:
+        with pytest.raises(R.OracleError) as e:
+            R.quant_sgd_step(w, g, m, 0.1, 0.9, f, IDENT, IDENT)
+        assert e.value.status == 2
+    with pytest.raises(R.OracleError) as e:
+        R.quant_sgd_step(w, g, m, 0.1, 0.9, IDENT, R.Format(2, 8, 6, 7, 0), IDENT)
+    assert e.value.status == 3
