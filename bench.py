@@ -1,0 +1,211 @@
+#!/usr/bin/env python3
+"""Throughput of the fused quantize-and-round kernels on one MI355X.
+
+A step is one fixed-point quantize call (wl = 8, fl = 6, stochastic rounding, clamp on overflow)
+over a 64 Mi-element fp32 tensor that is already resident in HBM.  Inputs rotate over three
+buffer sets so that no step finds its tensor in the memory-side cache.  One JSON line is printed:
+the headline elements/s, the HBM roofline of the dominant kernel measured with HIP events on
+the launch stream, the same figures for the other formats (`formats`), and the CPU oracle timed on
+the host cores as a reported baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-formats] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+BYTES_PER_ELEMENT = 8          # one fp32 read + one fp32 write
+SGD_BYTES_PER_PARAM = 24       # three reads + three writes
+NSETS = 3
+
+# HBM traffic per launch of the headline kernel measured with rocprofv3 --pmc (FETCH_SIZE and
+# WRITE_SIZE, scaled by a copy kernel of known size); None until such a run is recorded under
+# profiles/.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def _time_launches(fn, steps, warmup, torch):
+    """fn(k) enqueues launch k on torch's current stream.  Returns (wall seconds, event seconds)."""
+    for k in range(warmup):
+        fn(k)
+    torch.cuda.synchronize()
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    start.record()
+    for k in range(steps):
+        fn(k)
+    stop.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, start.elapsed_time(stop) * 1e-3
+
+
+def _rotating(x_host, torch):
+    """Three device copies of a workload (rolled so they differ) plus three output buffers."""
+    base = torch.from_numpy(x_host).cuda().reshape(-1)
+    ins = [base] + [torch.roll(base, 1234567 * (k + 1)) for k in range(NSETS - 1)]
+    outs = [torch.empty_like(base) for _ in range(NSETS)]
+    return ins, outs
+
+
+def _entry(name, elements, bytes_per_element, seconds, launches, extra=None):
+    per = seconds / launches
+    gbs = elements * bytes_per_element / per / 1e9
+    d = {"elements": elements, "us_per_call": per * 1e6, "elements_per_s": elements / per, "GBps": gbs,
+         "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+    if extra:
+        d.update(extra)
+    return name, d
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-formats", action="store_true", help="skip the per-format table")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_1910_04540_amd import binding as Q
+    from paper_1910_04540_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    Q.lib()
+    torch.cuda.set_device(0)
+
+    # ---- headline: fixed point (8, 6), stochastic, saturating, 64 Mi elements -----------------
+    x_host = W.uniform_with_outliers()
+    n = x_host.size
+    ins, outs = _rotating(x_host, torch)
+
+    def fixed_step(k):
+        Q.fixed_quantize(ins[k % NSETS], 8, 6, Q.STOCHASTIC, Q.SATURATE, seed=1234, stream_id=k, out=outs[k % NSETS])
+
+    wall, ev = _time_launches(fixed_step, args.steps, args.warmup, torch)
+    value = n * args.steps / wall
+    achieved = n * BYTES_PER_ELEMENT / (ev / args.steps) / 1e9
+    result = {
+        "metric": "quantized elements/sec, fixed-point (wl=8, fl=6) stochastic rounding with clamp, 1 MI355X",
+        "value": value,
+        "unit": "elements/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": "fixed_point_quantize 64Mi fp32 (90% U[-4,4) + 10% N(0,sd 10)), wl=8 fl=6, "
+                               "stochastic (Philox seed 1234), saturate", "elements": n,
+                   "buffer_sets": NSETS, "in_place": False},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
+                     "kernel": "elementwise_kernel<FixedOp, stochastic>", "algorithmic_bytes": n * BYTES_PER_ELEMENT,
+                     "avg_launch_us": ev / args.steps * 1e6},
+    }
+
+    # ---- the other formats ---------------------------------------------------------------------
+    if not args.no_formats:
+        formats = {}
+        reps = max(10, args.steps // 4)
+
+        def run(name, fn, elements, bpe=BYTES_PER_ELEMENT, extra=None):
+            _, e = _time_launches(fn, reps, 5, torch)
+            k, d = _entry(name, elements, bpe, e, reps, extra)
+            formats[k] = d
+
+        run("fixed_8_6_nearest_even", lambda k: Q.fixed_quantize(ins[k % NSETS], 8, 6, Q.RN_EVEN, Q.SATURATE,
+                                                                   out=outs[k % NSETS]), n)
+        run("fixed_8_6_stochastic_in_place", lambda k: Q.fixed_quantize(outs[k % NSETS], 8, 6, Q.STOCHASTIC, Q.SATURATE,
+                                                                          seed=1234, stream_id=k, out=outs[k % NSETS]), n,
+            extra={"note": "input already quantized by the previous runs"})
+        del ins, outs
+        torch.cuda.empty_cache()
+
+        small = torch.from_numpy(W.normal_tensor()).cuda()
+        small_out = torch.empty_like(small)
+        run("float_e5m2_nearest_even_1Mi", lambda k: Q.float_quantize(small, 5, 2, Q.RN_EVEN, Q.SATURATE, out=small_out),
+            small.numel(), extra={"note": "launch-latency bound, cache resident"})
+
+        a_in, a_out = _rotating(W.relu_activations().reshape(-1), torch)
+        na = a_in[0].numel()
+        run("float_e8m7_stochastic_activations", lambda k: Q.float_quantize(
+            a_in[k % NSETS], 8, 7, Q.STOCHASTIC, Q.SATURATE | Q.SUBNORMAL, seed=1234, stream_id=k, out=a_out[k % NSETS]), na)
+        g_host = W.lognormal_gradients().reshape(-1)
+        for k in range(NSETS):
+            a_in[k].copy_(torch.roll(torch.from_numpy(g_host).cuda(), 7654321 * k))
+        run("float_e5m10_nearest_even_gradients", lambda k: Q.float_quantize(
+            a_in[k % NSETS], 5, 10, Q.RN_EVEN, Q.SATURATE | Q.SUBNORMAL, out=a_out[k % NSETS]), na)
+        del a_in, a_out
+        torch.cuda.empty_cache()
+
+        m_host = W.row_scaled_matrix()
+        rows, cols = m_host.shape
+        m_in = [torch.from_numpy(np.roll(m_host, 17 * k, axis=0)).cuda() for k in range(NSETS)]
+        m_out = [torch.empty_like(m_in[0]) for _ in range(NSETS)]
+        nm = rows * cols
+        ws_bytes = Q.block_workspace_bytes(nm, 1, 1, nm)
+        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+        for mode, tag in ((Q.RN_EVEN, "nearest_even"), (Q.STOCHASTIC, "stochastic")):
+            run(f"block8_per_row_{tag}", lambda k, mode=mode: Q.block_quantize(
+                m_in[k % NSETS], 1, rows, cols, 8, mode, 0, 1234, k, out=m_out[k % NSETS]), nm)
+            run(f"block8_whole_tensor_{tag}", lambda k, mode=mode: Q.block_quantize(
+                m_in[k % NSETS], 1, 1, nm, 8, mode, 0, 1234, k, out=m_out[k % NSETS], workspace=ws), nm,
+                extra={"note": "fraction is against 8 B/element; the input is read twice"})
+        del m_in, m_out
+        torch.cuda.empty_cache()
+
+        w, g, m = W.sgd_state()
+        npar = w.size
+        fg = Q.Format(Q.KIND_FLOAT, 5, 2, Q.STOCHASTIC, Q.SATURATE | Q.SUBNORMAL)
+        fm = Q.Format(Q.KIND_FIXED, 16, 12, Q.STOCHASTIC, Q.SATURATE)
+        fw = Q.Format(Q.KIND_BLOCK, 8, 256, Q.RN_EVEN, 0)
+        sets = []
+        for k in range(NSETS):
+            sets.append([torch.from_numpy(np.roll(a, 99991 * k)).cuda() for a in (w, g, m)] + [torch.empty(npar, device="cuda")])
+        run("quant_sgd_step_25.6M", lambda k: Q.quant_sgd_step(sets[k % NSETS][0], sets[k % NSETS][1], sets[k % NSETS][2],
+                                                               0.1, 0.9, fg, fm, fw, 1234, k + 2, w_q=sets[k % NSETS][3]),
+            npar, bpe=SGD_BYTES_PER_PARAM,
+            extra={"note": "grad float(5,2) stochastic, momentum fixed(16,12) stochastic, weight block8 per 256 nearest"})
+        del sets
+        torch.cuda.empty_cache()
+        result["formats"] = formats
+
+    # ---- CPU baseline: the oracle as it stands, on the host cores ------------------------------
+    if not args.no_cpu:
+        from oracle import qsim_ref as R
+
+        threads = min(16, os.cpu_count() or 1)
+        R.lib()
+        t0 = time.perf_counter()
+        R.fixed_quantize(x_host, 8, 6, R.STOCHASTIC, R.SATURATE, seed=1234, threads=threads)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": n / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"the whole {n}-element tensor of the headline workload, one pass, "
+                                            f"split over {threads} threads ({dt:.2f} s wall)"}
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

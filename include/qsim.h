@@ -1,0 +1,146 @@
+/*
+ * qsim.h -- C-ABI of libqsim: fused quantize-and-round kernels for MI355X (gfx950).
+ *
+ * The library simulates low-precision number formats the way arXiv 1910.04540 (QPyTorch)
+ * describes in Sec. 3: a low-precision number is stored as the fp32 number it equals, so
+ * every call maps an fp32 array onto the values a format can represent, in one fused kernel
+ * appended after a regular fp32 operation (Sec. 3.2, the "two-kernel approach").
+ *
+ * Conventions shared by all entry points
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  Format descriptors
+ *     (qsim_format) are HOST pointers, read before the call returns.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it and the call returns without synchronising.
+ *   - The library allocates and frees nothing.  Scratch memory, where needed, is the caller's
+ *     `workspace`.
+ *   - in == out (exactly the same array) is allowed; any other overlap between arrays of one
+ *     call is rejected with QSIM_ERR_OVERLAP.
+ *   - n == 0 is a successful no-op.  n is limited to 2^40 elements.
+ *   - Return value: a QSIM_* status; 0 = success.  Arguments are validated in the order
+ *     rounding, format/flags, shape, n == 0, null pointers, overlap, workspace; nothing is
+ *     launched when validation fails.  No exception or abort crosses this boundary.
+ *   - Non-finite inputs (the paper does not simulate them): NaN is returned unchanged; +-Inf is
+ *     treated as larger than every finite number (the largest code when the format saturates,
+ *     unchanged otherwise).
+ *
+ * Rounding (Sec. 3.1 "Rounding mode"): every format rounds the magnitude |x| to an integer
+ * multiple K of a grid step 2^q and re-attaches the sign.  With y = |x| / 2^q, k = floor(y),
+ * f = y - k:  K = k + 1 if the mode rounds up, else k.
+ *     QSIM_RN_EVEN     up when f > 1/2, or f == 1/2 and k is odd
+ *     QSIM_RN_AWAY     up when f >= 1/2            (ties away from zero)
+ *     QSIM_RN_ZERO     up when f > 1/2             (ties toward zero)
+ *     QSIM_STOCHASTIC  up when r < floor(f * 2^32), r = the element's 32-bit random word
+ * Random words come from Philox4x32-10 with key = (seed mod 2^32, seed div 2^32) and counter =
+ * (lo32(i div 4), hi32(i div 4), stream_id, role): element i (flat row-major index in the
+ * array passed to the call) takes output word i mod 4.  role is 0 except in the SGD step.
+ * Results therefore do not depend on the launch shape and are reproducible from
+ * (seed, stream_id) alone.
+ */
+#ifndef QSIM_H
+#define QSIM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    QSIM_OK = 0,
+    QSIM_ERR_NULL = 1,        /* a required pointer is NULL */
+    QSIM_ERR_FORMAT = 2,      /* format parameters or flags out of range */
+    QSIM_ERR_ROUNDING = 3,    /* rounding mode not one of the four below */
+    QSIM_ERR_SHAPE = 4,       /* n does not match the block layout, or n too large */
+    QSIM_ERR_OVERLAP = 5,     /* arrays overlap (other than in == out) */
+    QSIM_ERR_WORKSPACE = 6,   /* workspace missing, misaligned or too small */
+    QSIM_ERR_UNSUPPORTED = 7,
+    QSIM_ERR_LAUNCH = 8       /* the HIP runtime refused the launch (no device, bad stream) */
+};
+
+/* Sec. 3.1 "Rounding mode". */
+enum { QSIM_RN_EVEN = 0, QSIM_RN_AWAY = 1, QSIM_RN_ZERO = 2, QSIM_STOCHASTIC = 3 };
+
+enum {
+    QSIM_SATURATE = 1u,   /* clamp to the format's range instead of leaving the range open */
+    QSIM_SUBNORMAL = 2u,  /* float only: gradual underflow below 2^emin instead of flush to zero */
+    QSIM_SYMMETRIC = 4u   /* fixed/block: drop the most negative two's-complement code */
+};
+
+/*
+ * Floating point with exp_bits exponent and man_bits mantissa bits (Sec. 3.1 "Number Formats",
+ * first paragraph).  2 <= exp_bits <= 8, 1 <= man_bits <= 23.  IEEE-like: bias = 2^(E-1) - 1,
+ * emax = bias, emin = 1 - bias, largest value (2 - 2^-M) * 2^emax; (5,10) is binary16, (8,7)
+ * is bfloat16.  Grid step of x: 2^(e - M) with e = floor(log2 |x|); with QSIM_SUBNORMAL the
+ * step stops shrinking at 2^(emin - M), without it results below 2^emin become (signed) zero.
+ * QSIM_SATURATE clamps magnitudes above the largest value to it; otherwise the exponent is
+ * unbounded above within the fp32 carrier.
+ */
+int qsim_float_quantize(const float* in, float* out, uint64_t n, int exp_bits, int man_bits,
+                        int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id,
+                        void* hip_stream);
+
+/*
+ * Fixed point with word length wl and fl fractional bits (Sec. 3.1 "Number Formats", second
+ * paragraph).  1 <= wl <= 24, wl - 128 <= fl <= 149.  Grid step 2^-fl.  With QSIM_SATURATE the
+ * integer code is clamped to [-2^(wl-1), 2^(wl-1) - 1] ([-(2^(wl-1) - 1), 2^(wl-1) - 1] with
+ * QSIM_SYMMETRIC); without it the value is only rounded to the grid.
+ */
+int qsim_fixed_quantize(const float* in, float* out, uint64_t n, int wl, int fl, int rounding,
+                        uint32_t flags, uint64_t seed, uint32_t stream_id, void* hip_stream);
+
+/*
+ * Block floating point with word length wl (Sec. 3.1 "Number Formats", second paragraph: the
+ * exponent is shared across a block; a block is one index of a tensor dimension or the whole
+ * tensor).  2 <= wl <= 24.  The array is viewed row-major as [outer, nblocks, inner]; block b
+ * is the set of elements (o, b, i).  Whole tensor: (1, 1, n).  Leading dimension of [R, C]:
+ * (1, R, C).  Contiguous chunks of L: (1, ceil(n / L), L), where the last chunk may be short.
+ * n must equal outer * nblocks * inner unless outer == 1.
+ * Per block: e_s = the fp32 exponent field of the largest |x| in the block, clamped to
+ * [1, 254], minus 127; grid step 2^(e_s + 2 - wl); integer codes always clamped to
+ * [-2^(wl-1), 2^(wl-1) - 1] (QSIM_SYMMETRIC as above).  The maximum is taken on the raw input.
+ *
+ * workspace: device scratch of at least qsim_block_workspace_bytes(...) bytes, 16-byte
+ * aligned, used for per-block maxima when a block is spread over several workgroups; may be
+ * NULL when that function returns 0.  Its contents are overwritten; it needs no initialisation.
+ */
+int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks,
+                        uint64_t inner, int wl, int rounding, uint32_t flags, uint64_t seed,
+                        uint32_t stream_id, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
+size_t qsim_block_workspace_bytes(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner);
+
+/* A number format for one category of numbers in the optimizer (Sec. 3.1 "Front-end interface"). */
+typedef struct {
+    int kind;       /* 0 identity (fp32), 1 float, 2 fixed, 3 block over contiguous chunks */
+    int a;          /* exp_bits | wl | wl */
+    int b;          /* man_bits | fl | chunk length L: a power of two, 4 <= L <= 1024 */
+    int rounding;   /* QSIM_RN_* or QSIM_STOCHASTIC */
+    uint32_t flags; /* QSIM_SATURATE | QSIM_SUBNORMAL | QSIM_SYMMETRIC */
+} qsim_format;
+
+/*
+ * Fused low-precision SGD-with-momentum step (Sec. 3.1 "Front-end interface": weight, gradient
+ * and accumulator are quantized by the optimizer, each with its own format; Sec. 1 footnote 1:
+ * an fp32 master copy of the weights accumulates the updates).  One pass, per element i:
+ *     gq        = Qg(grad[i])
+ *     v         = Qm(fma(momentum, mom[i], gq));     mom[i] = v
+ *     w         = fma(-lr, v, w_master[i]);          w_master[i] = w      (not quantized)
+ *     w_q[i]    = Qw(w)                              (skipped when w_q is NULL)
+ * Both fma are single-rounding fp32 operations.  A block-kind format groups the array it
+ * quantizes into contiguous chunks of L elements (the last may be short).  Random words use
+ * role 0 for the gradient, 1 for the momentum and 2 for the weight.  No dampening, Nesterov
+ * momentum or weight decay.  w_master and mom are updated in place; grad is read only.
+ */
+int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n,
+                        float lr, float momentum, const qsim_format* fmt_grad,
+                        const qsim_format* fmt_mom, const qsim_format* fmt_weight, uint64_t seed,
+                        uint32_t stream_id, void* hip_stream);
+
+/* Static description of a status code (never NULL). */
+const char* qsim_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

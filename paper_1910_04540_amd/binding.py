@@ -1,0 +1,147 @@
+"""Thin Python binding of the libqsim C-ABI (include/qsim.h): argument marshalling only.
+
+PyTorch supplies device memory and the current HIP stream; every step of the computation runs in
+the library's kernels.  There is no fallback: if libqsim.so is not built, importing the entry
+points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libqsim.so")
+
+RN_EVEN, RN_AWAY, RN_ZERO, STOCHASTIC = 0, 1, 2, 3
+SATURATE, SUBNORMAL, SYMMETRIC = 1, 2, 4
+KIND_IDENTITY, KIND_FLOAT, KIND_FIXED, KIND_BLOCK = 0, 1, 2, 3
+
+# Every symbol include/qsim.h declares.
+EXPORTS = ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_block_workspace_bytes",
+           "qsim_quant_sgd_step", "qsim_status_string")
+
+
+class Format(ctypes.Structure):
+    """qsim_format: kind, a, b, rounding, flags."""
+    _fields_ = [("kind", ctypes.c_int), ("a", ctypes.c_int), ("b", ctypes.c_int),
+                ("rounding", ctypes.c_int), ("flags", ctypes.c_uint32)]
+
+
+class QsimError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libqsim status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libqsim.so.  Fails loudly when it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_1910_04540_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, u64, u32, ci, sz = ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_int, ctypes.c_size_t
+    L.qsim_float_quantize.argtypes = [vp, vp, u64, ci, ci, ci, u32, u64, u32, vp]
+    L.qsim_fixed_quantize.argtypes = [vp, vp, u64, ci, ci, ci, u32, u64, u32, vp]
+    L.qsim_block_quantize.argtypes = [vp, vp, u64, u64, u64, u64, ci, ci, u32, u64, u32, vp, sz, vp]
+    L.qsim_block_workspace_bytes.argtypes = [u64, u64, u64, u64]
+    L.qsim_block_workspace_bytes.restype = sz
+    L.qsim_quant_sgd_step.argtypes = [vp, vp, vp, vp, u64, ctypes.c_float, ctypes.c_float,
+                                      ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
+                                      u64, u32, vp]
+    L.qsim_status_string.argtypes = [ci]
+    L.qsim_status_string.restype = ctypes.c_char_p
+    for name in ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_quant_sgd_step"):
+        getattr(L, name).restype = ci
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().qsim_status_string(status).decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise QsimError(status, status_string(status))
+
+
+def _device_f32(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.float32 or not t.is_contiguous():
+        raise TypeError(f"{name} must be a contiguous float32 tensor on the GPU")
+    return t
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _out_like(x: torch.Tensor, out) -> torch.Tensor:
+    if out is None:
+        return torch.empty_like(x)
+    _device_f32(out, "out")
+    if out.numel() != x.numel():
+        raise ValueError("out must have as many elements as the input")
+    return out
+
+
+def float_quantize(x, exp_bits, man_bits, rounding=RN_EVEN, flags=SATURATE, seed=0, stream_id=0, out=None):
+    """qsim_float_quantize on a device tensor; returns the output tensor (``out`` may be ``x``)."""
+    _device_f32(x, "x")
+    out = _out_like(x, out)
+    _check(lib().qsim_float_quantize(x.data_ptr(), out.data_ptr(), x.numel(), exp_bits, man_bits, rounding, flags,
+                                     seed, stream_id, _stream()))
+    return out
+
+
+def fixed_quantize(x, wl, fl, rounding=RN_EVEN, flags=SATURATE, seed=0, stream_id=0, out=None):
+    """qsim_fixed_quantize on a device tensor."""
+    _device_f32(x, "x")
+    out = _out_like(x, out)
+    _check(lib().qsim_fixed_quantize(x.data_ptr(), out.data_ptr(), x.numel(), wl, fl, rounding, flags, seed,
+                                     stream_id, _stream()))
+    return out
+
+
+def block_workspace_bytes(n, outer, nblocks, inner) -> int:
+    return int(lib().qsim_block_workspace_bytes(n, outer, nblocks, inner))
+
+
+def block_quantize(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed=0, stream_id=0, out=None,
+                   workspace=None):
+    """qsim_block_quantize on a device tensor viewed as [outer, nblocks, inner].
+
+    ``workspace``: a device tensor of at least ``block_workspace_bytes(...)`` bytes; allocated
+    through torch when omitted and needed."""
+    _device_f32(x, "x")
+    out = _out_like(x, out)
+    need = block_workspace_bytes(x.numel(), outer, nblocks, inner)
+    ws_ptr, ws_bytes = 0, 0
+    if need:
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
+    _check(lib().qsim_block_quantize(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, wl, rounding,
+                                     flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
+    return out
+
+
+def quant_sgd_step(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format,
+                   seed=0, stream_id=0, w_q=None):
+    """qsim_quant_sgd_step: updates ``w_master`` and ``mom`` in place, fills ``w_q`` when given."""
+    _device_f32(w_master, "w_master")
+    _device_f32(grad, "grad")
+    _device_f32(mom, "mom")
+    n = w_master.numel()
+    if grad.numel() != n or mom.numel() != n or (w_q is not None and _device_f32(w_q, "w_q").numel() != n):
+        raise ValueError("all tensors of the step must have the same number of elements")
+    _check(lib().qsim_quant_sgd_step(w_master.data_ptr(), w_q.data_ptr() if w_q is not None else None,
+                                     grad.data_ptr(), mom.data_ptr(), n, lr, momentum, ctypes.byref(fmt_grad),
+                                     ctypes.byref(fmt_mom), ctypes.byref(fmt_weight), seed, stream_id, _stream()))
+    return w_q

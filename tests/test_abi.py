@@ -1,0 +1,102 @@
+"""The C-ABI library loads, exports every symbol include/qsim.h declares, and validates its
+arguments before touching the GPU (so all of this runs on a host without one)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+B = pytest.importorskip("paper_1910_04540_amd.binding")
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "qsim.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qsim_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = _declared_symbols()
+    assert set(names) == set(B.EXPORTS), names
+    L = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    for s in range(0, 9):
+        assert B.status_string(s) and B.status_string(s) != "unknown status"
+    assert B.status_string(99) == "unknown status"
+
+
+FAKE = 0x10000   # a non-null, 16-byte aligned address that is never dereferenced on the host
+
+
+def test_elementwise_validation_without_gpu():
+    L = B.lib()
+    ok = (8, 6, 0, 1, 0, 0, None)
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 0, *ok) == 0                           # n == 0: no-op
+    assert L.qsim_fixed_quantize(None, None, 0, *ok) == 0
+    assert L.qsim_fixed_quantize(None, FAKE, 16, *ok) == 1
+    assert L.qsim_fixed_quantize(FAKE, None, 16, *ok) == 1
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 16, 0, 6, 0, 1, 0, 0, None) == 2
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 16, 25, 6, 0, 1, 0, 0, None) == 2
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 16, 8, 150, 0, 1, 0, 0, None) == 2
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 16, 8, -121, 0, 1, 0, 0, None) == 2
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 16, 8, 6, 0, 8, 0, 0, None) == 2       # unknown flag
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 16, 8, 6, 4, 1, 0, 0, None) == 3
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 16, 0, 6, 4, 1, 0, 0, None) == 3       # rounding is checked first
+    assert L.qsim_fixed_quantize(FAKE, FAKE + 32, 16, *ok) == 5                     # partial overlap
+    assert L.qsim_fixed_quantize(FAKE, FAKE, (1 << 40) + 1, *ok) == 4
+    assert L.qsim_float_quantize(FAKE, FAKE, 16, 1, 2, 0, 1, 0, 0, None) == 2
+    assert L.qsim_float_quantize(FAKE, FAKE, 16, 9, 2, 0, 1, 0, 0, None) == 2
+    assert L.qsim_float_quantize(FAKE, FAKE, 16, 5, 0, 0, 1, 0, 0, None) == 2
+    assert L.qsim_float_quantize(FAKE, FAKE, 16, 5, 24, 0, 1, 0, 0, None) == 2
+    assert L.qsim_float_quantize(FAKE, FAKE, 16, 5, 2, -1, 1, 0, 0, None) == 3
+    assert L.qsim_float_quantize(None, FAKE, 16, 5, 2, 0, 1, 0, 0, None) == 1
+    assert L.qsim_float_quantize(FAKE, FAKE + 4, 16, 5, 2, 0, 1, 0, 0, None) == 5
+
+
+def test_block_validation_without_gpu():
+    L = B.lib()
+
+    def call(n, outer, nblocks, inner, wl=8, rounding=0, flags=0, ws=None, ws_bytes=0, a=FAKE, b=FAKE):
+        return L.qsim_block_quantize(a, b, n, outer, nblocks, inner, wl, rounding, flags, 0, 0, ws, ws_bytes, None)
+
+    assert call(0, 1, 1, 1) == 0
+    assert call(6, 1, 1, 6, wl=1) == 2 and call(6, 1, 1, 6, wl=25) == 2
+    assert call(6, 1, 1, 6, rounding=9) == 3
+    assert call(6, 1, 1, 5) == 4 and call(6, 2, 3, 2) == 4 and call(6, 1, 0, 6) == 4 and call(6, 1, 3, 3) == 4
+    assert call(6, 1, 1, 6, a=None) == 1
+    assert call(64, 1, 1, 64, b=FAKE + 16) == 5
+    # a block spread over several workgroups needs the scratch the size query asks for
+    n = 1 << 24
+    need = B.block_workspace_bytes(n, 1, 1, n)
+    assert need > 0 and need % 4 == 0
+    assert call(n, 1, 1, n) == 6
+    assert call(n, 1, 1, n, ws=FAKE + (1 << 30), ws_bytes=need - 4) == 6
+    assert call(n, 1, 1, n, ws=FAKE + (1 << 30) + 4, ws_bytes=need) == 6            # misaligned
+    assert B.block_workspace_bytes(4096 * 4096, 1, 4096, 4096) == 0                 # one workgroup per row
+    assert B.block_workspace_bytes(0, 1, 1, 1) == 0
+    assert B.block_workspace_bytes(7, 2, 2, 2) == 0                                 # invalid shape: nothing to do
+
+
+def test_sgd_validation_without_gpu():
+    L = B.lib()
+    ident = B.Format(0, 0, 0, 0, 0)
+
+    def call(fg=ident, fm=ident, fw=ident, n=64, w=FAKE, q=FAKE + (1 << 20), g=FAKE + (2 << 20), m=FAKE + (3 << 20)):
+        return L.qsim_quant_sgd_step(w, q, g, m, n, 0.1, 0.9, ctypes.byref(fg), ctypes.byref(fm), ctypes.byref(fw),
+                                     0, 0, None)
+
+    assert call(n=0) == 0
+    for bad in [B.Format(4, 0, 0, 0, 0), B.Format(1, 9, 2, 0, 0), B.Format(2, 30, 2, 0, 0), B.Format(3, 8, 100, 0, 0),
+                B.Format(3, 8, 2048, 0, 0), B.Format(3, 8, 2, 0, 0), B.Format(3, 1, 64, 0, 0), B.Format(2, 8, 6, 0, 16)]:
+        assert call(fg=bad) == 2 and call(fm=bad) == 2 and call(fw=bad) == 2
+    assert call(fm=B.Format(2, 8, 6, 7, 0)) == 3
+    assert call(w=None) == 1 and call(g=None) == 1 and call(m=None) == 1
+    assert call(g=FAKE) == 5 and call(m=FAKE + 8) == 5 and call(q=FAKE + (3 << 20)) == 5
+    assert L.qsim_quant_sgd_step(FAKE, None, FAKE + 4096, FAKE + 8192, 64, 0.1, 0.9, None, ctypes.byref(ident),
+                                 ctypes.byref(ident), 0, 0, None) == 1
