@@ -100,6 +100,11 @@ def main() -> int:
         Q.fixed_quantize(ins[k % NSETS], 8, 6, Q.STOCHASTIC, Q.SATURATE, seed=1234, stream_id=k, out=outs[k % NSETS])
 
     wall, ev = _time_launches(fixed_step, args.steps, args.warmup, torch)
+    # a plain device-to-device copy of the same tensor: the known-size reference that scales the
+    # profiler's HBM byte counters (it is outside every timed region)
+    for k in range(NSETS):
+        outs[k].copy_(ins[k])
+    torch.cuda.synchronize()
     value = n * args.steps / wall
     achieved = n * BYTES_PER_ELEMENT / (ev / args.steps) / 1e9
     result = {

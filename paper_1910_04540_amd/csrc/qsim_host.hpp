@@ -28,6 +28,13 @@ inline bool partial_overlap(const void* a, const void* b, uint64_t n)
 }
 inline bool any_overlap(const void* a, const void* b, uint64_t n) { return a == b || partial_overlap(a, b, n); }
 
+// Byte ranges [a, a + bytes_a) and [b, b + bytes_b) share at least one byte.
+inline bool ranges_overlap(const void* a, uint64_t bytes_a, const void* b, uint64_t bytes_b)
+{
+    const uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+    return pa < pb + bytes_b && pb < pa + bytes_a;
+}
+
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 inline uint32_t float_bits(float f)
@@ -37,19 +44,27 @@ inline uint32_t float_bits(float f)
     return u;
 }
 
+inline float bits_float(uint32_t u)
+{
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
 inline GridPlan fixed_plan(int wl, int fl, uint32_t flags)
 {
     GridPlan p;
     p.q = -fl;
     const double kmax = ldexp(1.0, wl - 1) - 1.0;
     const double kneg = (flags & QSIM_SYMMETRIC) ? kmax : ldexp(1.0, wl - 1);
-    p.pos_lim = float_bits((float)ldexp(kmax, p.q));   // exact: at most 23 significant bits
-    p.neg_lim = float_bits((float)ldexp(kneg, p.q));
-    p.saturate = (flags & QSIM_SATURATE) ? 1 : 0;
+    p.hi = (float)ldexp(kmax, p.q);                   // exact: at most 23 significant bits
+    p.lo = -(float)ldexp(kneg, p.q);
+    p.thr = (p.q + 24 <= 127) ? (float)ldexp(1.0, p.q + 24) : INFINITY;
+    p.keep_class = kClassNaN;
     return p;
 }
 
-inline FloatPlan float_plan(int exp_bits, int man_bits, uint32_t flags)
+inline FloatPlan float_plan(int exp_bits, int man_bits)
 {
     FloatPlan p;
     const int bias = (1 << (exp_bits - 1)) - 1;
@@ -57,11 +72,23 @@ inline FloatPlan float_plan(int exp_bits, int man_bits, uint32_t flags)
     p.drop = 23 - man_bits;
     p.man_bits = man_bits;
     p.emin_field = emin + 127;
-    p.max_enc = float_bits((float)ldexp(2.0 - ldexp(1.0, -man_bits), bias));
+    p.maxval = (float)ldexp(2.0 - ldexp(1.0, -man_bits), bias);
+    p.max_enc = float_bits(p.maxval);
     p.min_normal = (uint32_t)p.emin_field << 23;
-    p.saturate = (flags & QSIM_SATURATE) ? 1 : 0;
-    p.subnormal = (flags & QSIM_SUBNORMAL) ? 1 : 0;
     return p;
+}
+
+// Which device form carries a float format out, and how it treats results below 2^emin.
+inline void float_strategy(int exp_bits, uint32_t flags, int* form, int* ftz)
+{
+    const bool subnormal = (flags & QSIM_SUBNORMAL) != 0;
+    if (subnormal && exp_bits < 8) {
+        *form = kFloatGeneral;
+        *ftz = 0;
+    } else {
+        *form = kFloatShift;
+        *ftz = subnormal ? 0 : (exp_bits == 8 ? 2 : 1);
+    }
 }
 
 // n must fit the [outer, nblocks, inner] view; only outer == 1 may leave the last block short.
@@ -74,17 +101,7 @@ inline bool valid_block_shape(uint64_t n, uint64_t outer, uint64_t nblocks, uint
     return n == (uint64_t)total;
 }
 
-// Format of one number category in the SGD step, resolved for the device.
-struct FormatPlan {
-    int kind;           // qsim_format::kind
-    int mode;           // rounding
-    int wl;             // block: word length
-    int symmetric;      // block: symmetric clamp
-    int lanes;          // block: lanes (groups of 4 elements) per chunk = L / 4
-    GridPlan grid;      // fixed
-    FloatPlan flt;      // float
-};
-
+// Resolves the format of one number category of the SGD step for the device.
 inline int make_format_plan(const qsim_format* f, FormatPlan* out)
 {
     if (!f) return QSIM_ERR_NULL;
@@ -98,11 +115,14 @@ inline int make_format_plan(const qsim_format* f, FormatPlan* out)
     case 0: break;
     case 1:
         if (!valid_float(f->a, f->b)) return QSIM_ERR_FORMAT;
-        p.flt = float_plan(f->a, f->b, f->flags);
+        p.flt = float_plan(f->a, f->b);
+        p.saturate = (f->flags & QSIM_SATURATE) ? 1 : 0;
+        float_strategy(f->a, f->flags, &p.float_form, &p.ftz);
         break;
     case 2:
         if (!valid_fixed(f->a, f->b)) return QSIM_ERR_FORMAT;
         p.grid = fixed_plan(f->a, f->b, f->flags);
+        p.saturate = (f->flags & QSIM_SATURATE) ? 1 : 0;
         break;
     case 3:
         if (!valid_block_wl(f->a) || f->b < 4 || f->b > 1024 || (f->b & (f->b - 1)) != 0) return QSIM_ERR_FORMAT;

@@ -1,0 +1,432 @@
+// Kernels of libqsim.  Hand-written HIP for gfx950 (MI355X).
+//
+// All kernels are streaming: a thread's unit of work is one group of four consecutive elements
+// whose first index is a multiple of four, i.e. one dwordx4 load, one Philox4x32-10 block (its
+// four words belong to exactly these four elements) and one dwordx4 store.  Loads and stores are
+// non-temporal: every byte is touched once.  Arrays that are not 16-byte aligned take the dword
+// path of the run-time-format kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "qsim_device.hpp"
+
+namespace qsim {
+
+constexpr int kThreads = 256;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint4 to_uint4(const u32x4& v) { return make_uint4(v.x, v.y, v.z, v.w); }
+__device__ __forceinline__ u32x4 to_u32x4(const uint4& v) { return u32x4{v.x, v.y, v.z, v.w}; }
+
+// ---------------------------------------------------------------------------------------------
+// Group access: elements [4*j, 4*j+4) of an array whose valid elements end at `end`.
+// VEC: the array is 16-byte aligned, so a whole group is one dwordx4 access.
+// ---------------------------------------------------------------------------------------------
+template <bool VEC>
+__device__ __forceinline__ uint4 load_group(const uint32_t* p, uint64_t j, uint64_t end)
+{
+    const uint64_t i = j * 4;
+    if (VEC && i + 4 <= end) return to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + i)));
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (i + 0 < end) v.x = p[i + 0];
+    if (i + 1 < end) v.y = p[i + 1];
+    if (i + 2 < end) v.z = p[i + 2];
+    if (i + 3 < end) v.w = p[i + 3];
+    return v;
+}
+
+template <bool VEC>
+__device__ __forceinline__ void store_group(uint32_t* p, uint64_t j, uint64_t end, const uint4& v)
+{
+    const uint64_t i = j * 4;
+    if (VEC && i + 4 <= end) {
+        __builtin_nontemporal_store(to_u32x4(v), reinterpret_cast<u32x4*>(p + i));
+        return;
+    }
+    if (i + 0 < end) p[i + 0] = v.x;
+    if (i + 1 < end) p[i + 1] = v.y;
+    if (i + 2 < end) p[i + 2] = v.z;
+    if (i + 3 < end) p[i + 3] = v.w;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Elementwise quantizers with the format resolved at compile time (aligned arrays).
+// ---------------------------------------------------------------------------------------------
+template <bool SAT>
+struct FixedOp {
+    GridPlan plan;
+    template <int MODE>
+    __device__ __forceinline__ uint32_t apply(uint32_t bits, uint32_t r) const
+    {
+        return quantize_to_grid<MODE, SAT>(bits, plan, r);
+    }
+};
+
+template <bool SAT, int FTZ>
+struct FloatShiftOp {
+    FloatPlan plan;
+    template <int MODE>
+    __device__ __forceinline__ uint32_t apply(uint32_t bits, uint32_t r) const
+    {
+        return quantize_float_shift<MODE, SAT, FTZ>(bits, plan, r);
+    }
+};
+
+template <bool SAT>
+struct FloatGeneralOp {
+    FloatPlan plan;
+    template <int MODE>
+    __device__ __forceinline__ uint32_t apply(uint32_t bits, uint32_t r) const
+    {
+        return quantize_float_general<MODE, SAT>(bits, plan, r);
+    }
+};
+
+template <class Op, int MODE, int UNROLL>
+__global__ __launch_bounds__(kThreads) void elementwise_kernel(const uint32_t* in, uint32_t* out, uint64_t n,
+                                                               uint64_t groups, Op op, RngKey key)
+{
+    const uint64_t base = (uint64_t)blockIdx.x * (kThreads * UNROLL) + threadIdx.x;
+    uint4 v[UNROLL];
+#pragma unroll
+    for (int k = 0; k < UNROLL; ++k) {
+        const uint64_t j = base + (uint64_t)k * kThreads;
+        if (j < groups) v[k] = load_group<true>(in, j, n);
+    }
+#pragma unroll
+    for (int k = 0; k < UNROLL; ++k) {
+        const uint64_t j = base + (uint64_t)k * kThreads;
+        if (j < groups) {
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+            uint4 o;
+            o.x = op.template apply<MODE>(v[k].x, r.w[0]);
+            o.y = op.template apply<MODE>(v[k].y, r.w[1]);
+            o.z = op.template apply<MODE>(v[k].z, r.w[2]);
+            o.w = op.template apply<MODE>(v[k].w, r.w[3]);
+            store_group<true>(out, j, n, o);
+        }
+    }
+}
+
+// Float or fixed format chosen at run time, dword accesses: the path for unaligned arrays.
+__global__ __launch_bounds__(kThreads) void elementwise_rt_kernel(const uint32_t* in, uint32_t* out, uint64_t n,
+                                                                  uint64_t groups, FormatPlan f, RngKey key)
+{
+    const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (j >= groups) return;
+    const uint4 v = load_group<false>(in, j, n);
+    Words4 r = {{0u, 0u, 0u, 0u}};
+    if (f.mode == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+    store_group<false>(out, j, n, quantize_group_rt(f, f.grid, f.saturate, v, r));
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block floating point.
+// ---------------------------------------------------------------------------------------------
+
+// Workgroup-wide maximum: wave reduction, then one LDS slot per wave.
+__device__ __forceinline__ uint32_t workgroup_max(uint32_t v, uint32_t* lds /* kThreads / 64 slots */)
+{
+    const uint32_t w = wave_max(v);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();                        // protects the slots against the previous use
+    if ((threadIdx.x & 63) == 0) lds[wave] = w;
+    __syncthreads();
+    uint32_t m = lds[0];
+#pragma unroll
+    for (int k = 1; k < kThreads / 64; ++k) m = m > lds[k] ? m : lds[k];
+    return m;
+}
+
+template <int MODE>
+__device__ __forceinline__ uint4 quantize_group_to_grid(const uint4& v, const GridPlan& p, const Words4& r)
+{
+    uint4 o;
+    o.x = quantize_to_grid<MODE, true>(v.x, p, r.w[0]);
+    o.y = quantize_to_grid<MODE, true>(v.y, p, r.w[1]);
+    o.z = quantize_to_grid<MODE, true>(v.z, p, r.w[2]);
+    o.w = quantize_to_grid<MODE, true>(v.w, p, r.w[3]);
+    return o;
+}
+
+// Geometry of the [outer, nblocks, inner] view.  A block's elements are numbered t = o * inner + i;
+// element t of block b sits at flat index (o * nblocks + b) * inner + i.
+struct BlockGeom {
+    uint64_t n, outer, nblocks, inner;
+};
+
+// Contiguous blocks (outer == 1, inner % 4 == 0, aligned arrays) held in registers: a team of
+// `team` lanes (a power of two, 1..64, or the whole workgroup when team == 256) owns one block and
+// every lane keeps GPT groups of it, so the block is read from memory exactly once.
+// Requires ceil(inner / 4) <= team * GPT.
+template <int MODE, int GPT, bool WHOLE_WORKGROUP>
+__global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* in, uint32_t* out, BlockGeom g,
+                                                                int team_log2, int wl, int symmetric, RngKey key)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    const int team = 1 << team_log2;
+    const int teams_per_wg = WHOLE_WORKGROUP ? 1 : (kThreads >> team_log2);
+    const int lane = WHOLE_WORKGROUP ? (int)threadIdx.x : ((int)threadIdx.x & (team - 1));
+    const uint64_t b = (uint64_t)blockIdx.x * teams_per_wg + (WHOLE_WORKGROUP ? 0 : ((int)threadIdx.x >> team_log2));
+    // a team past the last block keeps all its lanes running with nothing to load or store, so the
+    // cross-lane operations below always see a full wavefront
+    const uint64_t start = b < g.nblocks ? b * g.inner : g.n;
+    const uint64_t len = (g.n - start < g.inner) ? g.n - start : g.inner;
+    const uint64_t end = start + len;
+    const uint64_t j0 = start / 4;
+    const int groups = (int)((len + 3) / 4);
+    const int stride = WHOLE_WORKGROUP ? kThreads : team;
+
+    uint4 v[GPT];
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const int t = lane + k * stride;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (t < groups) v[k] = load_group<true>(in, j0 + t, end);
+        const uint32_t gm = max4_mag(v[k]);
+        m = m > gm ? m : gm;
+    }
+    m = WHOLE_WORKGROUP ? workgroup_max(m, lds) : group_max(m, team);
+    const GridPlan p = block_plan(m, wl, symmetric);
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const int t = lane + k * stride;
+        if (t < groups) {
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (MODE == QSIM_STOCHASTIC) r = random_words(j0 + t, key, 0u);
+            store_group<true>(out, j0 + t, end, quantize_group_to_grid<MODE>(v[k], p, r));
+        }
+    }
+}
+
+// One contiguous block per workgroup (outer == 1), any length and alignment: the block is read
+// twice by the same workgroup, the second time out of cache.
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(kThreads) void block_rows_kernel(const uint32_t* in, uint32_t* out, BlockGeom g, int wl,
+                                                              int symmetric, RngKey key)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    const uint64_t b = blockIdx.x;
+    const uint64_t start = b * g.inner;
+    const uint64_t len = (g.n - start < g.inner) ? g.n - start : g.inner;
+    uint32_t m = 0;
+    if (VEC) {
+        // start is a multiple of four, so groups are those of the whole array
+        const uint64_t j0 = start / 4, groups = (len + 3) / 4;
+        for (uint64_t t = threadIdx.x; t < groups; t += kThreads) {
+            const uint64_t i = (j0 + t) * 4;
+            uint4 v = {0u, 0u, 0u, 0u};
+            if (i + 4 <= start + len) v = *reinterpret_cast<const uint4*>(in + i);     // cached on purpose
+            else v = load_group<false>(in, j0 + t, start + len);
+            const uint32_t gm = max4_mag(v);
+            m = m > gm ? m : gm;
+        }
+        const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
+        for (uint64_t t = threadIdx.x; t < groups; t += kThreads) {
+            const uint64_t j = j0 + t;
+            const uint4 v = load_group<true>(in, j, start + len);
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+            store_group<true>(out, j, start + len, quantize_group_to_grid<MODE>(v, p, r));
+        }
+    } else {
+        for (uint64_t t = threadIdx.x; t < len; t += kThreads) {
+            const uint32_t a = in[start + t] & 0x7fffffffu;
+            m = m > a ? m : a;
+        }
+        const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
+        for (uint64_t t = threadIdx.x; t < len; t += kThreads) {
+            const uint64_t i = start + t;
+            uint32_t r = 0;
+            if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
+            out[i] = quantize_to_grid<MODE, true>(in[i], p, r);
+        }
+    }
+}
+
+// Blocks spread over several workgroups, any layout.  Pass 1: workgroup (b, s) reduces slice s of
+// block b and writes one partial maximum to partial[b * slices + s] (no atomics, so the scratch
+// needs no initialisation).  Pass 2: every workgroup folds the partials of its block, then
+// quantizes its slice.  A slice is a range of t = o * inner + i.
+// VEC: inner % 4 == 0 and aligned arrays, so four consecutive t are four consecutive addresses.
+struct SliceGeom {
+    BlockGeom g;
+    uint64_t block_len;    // outer * inner (for outer == 1 the last block may be shorter)
+    uint64_t slice_len;    // elements of t per workgroup, a multiple of 1024
+    uint32_t slices;       // workgroups per block
+};
+
+__device__ __forceinline__ uint64_t flat_index(const BlockGeom& g, uint64_t b, uint64_t t)
+{
+    if (g.outer == 1) return b * g.inner + t;
+    const uint64_t o = t / g.inner, i = t - o * g.inner;
+    return (o * g.nblocks + b) * g.inner + i;
+}
+
+__device__ __forceinline__ uint64_t block_length(const SliceGeom& sg, uint64_t b)
+{
+    if (sg.g.outer != 1) return sg.block_len;
+    const uint64_t start = b * sg.g.inner;
+    return (sg.g.n - start < sg.g.inner) ? sg.g.n - start : sg.g.inner;
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void block_partial_max_kernel(const uint32_t* in, uint32_t* partial, SliceGeom sg)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    const uint64_t b = blockIdx.x;
+    const uint64_t len = block_length(sg, b);
+    const uint64_t t0 = (uint64_t)blockIdx.y * sg.slice_len;
+    const uint64_t t1 = (t0 + sg.slice_len < len) ? t0 + sg.slice_len : len;
+    uint32_t m = 0;
+    if (VEC) {
+        for (uint64_t t = t0 + 4ull * threadIdx.x; t < t1; t += 4ull * kThreads) {
+            const uint64_t i = flat_index(sg.g, b, t);
+            uint4 v;
+            if (i + 4 <= sg.g.n) v = *reinterpret_cast<const uint4*>(in + i);         // cached: read again in pass 2
+            else v = load_group<false>(in, i / 4, sg.g.n);
+            const uint32_t gm = max4_mag(v);
+            m = m > gm ? m : gm;
+        }
+    } else {
+        for (uint64_t t = t0 + threadIdx.x; t < t1; t += kThreads) {
+            const uint32_t a = in[flat_index(sg.g, b, t)] & 0x7fffffffu;
+            m = m > a ? m : a;
+        }
+    }
+    m = workgroup_max(m, lds);
+    if (threadIdx.x == 0) partial[b * sg.slices + blockIdx.y] = m;
+}
+
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* in, uint32_t* out, const uint32_t* partial,
+                                                               SliceGeom sg, int wl, int symmetric, RngKey key)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    const uint64_t b = blockIdx.x;
+    uint32_t m = 0;
+    for (uint32_t s = threadIdx.x; s < sg.slices; s += kThreads) {
+        const uint32_t a = partial[b * sg.slices + s];
+        m = m > a ? m : a;
+    }
+    const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
+    const uint64_t len = block_length(sg, b);
+    const uint64_t t0 = (uint64_t)blockIdx.y * sg.slice_len;
+    const uint64_t t1 = (t0 + sg.slice_len < len) ? t0 + sg.slice_len : len;
+    if (VEC) {
+        for (uint64_t t = t0 + 4ull * threadIdx.x; t < t1; t += 4ull * kThreads) {
+            const uint64_t j = flat_index(sg.g, b, t) / 4;
+            const uint4 v = load_group<true>(in, j, sg.g.n);
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+            store_group<true>(out, j, sg.g.n, quantize_group_to_grid<MODE>(v, p, r));
+        }
+    } else {
+        for (uint64_t t = t0 + threadIdx.x; t < t1; t += kThreads) {
+            const uint64_t i = flat_index(sg.g, b, t);
+            uint32_t r = 0;
+            if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
+            out[i] = quantize_to_grid<MODE, true>(in[i], p, r);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fused quantized SGD step.  A workgroup walks tiles of 1024 elements (one group per thread), so a
+// chunk of L <= 1024 elements never leaves the workgroup: its maximum is a reduction over L/4
+// neighbouring lanes (inside a wave up to L = 256, through LDS above).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t chunk_max(uint32_t v, int lanes, uint32_t* lds)
+{
+    if (lanes <= 64) return group_max(v, lanes);
+    // lanes is 128 or 256: whole waves
+    const uint32_t w = wave_max(v);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) lds[wave] = w;
+    __syncthreads();
+    if (lanes == 128) {
+        const uint32_t a = lds[wave & ~1], b = lds[wave | 1];
+        return a > b ? a : b;
+    }
+    uint32_t m = lds[0];
+#pragma unroll
+    for (int k = 1; k < kThreads / 64; ++k) m = m > lds[k] ? m : lds[k];
+    return m;
+}
+
+// Quantize one group with a run-time format.  Called by every thread of the workgroup (a block
+// kind synchronises inside); groups past the end of the array carry zeros.
+__device__ __forceinline__ uint4 apply_format(const FormatPlan& f, const uint4& v, uint64_t j, const RngKey& key,
+                                              uint32_t role, uint32_t* lds)
+{
+    if (f.kind == 0) return v;
+    Words4 r = {{0u, 0u, 0u, 0u}};
+    if (f.mode == QSIM_STOCHASTIC) r = random_words(j, key, role);
+    if (f.kind == 3) {
+        const GridPlan p = block_plan(chunk_max(max4_mag(v), f.lanes, lds), f.wl, f.symmetric);
+        return quantize_group_rt(f, p, 1, v, r);
+    }
+    return quantize_group_rt(f, f.grid, f.saturate, v, r);
+}
+
+__device__ __forceinline__ uint32_t fma_bits(float a, uint32_t b, uint32_t c)
+{
+    return __float_as_uint(__builtin_fmaf(a, __uint_as_float(b), __uint_as_float(c)));
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void sgd_step_kernel(uint32_t* w_master, uint32_t* w_q, const uint32_t* grad,
+                                                            uint32_t* mom, uint64_t n, uint64_t tiles, float lr,
+                                                            float momentum, FormatPlan fg, FormatPlan fm, FormatPlan fw,
+                                                            RngKey key)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    // every thread of a workgroup runs the same number of tiles, so the barriers inside
+    // apply_format are reached by all of them; groups past the end load zeros and store nothing
+    for (uint64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+        const uint64_t j = tile * kThreads + threadIdx.x;
+        const uint4 g = load_group<VEC>(grad, j, n);
+        const uint4 v = load_group<VEC>(mom, j, n);
+        const uint4 w = load_group<VEC>(w_master, j, n);
+
+        const uint4 gq = apply_format(fg, g, j, key, 0u, lds);
+        uint4 t;
+        t.x = fma_bits(momentum, v.x, gq.x);
+        t.y = fma_bits(momentum, v.y, gq.y);
+        t.z = fma_bits(momentum, v.z, gq.z);
+        t.w = fma_bits(momentum, v.w, gq.w);
+        // elements past the end must not disturb a chunk maximum: they are forced to zero
+        const uint64_t i = j * 4;
+        if (i + 4 > n) {
+            if (i + 0 >= n) t.x = 0u;
+            if (i + 1 >= n) t.y = 0u;
+            if (i + 2 >= n) t.z = 0u;
+            if (i + 3 >= n) t.w = 0u;
+        }
+        const uint4 vq = apply_format(fm, t, j, key, 1u, lds);
+        uint4 wn;
+        wn.x = fma_bits(-lr, vq.x, w.x);
+        wn.y = fma_bits(-lr, vq.y, w.y);
+        wn.z = fma_bits(-lr, vq.z, w.z);
+        wn.w = fma_bits(-lr, vq.w, w.w);
+        if (i + 4 > n) {
+            if (i + 0 >= n) wn.x = 0u;
+            if (i + 1 >= n) wn.y = 0u;
+            if (i + 2 >= n) wn.z = 0u;
+            if (i + 3 >= n) wn.w = 0u;
+        }
+        store_group<VEC>(mom, j, n, vq);
+        store_group<VEC>(w_master, j, n, wn);
+        if (w_q) {
+            const uint4 wq = apply_format(fw, wn, j, key, 2u, lds);
+            store_group<VEC>(w_q, j, n, wq);
+        }
+    }
+}
+
+}  // namespace qsim

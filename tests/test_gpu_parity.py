@@ -210,6 +210,25 @@ def test_block_misaligned_and_inplace():
         assert_bit_equal(np.concatenate([full[:off], full[off + n:]]), np.concatenate([x[:off], x[off + n:]]), "outside")
 
 
+def test_block_workspace_next_to_the_arrays():
+    """Scratch that touches the arrays without overlapping them is accepted; overlapping scratch is not."""
+    n = 1 << 18
+    need = Q.block_workspace_bytes(n, 1, 1, n)
+    assert need > 0
+    x = W.row_scaled_matrix(1, n, seed=4).reshape(-1)
+    pad = (need + 3) // 4
+    buf = torch.zeros(2 * n + 2 * pad, device="cuda")
+    buf[pad:pad + n] = dev(x)
+    inp, out = buf[pad:pad + n], buf[pad + n:pad + 2 * n]
+    want = R.block_quantize(x, 1, 1, n, 8, STOCHASTIC, 0, 3, 4)
+    for ws in (buf[:pad], buf[pad + 2 * n:]):
+        got = Q.block_quantize(inp, 1, 1, n, 8, STOCHASTIC, 0, 3, 4, out=out, workspace=ws.view(torch.uint8))
+        assert_bit_equal(host(got), want, "scratch adjacent to the arrays")
+    with pytest.raises(Q.QsimError) as e:
+        Q.block_quantize(inp, 1, 1, n, 8, STOCHASTIC, 0, 3, 4, out=out, workspace=buf[pad + n - 4:].view(torch.uint8))
+    assert e.value.status == 5
+
+
 def test_block_with_nonfinite_elements():
     x = W.row_scaled_matrix(4, 2048, seed=2)
     x[1, 3] = np.nan
