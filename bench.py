@@ -27,10 +27,10 @@ BYTES_PER_ELEMENT = 8          # one fp32 read + one fp32 write
 SGD_BYTES_PER_PARAM = 24       # three reads + three writes
 NSETS = 3
 
-# HBM traffic per launch of the headline kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-# WRITE_SIZE, scaled by a copy kernel of known size); None until such a run is recorded under
-# profiles/.
-MEASURED_TRAFFIC_BYTES = None
+# HBM traffic per launch of the headline kernel measured with rocprofv3 --pmc (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the same counter reads for the device-to-device copy below);
+# the runs are summarised in profiles/fixed_sr_64Mi_hbm_counters.txt.
+MEASURED_TRAFFIC_BYTES = 536968146
 
 
 def _time_launches(fn, steps, warmup, torch):

@@ -127,10 +127,17 @@ def test_float_every_exponent_and_dropped_bit_class(e, m, flags, rounding):
     assert_bit_equal(got, want, f"float({e},{m}) flags {flags} mode {rounding}")
 
 
-@pytest.mark.skipif(os.environ.get("QSIM_EXHAUSTIVE") != "1", reason="all 2^32 inputs: set QSIM_EXHAUSTIVE=1")
-@pytest.mark.parametrize("kind,a,b,rounding,flags", [("float", 5, 10, RN_EVEN, 3), ("float", 8, 7, STOCHASTIC, 3),
-                                                     ("float", 5, 2, RN_EVEN, 1), ("fixed", 8, 6, STOCHASTIC, 1)])
+@pytest.mark.parametrize("kind,a,b,rounding,flags", [
+    ("float", 5, 10, RN_EVEN, 3),        # per-element grid, nearest
+    ("float", 5, 2, STOCHASTIC, 3),      # per-element grid, stochastic
+    ("float", 8, 7, STOCHASTIC, 3),      # constant mask, stochastic
+    ("float", 5, 2, RN_EVEN, 1),         # constant mask, flush to zero
+    ("float", 8, 7, RN_AWAY, 0),         # constant mask, flush with the fp32-denormal side path, no saturation
+    ("fixed", 8, 6, STOCHASTIC, 1),      # fixed grid, saturating
+    ("fixed", 12, 20, RN_ZERO, 0),       # fixed grid, open range
+])
 def test_exhaustive_all_fp32_encodings(kind, a, b, rounding, flags):
+    """All 2^32 fp32 encodings (NaN and Inf included) through one format, against the oracle."""
     chunk = 1 << 26
     for start in range(0, 1 << 32, chunk):
         x = np.arange(start, start + chunk, dtype=np.uint64).astype(np.uint32).view(np.float32)
