@@ -3,6 +3,8 @@
 // stream.  Nothing here allocates or synchronises.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "qsim.h"
 #include "qsim_device.hpp"
 #include "qsim_host.hpp"
@@ -16,7 +18,7 @@ static const uint32_t* u32(const float* p) { return reinterpret_cast<const uint3
 static uint32_t* u32(float* p) { return reinterpret_cast<uint32_t*>(p); }
 
 // Groups per thread of the elementwise kernels.
-constexpr int kUnroll = 2;
+constexpr int kUnroll = 1;
 
 // ---- elementwise ---------------------------------------------------------------------------
 template <class Op, int MODE>
@@ -73,10 +75,10 @@ struct BlockSchedule {
 };
 
 constexpr uint64_t kCachedMaxInner = 16384;      // 256 threads x 16 groups x 4 elements
-constexpr uint64_t kRowsMaxInner = 1ull << 16;   // a block up to 256 KiB is re-read out of cache
-constexpr uint64_t kRowsMinBlocks = 512;         // enough workgroups to fill the chip
 constexpr uint32_t kMaxSlices = 1024;
-constexpr uint64_t kMinSliceLen = 8192;
+constexpr uint64_t kMinSliceLen = 16384;
+constexpr uint64_t kTileLen = 4ull * kTileGroups;
+constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
 
 static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner)
 {
@@ -84,17 +86,81 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
     memset(&s, 0, sizeof(s));
     s.sg.g = BlockGeom{n, outer, nblocks, inner};
     s.sg.block_len = outer * inner;
-    s.one_launch = outer == 1 && (inner <= kCachedMaxInner || (inner <= kRowsMaxInner && nblocks >= kRowsMinBlocks));
+    s.one_launch = outer == 1 && inner <= kCachedMaxInner;
     if (s.one_launch) return s;
     uint64_t slices = (s.sg.block_len + kMinSliceLen - 1) / kMinSliceLen;
     if (slices > kMaxSlices) slices = kMaxSlices;
     uint64_t slice_len = (s.sg.block_len + slices - 1) / slices;
-    slice_len = (slice_len + 1023) / 1024 * 1024;
+    slice_len = (slice_len + kTileLen - 1) / kTileLen * kTileLen;
     slices = (s.sg.block_len + slice_len - 1) / slice_len;
     s.sg.slice_len = slice_len;
     s.sg.slices = (uint32_t)slices;
     s.workspace = (size_t)(nblocks * slices * sizeof(uint32_t));
+    // the single-pass form keeps its counter and one slot per workgroup in the same scratch
+    const size_t resident = (size_t)(kSyncSlots0 + kMaxResidentWgs) * sizeof(uint32_t);
+    if (outer == 1 && s.workspace < resident) s.workspace = resident;
     return s;
+}
+
+// ---- single pass over resident workgroups ----------------------------------------------------
+static std::atomic<uint32_t> g_spin_limit{1u << 20};
+
+// Workgroups of block_resident_kernel<MODE, GPT> that fit on the current device at once.
+template <int MODE, int GPT>
+static uint32_t resident_capacity()
+{
+    static std::atomic<int> cache[64];          // per device; 0 = not asked yet, -1 = unknown
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    int c = cache[dev].load(std::memory_order_relaxed);
+    if (c == 0) {
+        int per_cu = 0, cus = 0;
+        const bool ok =
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)block_resident_kernel<MODE, GPT>, kThreads,
+                                                         0) == hipSuccess &&
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess;
+        c = ok && per_cu > 0 && cus > 0 ? per_cu * cus : -1;
+        if (!ok) (void)hipGetLastError();
+        cache[dev].store(c, std::memory_order_relaxed);
+    }
+    return c > 0 ? (uint32_t)c : 0u;
+}
+
+// Tries the single-pass form with GPT groups per thread; false = does not fit (nothing launched).
+// The launch is an ordinary one: the grid is no larger than what the device holds at once, and a
+// workgroup that waits in vain (the device is shared with other work) falls back to an exact slow
+// path, so residency is a matter of speed, not of correctness or termination.
+template <int MODE, int GPT>
+static bool try_resident(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
+                         uint32_t* sync, hipStream_t stream)
+{
+    const uint64_t slice_len = 4ull * kThreads * GPT;
+    const uint64_t slices = (g.inner + slice_len - 1) / slice_len;
+    const uint64_t total = slices * g.nblocks;
+    if (total > kMaxResidentWgs || total > kSyncGroup * kSyncMaxGroups || total > resident_capacity<MODE, GPT>()) return false;
+    ResidentGeom rg;
+    rg.sg.g = g;
+    rg.sg.block_len = g.inner;
+    rg.sg.slice_len = slice_len;
+    rg.sg.slices = (uint32_t)slices;
+    rg.total_wgs = (uint32_t)total;
+    rg.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
+    const uint32_t words = kSyncSlots0 + (uint32_t)total;
+    hipLaunchKernelGGL(block_sync_clear_kernel, dim3((words + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, sync, words);
+    hipLaunchKernelGGL((block_resident_kernel<MODE, GPT>), dim3((unsigned)total), dim3(kThreads), 0, stream, in, out, sync, rg,
+                       wl, symmetric, key);
+    return true;
+}
+
+template <int MODE>
+static bool try_resident_any(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
+                             uint32_t* sync, hipStream_t stream)
+{
+    // fewest groups per thread that still fit: more workgroups in flight hide more latency
+    return try_resident<MODE, 2>(in, out, g, wl, symmetric, key, sync, stream) ||
+           try_resident<MODE, 4>(in, out, g, wl, symmetric, key, sync, stream) ||
+           try_resident<MODE, 8>(in, out, g, wl, symmetric, key, sync, stream) ||
+           try_resident<MODE, 16>(in, out, g, wl, symmetric, key, sync, stream);
 }
 
 template <int MODE, int GPT, bool WHOLE>
@@ -131,9 +197,6 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
             else if (per_lane <= 4) launch_block_cached<MODE, 4, true>(pin, pout, g, 8, wl, symmetric, key, stream);
             else if (per_lane <= 8) launch_block_cached<MODE, 8, true>(pin, pout, g, 8, wl, symmetric, key, stream);
             else launch_block_cached<MODE, 16, true>(pin, pout, g, 8, wl, symmetric, key, stream);
-        } else if (vec) {
-            hipLaunchKernelGGL((block_rows_kernel<MODE, true>), dim3((unsigned)g.nblocks), dim3(kThreads), 0, stream, pin,
-                               pout, g, wl, symmetric, key);
         } else {
             hipLaunchKernelGGL((block_rows_kernel<MODE, false>), dim3((unsigned)g.nblocks), dim3(kThreads), 0, stream, pin,
                                pout, g, wl, symmetric, key);
@@ -142,7 +205,15 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
     }
     uint32_t* partial = reinterpret_cast<uint32_t*>(workspace);
     const dim3 grid((unsigned)g.nblocks, s.sg.slices);
-    if (vec) {
+    if (vec && g.outer == 1) {
+        // single pass when the blocks fit in the chip's registers, else the streaming two-pass form:
+        // blocks on grid.y (folded when there are more than 65535), slices on grid.x
+        if (try_resident_any<MODE>(pin, pout, g, wl, symmetric, key, partial, stream)) return launch_status();
+        const unsigned by = (unsigned)(g.nblocks < 65535 ? g.nblocks : 65535);
+        hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
+        hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
+                           partial, s.sg, wl, symmetric, key);
+    } else if (vec) {
         hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg, wl,
                            symmetric, key);
@@ -268,6 +339,8 @@ int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* m
                            u32(w_q), u32(grad), u32(mom), n, tiles, lr, momentum, fg, fm, fw, key);
     return launch_status();
 }
+
+void qsim_set_barrier_spin_limit(uint32_t polls) { g_spin_limit.store(polls, std::memory_order_relaxed); }
 
 const char* qsim_status_string(int status)
 {

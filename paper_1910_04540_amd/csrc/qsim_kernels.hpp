@@ -256,7 +256,7 @@ __global__ __launch_bounds__(kThreads) void block_rows_kernel(const uint32_t* in
 struct SliceGeom {
     BlockGeom g;
     uint64_t block_len;    // outer * inner (for outer == 1 the last block may be shorter)
-    uint64_t slice_len;    // elements of t per workgroup, a multiple of 1024
+    uint64_t slice_len;    // elements of t per workgroup, a multiple of 4096
     uint32_t slices;       // workgroups per block
 };
 
@@ -331,6 +331,272 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
             uint32_t r = 0;
             if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
             out[i] = quantize_to_grid<MODE, true>(in[i], p, r);
+        }
+    }
+}
+
+// Contiguous blocks spread over several workgroups (outer == 1, inner % 4 == 0, aligned arrays):
+// the streaming forms of the two passes.  Workgroup (s, b) owns slice s of block b in both passes
+// and walks it in steps of 4096 elements with four loads in flight per thread.  Pass 1 writes the
+// slice's maximum to partial[b * slices + s]; pass 2 folds the partials of its block once, then
+// quantizes its slice.
+constexpr int kTileGroups = 4 * kThreads;          // groups per workgroup step: 4096 elements
+
+struct SliceView {
+    uint64_t end;      // one past the last element of the block (flat index)
+    uint64_t j0;       // first group of the slice
+    uint64_t groups;   // groups in the slice
+};
+
+__device__ __forceinline__ SliceView slice_view(const SliceGeom& sg, uint64_t b, uint64_t s)
+{
+    const uint64_t start = b * sg.g.inner;
+    const uint64_t len = block_length(sg, b);
+    const uint64_t t0 = s * sg.slice_len;
+    const uint64_t t1 = (t0 + sg.slice_len < len) ? t0 + sg.slice_len : len;
+    SliceView v;
+    v.end = start + len;
+    v.j0 = (start + t0) / 4;
+    v.groups = t1 > t0 ? (t1 - t0 + 3) / 4 : 0;
+    return v;
+}
+
+// Largest magnitude encoding of a slice, read with plain (cached) loads.
+__device__ __forceinline__ uint32_t slice_max(const uint32_t* in, const SliceView& sv)
+{
+    uint32_t m = 0;
+    for (uint64_t base = threadIdx.x; base < sv.groups; base += kTileGroups) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint64_t t = base + (uint64_t)k * kThreads;
+            v[k] = make_uint4(0u, 0u, 0u, 0u);
+            if (t < sv.groups) {
+                const uint64_t i = (sv.j0 + t) * 4;
+                if (i + 4 <= sv.end) v[k] = *reinterpret_cast<const uint4*>(in + i);
+                else v[k] = load_group<false>(in, sv.j0 + t, sv.end);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t gm = max4_mag(v[k]);
+            m = m > gm ? m : gm;
+        }
+    }
+    return m;
+}
+
+__global__ __launch_bounds__(kThreads) void block_slice_max_kernel(const uint32_t* in, uint32_t* partial, SliceGeom sg)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    for (uint64_t b = blockIdx.y; b < sg.g.nblocks; b += gridDim.y) {
+        const uint32_t m = workgroup_max(slice_max(in, slice_view(sg, b, blockIdx.x)), lds);
+        if (threadIdx.x == 0) partial[b * sg.slices + blockIdx.x] = m;
+    }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void block_slice_apply_kernel(const uint32_t* in, uint32_t* out,
+                                                                     const uint32_t* partial, SliceGeom sg, int wl,
+                                                                     int symmetric, RngKey key)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    for (uint64_t b = blockIdx.y; b < sg.g.nblocks; b += gridDim.y) {
+        uint32_t m = 0;
+        for (uint32_t s = threadIdx.x; s < sg.slices; s += kThreads) {
+            const uint32_t a = partial[b * sg.slices + s];
+            m = m > a ? m : a;
+        }
+        const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
+        const SliceView sv = slice_view(sg, b, blockIdx.x);
+        for (uint64_t base = threadIdx.x; base < sv.groups; base += kTileGroups) {
+            uint4 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint64_t t = base + (uint64_t)k * kThreads;
+                if (t < sv.groups) v[k] = load_group<true>(in, sv.j0 + t, sv.end);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint64_t t = base + (uint64_t)k * kThreads;
+                if (t < sv.groups) {
+                    Words4 r = {{0u, 0u, 0u, 0u}};
+                    if (MODE == QSIM_STOCHASTIC) r = random_words(sv.j0 + t, key, 0u);
+                    store_group<true>(out, sv.j0 + t, sv.end, quantize_group_to_grid<MODE>(v[k], p, r));
+                }
+            }
+        }
+    }
+}
+
+// Single pass for contiguous blocks that fit in the register files of the whole chip (for instance
+// a 4096 x 4096 tensor quantized as one block).  Every workgroup is resident at the same time
+// (cooperative launch); it loads its slice of 256 * GPT groups into registers, publishes the
+// slice's maximum, waits until all workgroups have arrived, folds the maxima of its block and
+// quantizes out of registers: HBM sees each element once in and once out.
+//
+// Scratch layout (zeroed by block_sync_clear_kernel before the launch; every counter and flag has
+// a 64-byte line to itself):
+//   sync[0]                              arrivals of whole groups of 32 workgroups
+//   sync[16 * (1 + c)],   c < 32         "everyone has arrived" flag, 32 copies
+//   sync[16 * (33 + g)],  g < 128        arrivals inside group g = workgroup / 32
+//   sync[kSyncSlots0 + w]                slot of workgroup w: its maximum with the top bit set as a
+//                                        "published" mark (magnitude encodings have that bit clear)
+// Arrival is two-level and the wait polls one of 32 flag copies, so no address sees more than a
+// few dozen device-scope operations: a single counter polled by a thousand workgroups serialises
+// at its memory channel and costs far more than the kernel's whole memory traffic.
+//
+// The wait is bounded.  A workgroup whose wait runs out (never expected under a cooperative
+// launch) still produces the right result: for every slot of its block that is not yet published
+// it computes the slice's maximum from memory itself.  That is safe even in place, because a
+// workgroup writes its output only after its own wait, which starts after it has published; so if
+// the slot is still unpublished after the read, the read saw nothing but input.
+constexpr uint32_t kSyncFlagCopies = 32;
+constexpr uint32_t kSyncGroup = 32;                // workgroups per first-level counter
+constexpr uint32_t kSyncMaxGroups = 128;
+constexpr uint32_t kSyncSlots0 = 16 * (1 + kSyncFlagCopies + kSyncMaxGroups);
+constexpr uint32_t kPublished = 0x80000000u;
+
+__global__ void block_sync_clear_kernel(uint32_t* sync, uint32_t words)
+{
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < words) sync[i] = 0u;
+}
+
+struct ResidentGeom {
+    SliceGeom sg;            // slice_len = 1024 * GPT elements; slices = workgroups per block
+    uint32_t total_wgs;      // nblocks * slices
+    uint32_t spin_limit;     // polls before the fallback
+};
+
+// With 16 groups per thread the kernel must keep to 128 VGPRs (four waves per SIMD, four workgroups
+// per CU): that is what lets 1024 workgroups hold a 16 Mi-element tensor.
+template <int MODE, int GPT>
+__global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_kernel(const uint32_t* in, uint32_t* out, uint32_t* sync,
+                                                                  ResidentGeom rg, int wl, int symmetric, RngKey key)
+{
+    // Stochastic rounding: the random words of the first PRE groups are drawn while the loads are
+    // in flight and parked in LDS (36 KiB at most, so four workgroups still share a CU); after the
+    // wait only the remaining groups pay for Philox, and the arithmetic hides behind the stores.
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 9 ? GPT : 9) : 0;
+    __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
+    __shared__ uint32_t lds[kThreads / 64];
+    __shared__ uint32_t shared_word;
+    const uint32_t wg = blockIdx.x;
+    const uint32_t b = wg / rg.sg.slices, s = wg - b * rg.sg.slices;
+    const SliceView sv = slice_view(rg.sg, b, s);
+    uint32_t* slots = sync + kSyncSlots0;
+
+    // the slice is addressed from a wave-uniform base with small per-thread offsets, which keeps
+    // the address arithmetic out of the vector registers that hold the data
+    const uint32_t* sin = in + sv.j0 * 4;
+    uint32_t* sout = out + sv.j0 * 4;
+    const uint64_t slice_end = sv.end - sv.j0 * 4;               // elements reachable from the base
+    const int ngroups = (int)sv.groups;
+    const bool full = ngroups == kThreads * GPT && slice_end >= 4ull * kThreads * GPT;
+
+    uint4 v[GPT];
+    uint32_t m = 0;
+    if (full) {
+#pragma unroll
+        for (int k = 0; k < GPT; ++k) {
+            const int t = (int)threadIdx.x + k * kThreads;
+            v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(sin) + t));
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < GPT; ++k) {
+            const int t = (int)threadIdx.x + k * kThreads;
+            v[k] = make_uint4(0u, 0u, 0u, 0u);
+            if (t < ngroups) v[k] = load_group<true>(sin, (uint64_t)t, slice_end);
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < PRE; ++k) {
+        const Words4 r = random_words(sv.j0 + (uint64_t)((int)threadIdx.x + k * kThreads), key, 0u);
+        parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+    }
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t gm = max4_mag(v[k]);
+        m = m > gm ? m : gm;
+    }
+    m = workgroup_max(m, lds);
+
+    // All communication is through relaxed device-scope atomics on words that only atomics touch:
+    // nothing else has to become visible between workgroups, so no release or acquire fence (each
+    // of which writes back or invalidates a whole L2 on this multi-die part) is needed.  Order is
+    // kept by waiting for the returned value of one atomic before the next one is issued.
+    if (threadIdx.x == 0) {
+        uint32_t old = __hip_atomic_exchange(&slots[wg], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");       // the slot is published before we count
+        const uint32_t group = wg / kSyncGroup;
+        const uint32_t ngroups_sync = (rg.total_wgs + kSyncGroup - 1) / kSyncGroup;
+        const uint32_t in_group = (group + 1 == ngroups_sync) ? rg.total_wgs - group * kSyncGroup : kSyncGroup;
+        uint32_t* flags = sync + 16;
+        if (__hip_atomic_fetch_add(&sync[16 * (1 + kSyncFlagCopies + group)], 1u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT) == in_group - 1u) {
+            if (__hip_atomic_fetch_add(&sync[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ngroups_sync - 1u) {
+                for (uint32_t c = 0; c < kSyncFlagCopies; ++c)
+                    __hip_atomic_store(&flags[16 * c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        const uint32_t* my_flag = &flags[16 * (wg % kSyncFlagCopies)];
+        uint32_t polls = 0;
+        bool all = __hip_atomic_load(my_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+        while (!all && polls < rg.spin_limit) {
+            __builtin_amdgcn_s_sleep(2);
+            ++polls;
+            all = __hip_atomic_load(my_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+        }
+        shared_word = all ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool all_arrived = shared_word != 0u;
+
+    uint32_t bm = 0;
+    uint32_t* mine = slots + (uint64_t)b * rg.sg.slices;
+    if (all_arrived) {
+        for (uint32_t i = threadIdx.x; i < rg.sg.slices; i += kThreads) {
+            const uint32_t a = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ~kPublished;
+            bm = bm > a ? bm : a;
+        }
+        bm = workgroup_max(bm, lds);
+    } else {
+        for (uint32_t i = 0; i < rg.sg.slices; ++i) {
+            __syncthreads();
+            if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            uint32_t a = shared_word;
+            if (!(a & kPublished)) {
+                // the owner of slice i has not published, so it has not written any output yet:
+                // read its input; if the slot is still unpublished afterwards, the read was clean
+                const uint32_t own = workgroup_max(slice_max(in, slice_view(rg.sg, b, i)), lds);
+                __syncthreads();
+                if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __syncthreads();
+                a = (shared_word & kPublished) ? shared_word : own;
+            }
+            a &= ~kPublished;
+            bm = bm > a ? bm : a;
+        }
+    }
+
+    const GridPlan p = block_plan(bm, wl, symmetric);
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const int t = (int)threadIdx.x + k * kThreads;
+        if (full || t < ngroups) {
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (k < PRE) {
+                const uint4 w = parked[k * kThreads + threadIdx.x];
+                r = Words4{{w.x, w.y, w.z, w.w}};
+            } else if (MODE == QSIM_STOCHASTIC) {
+                r = random_words(sv.j0 + (uint64_t)t, key, 0u);
+            }
+            const uint4 o = quantize_group_to_grid<MODE>(v[k], p, r);
+            if (full) __builtin_nontemporal_store(to_u32x4(o), reinterpret_cast<u32x4*>(sout) + t);
+            else store_group<true>(sout, (uint64_t)t, slice_end, o);
         }
     }
 }

@@ -217,6 +217,32 @@ def test_block_misaligned_and_inplace():
         assert_bit_equal(np.concatenate([full[:off], full[off + n:]]), np.concatenate([x[:off], x[off + n:]]), "outside")
 
 
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+def test_block_single_pass_when_the_wait_runs_out(rounding):
+    """The single-pass kernel's wait for the other workgroups is bounded; with the bound forced to
+    zero from the host every workgroup derives the missing maxima from memory itself and the
+    result must still be exact, also in place and with several blocks."""
+    Q.set_barrier_spin_limit(0)
+    try:
+        for rows, cols in [(1, 200000), (3, 40000), (1, 16388)]:
+            x = W.row_scaled_matrix(rows, cols, seed=rows * 7 + 1)
+            x[0, cols // 2] = np.float32(-3.0e4)            # the maximum sits in one slice only
+            want = R.block_quantize(x, 1, rows, cols, 8, rounding, 0, 11, 3)
+            d = dev(x)
+            assert_bit_equal(host(Q.block_quantize(d, 1, rows, cols, 8, rounding, 0, 11, 3)), want, f"{rows}x{cols}")
+            Q.block_quantize(d, 1, rows, cols, 8, rounding, 0, 11, 3, out=d)
+            assert_bit_equal(host(d), want, f"{rows}x{cols} in place")
+    finally:
+        Q.set_barrier_spin_limit(1 << 20)
+
+
+def test_block_whole_tensor_beyond_register_capacity():
+    """A single block of 20 Mi elements does not fit in the chip's registers: two streaming passes."""
+    n = 5 * (1 << 22)
+    x = W.row_scaled_matrix(1, n, seed=77)
+    _block_case(x, 1, 1, n, 8, STOCHASTIC)
+
+
 def test_block_workspace_next_to_the_arrays():
     """Scratch that touches the arrays without overlapping them is accepted; overlapping scratch is not."""
     n = 1 << 18
