@@ -1,0 +1,28 @@
+"""Host-side logic of the front-end descriptors (no GPU needed)."""
+import pytest
+
+torch = pytest.importorskip("torch")
+from paper_1910_04540_amd import quantizer as Z     # noqa: E402
+
+
+def test_block_layouts():
+    shape = (6, 5, 7)
+    assert Z.BlockFloatingPoint(8, None).layout(shape) == (1, 1, 210)
+    assert Z.BlockFloatingPoint(8, 0).layout(shape) == (1, 6, 35)
+    assert Z.BlockFloatingPoint(8, 1).layout(shape) == (6, 5, 7)
+    assert Z.BlockFloatingPoint(8, 2).layout(shape) == (30, 7, 1)
+    assert Z.BlockFloatingPoint(8, -1).layout(shape) == (30, 7, 1)
+    assert Z.BlockFloatingPoint(8, 0).layout((9,)) == (1, 9, 1)
+
+
+def test_flags_and_rounding_names():
+    assert Z.FloatingPoint(5, 2).flags() == 1 and Z.FloatingPoint(5, 2, subnormal=True).flags() == 3
+    assert Z.FloatingPoint(8, 7, saturate=False).flags() == 0
+    assert Z.FixedPoint(8, 6).flags() == 1 and Z.FixedPoint(8, 6, clamp=False, symmetric=True).flags() == 4
+    assert Z.BlockFloatingPoint(8).flags() == 0 and Z.BlockFloatingPoint(8, symmetric=True).flags() == 4
+    assert [Z._rounding(k) for k in ("nearest", "nearest_away", "nearest_zero", "stochastic")] == [0, 1, 2, 3]
+    with pytest.raises(ValueError):
+        Z._rounding("banker")
+    q = Z.Quantizer(Z.FixedPoint(8, 6), None, "stochastic", "nearest", seed=4)
+    assert (q.forward_rounding, q.backward_rounding, q.seed, q.calls) == (3, 0, 4, 0)
+    assert "FixedPoint" in repr(q)
