@@ -113,12 +113,13 @@ size_t qsim_block_workspace_bytes(uint64_t n, uint64_t outer, uint64_t nblocks, 
 /*
  * Tuning and test knob of qsim_block_quantize.  A contiguous block that is too long for one
  * workgroup but fits in the register files of the whole chip is quantized in a single pass by
- * workgroups that wait for each other once.  That wait is bounded: after `polls` polls (about a
- * microsecond each; default 2^20) a workgroup stops waiting and derives the missing maxima from
- * memory itself, so the result is the same, only slower.  0 makes every workgroup take that path
- * at once.  Process-wide; affects calls made after it returns.
+ * workgroups that wait for each other once.  That wait is bounded: after `microseconds` (default
+ * 2000) a workgroup stops waiting and derives the missing maxima from memory itself, so the result
+ * is the same, only slower; this happens when the device is shared with other work and not every
+ * workgroup got a slot.  0 makes every workgroup take that path at once.  Process-wide; affects
+ * calls made after it returns.
  */
-void qsim_set_barrier_spin_limit(uint32_t polls);
+void qsim_set_barrier_wait_us(uint32_t microseconds);
 
 /* A number format for one category of numbers in the optimizer (Sec. 3.1 "Front-end interface"). */
 typedef struct {

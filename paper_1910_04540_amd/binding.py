@@ -20,7 +20,7 @@ KIND_IDENTITY, KIND_FLOAT, KIND_FIXED, KIND_BLOCK = 0, 1, 2, 3
 
 # Every symbol include/qsim.h declares.
 EXPORTS = ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_block_workspace_bytes",
-           "qsim_set_barrier_spin_limit", "qsim_quant_sgd_step", "qsim_status_string")
+           "qsim_set_barrier_wait_us", "qsim_quant_sgd_step", "qsim_status_string")
 
 
 class Format(ctypes.Structure):
@@ -55,8 +55,8 @@ def lib() -> ctypes.CDLL:
     L.qsim_quant_sgd_step.argtypes = [vp, vp, vp, vp, u64, ctypes.c_float, ctypes.c_float,
                                       ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
                                       u64, u32, vp]
-    L.qsim_set_barrier_spin_limit.argtypes = [u32]
-    L.qsim_set_barrier_spin_limit.restype = None
+    L.qsim_set_barrier_wait_us.argtypes = [u32]
+    L.qsim_set_barrier_wait_us.restype = None
     L.qsim_status_string.argtypes = [ci]
     L.qsim_status_string.restype = ctypes.c_char_p
     for name in ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_quant_sgd_step"):
@@ -111,9 +111,9 @@ def fixed_quantize(x, wl, fl, rounding=RN_EVEN, flags=SATURATE, seed=0, stream_i
     return out
 
 
-def set_barrier_spin_limit(polls: int) -> None:
-    """qsim_set_barrier_spin_limit: bound of the single-pass block kernel's wait (0 = fall back at once)."""
-    lib().qsim_set_barrier_spin_limit(polls)
+def set_barrier_wait_us(microseconds: int) -> None:
+    """qsim_set_barrier_wait_us: bound of the single-pass block kernel's wait (0 = fall back at once)."""
+    lib().qsim_set_barrier_wait_us(microseconds)
 
 
 def block_workspace_bytes(n, outer, nblocks, inner) -> int:

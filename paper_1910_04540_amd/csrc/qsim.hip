@@ -103,9 +103,15 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
 }
 
 // ---- single pass over resident workgroups ----------------------------------------------------
-static std::atomic<uint32_t> g_spin_limit{1u << 20};
+static std::atomic<uint32_t> g_barrier_wait_us{2000u};
 
-// Workgroups of block_resident_kernel<MODE, GPT> that fit on the current device at once.
+// Workgroups of block_resident_kernel<MODE, GPT> that are certain to be resident together on the
+// current device: four per CU at most.  At that occupancy every resource is accounted for by
+// construction (128 VGPRs by launch bounds, about 100 SGPRs, 36 KiB of LDS each); the runtime's
+// occupancy query is only allowed to lower the figure, because it has been seen to ignore the
+// scalar register file.
+constexpr int kResidentPerCu = 4;
+
 template <int MODE, int GPT>
 static uint32_t resident_capacity()
 {
@@ -119,8 +125,9 @@ static uint32_t resident_capacity()
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)block_resident_kernel<MODE, GPT>, kThreads,
                                                          0) == hipSuccess &&
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess;
-        c = ok && per_cu > 0 && cus > 0 ? per_cu * cus : -1;
         if (!ok) (void)hipGetLastError();
+        if (per_cu > kResidentPerCu) per_cu = kResidentPerCu;
+        c = ok && per_cu > 0 && cus > 0 ? per_cu * cus : -1;
         cache[dev].store(c, std::memory_order_relaxed);
     }
     return c > 0 ? (uint32_t)c : 0u;
@@ -144,7 +151,7 @@ static bool try_resident(const uint32_t* in, uint32_t* out, const BlockGeom& g, 
     rg.sg.slice_len = slice_len;
     rg.sg.slices = (uint32_t)slices;
     rg.total_wgs = (uint32_t)total;
-    rg.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
+    rg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
     const uint32_t words = kSyncSlots0 + (uint32_t)total;
     hipLaunchKernelGGL(block_sync_clear_kernel, dim3((words + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, sync, words);
     hipLaunchKernelGGL((block_resident_kernel<MODE, GPT>), dim3((unsigned)total), dim3(kThreads), 0, stream, in, out, sync, rg,
@@ -157,7 +164,8 @@ static bool try_resident_any(const uint32_t* in, uint32_t* out, const BlockGeom&
                              uint32_t* sync, hipStream_t stream)
 {
     // fewest groups per thread that still fit: more workgroups in flight hide more latency
-    return try_resident<MODE, 2>(in, out, g, wl, symmetric, key, sync, stream) ||
+    return try_resident<MODE, 1>(in, out, g, wl, symmetric, key, sync, stream) ||
+           try_resident<MODE, 2>(in, out, g, wl, symmetric, key, sync, stream) ||
            try_resident<MODE, 4>(in, out, g, wl, symmetric, key, sync, stream) ||
            try_resident<MODE, 8>(in, out, g, wl, symmetric, key, sync, stream) ||
            try_resident<MODE, 16>(in, out, g, wl, symmetric, key, sync, stream);
@@ -340,7 +348,7 @@ int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* m
     return launch_status();
 }
 
-void qsim_set_barrier_spin_limit(uint32_t polls) { g_spin_limit.store(polls, std::memory_order_relaxed); }
+void qsim_set_barrier_wait_us(uint32_t microseconds) { g_barrier_wait_us.store(microseconds, std::memory_order_relaxed); }
 
 const char* qsim_status_string(int status)
 {

@@ -430,8 +430,8 @@ __global__ __launch_bounds__(kThreads) void block_slice_apply_kernel(const uint3
 }
 
 // Single pass for contiguous blocks that fit in the register files of the whole chip (for instance
-// a 4096 x 4096 tensor quantized as one block).  Every workgroup is resident at the same time
-// (cooperative launch); it loads its slice of 256 * GPT groups into registers, publishes the
+// a 4096 x 4096 tensor quantized as one block).  The grid is small enough for every workgroup to be
+// resident at the same time; each loads its slice of 256 * GPT groups into registers, publishes the
 // slice's maximum, waits until all workgroups have arrived, folds the maxima of its block and
 // quantizes out of registers: HBM sees each element once in and once out.
 //
@@ -446,8 +446,8 @@ __global__ __launch_bounds__(kThreads) void block_slice_apply_kernel(const uint3
 // few dozen device-scope operations: a single counter polled by a thousand workgroups serialises
 // at its memory channel and costs far more than the kernel's whole memory traffic.
 //
-// The wait is bounded.  A workgroup whose wait runs out (never expected under a cooperative
-// launch) still produces the right result: for every slot of its block that is not yet published
+// The wait is bounded in time.  A workgroup whose wait runs out (the device is shared with other
+// work, so not every workgroup got a slot) still produces the right result: for every slot of its block that is not yet published
 // it computes the slice's maximum from memory itself.  That is safe even in place, because a
 // workgroup writes its output only after its own wait, which starts after it has published; so if
 // the slot is still unpublished after the read, the read saw nothing but input.
@@ -466,7 +466,7 @@ __global__ void block_sync_clear_kernel(uint32_t* sync, uint32_t words)
 struct ResidentGeom {
     SliceGeom sg;            // slice_len = 1024 * GPT elements; slices = workgroups per block
     uint32_t total_wgs;      // nblocks * slices
-    uint32_t spin_limit;     // polls before the fallback
+    uint32_t wait_us;        // microseconds a workgroup waits for the others before the fallback
 };
 
 // With 16 groups per thread the kernel must keep to 128 VGPRs (four waves per SIMD, four workgroups
@@ -542,11 +542,11 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
             }
         }
         const uint32_t* my_flag = &flags[16 * (wg % kSyncFlagCopies)];
-        uint32_t polls = 0;
+        const uint64_t t0 = __builtin_amdgcn_s_memrealtime();            // 100 MHz
+        const uint64_t budget = (uint64_t)rg.wait_us * 100u;
         bool all = __hip_atomic_load(my_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
-        while (!all && polls < rg.spin_limit) {
+        while (!all && __builtin_amdgcn_s_memrealtime() - t0 < budget) {
             __builtin_amdgcn_s_sleep(2);
-            ++polls;
             all = __hip_atomic_load(my_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
         }
         shared_word = all ? 1u : 0u;

@@ -222,7 +222,7 @@ def test_block_single_pass_when_the_wait_runs_out(rounding):
     """The single-pass kernel's wait for the other workgroups is bounded; with the bound forced to
     zero from the host every workgroup derives the missing maxima from memory itself and the
     result must still be exact, also in place and with several blocks."""
-    Q.set_barrier_spin_limit(0)
+    Q.set_barrier_wait_us(0)
     try:
         for rows, cols in [(1, 200000), (3, 40000), (1, 16388)]:
             x = W.row_scaled_matrix(rows, cols, seed=rows * 7 + 1)
@@ -233,7 +233,27 @@ def test_block_single_pass_when_the_wait_runs_out(rounding):
             Q.block_quantize(d, 1, rows, cols, 8, rounding, 0, 11, 3, out=d)
             assert_bit_equal(host(d), want, f"{rows}x{cols} in place")
     finally:
-        Q.set_barrier_spin_limit(1 << 20)
+        Q.set_barrier_wait_us(2000)
+
+
+@pytest.mark.parametrize("log2n", [20, 22, 23, 24])
+def test_block_single_pass_meets_without_waiting_out(log2n):
+    """On an otherwise idle GPU every workgroup of the single-pass kernel gets a slot, so the
+    bounded wait never runs out: a call takes microseconds, not the wait limit."""
+    n = 1 << log2n
+    x = dev(W.row_scaled_matrix(1, n, seed=log2n))
+    out = torch.empty_like(x)
+    ws = torch.empty(Q.block_workspace_bytes(n, 1, 1, n), dtype=torch.uint8, device="cuda")
+    for mode in (RN_EVEN, STOCHASTIC):
+        Q.block_quantize(x, 1, 1, n, 8, mode, 0, 1, 0, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for k in range(5):
+            Q.block_quantize(x, 1, 1, n, 8, mode, 0, 1, k, out=out, workspace=ws)
+        b.record()
+        torch.cuda.synchronize()
+        assert a.elapsed_time(b) / 5 < 1.0, f"n=2^{log2n} mode {mode}: {a.elapsed_time(b) / 5:.3f} ms per call"
 
 
 def test_block_whole_tensor_beyond_register_capacity():
