@@ -70,8 +70,8 @@ def _entry(name, elements, bytes_per_element, seconds, launches, extra=None):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=500, help="untimed launches; enough to bring the clocks up after an idle phase")
     ap.add_argument("--no-formats", action="store_true", help="skip the per-format table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     args = ap.parse_args()
@@ -133,9 +133,10 @@ def main() -> int:
     if not args.no_formats:
         formats = {}
         reps = max(10, args.steps // 4)
+        warm = max(10, args.warmup // 2)
 
         def run(name, fn, elements, bpe=BYTES_PER_ELEMENT, extra=None):
-            _, e = _time_launches(fn, reps, 5, torch)
+            _, e = _time_launches(fn, reps, warm, torch)
             k, d = _entry(name, elements, bpe, e, reps, extra)
             formats[k] = d
 

@@ -55,15 +55,6 @@ static int launch_elementwise_rt(const float* in, float* out, uint64_t n, const 
     return launch_status();
 }
 
-template <bool SAT>
-static int launch_float_shift(const float* in, float* out, uint64_t n, int rounding, const FormatPlan& f,
-                              const RngKey& key, hipStream_t stream)
-{
-    if (f.ftz == 0) return launch_elementwise(in, out, n, rounding, FloatShiftOp<SAT, 0>{f.flt}, key, stream);
-    if (f.ftz == 1) return launch_elementwise(in, out, n, rounding, FloatShiftOp<SAT, 1>{f.flt}, key, stream);
-    return launch_elementwise(in, out, n, rounding, FloatShiftOp<SAT, 2>{f.flt}, key, stream);
-}
-
 // ---- block floating point ------------------------------------------------------------------
 // How a block-quantize call is carried out; decided on the host from the shape alone, so that
 // qsim_block_workspace_bytes and qsim_block_quantize always agree.  (Alignment can only move a
@@ -255,12 +246,8 @@ int qsim_float_quantize(const float* in, float* out, uint64_t n, int exp_bits, i
     const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
     hipStream_t stream = as_stream(hip_stream);
     if (!aligned16(in) || !aligned16(out)) return launch_elementwise_rt(in, out, n, f, key, stream);
-    if (f.float_form == kFloatGeneral) {
-        if (f.saturate) return launch_elementwise(in, out, n, rounding, FloatGeneralOp<true>{f.flt}, key, stream);
-        return launch_elementwise(in, out, n, rounding, FloatGeneralOp<false>{f.flt}, key, stream);
-    }
-    if (f.saturate) return launch_float_shift<true>(in, out, n, rounding, f, key, stream);
-    return launch_float_shift<false>(in, out, n, rounding, f, key, stream);
+    if (f.float_form == kFloatGeneral) return launch_elementwise(in, out, n, rounding, FloatGeneralOp{f.flt}, key, stream);
+    return launch_elementwise(in, out, n, rounding, FloatShiftOp{f.flt}, key, stream);
 }
 
 int qsim_fixed_quantize(const float* in, float* out, uint64_t n, int wl, int fl, int rounding, uint32_t flags,
@@ -279,8 +266,7 @@ int qsim_fixed_quantize(const float* in, float* out, uint64_t n, int wl, int fl,
     const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
     hipStream_t stream = as_stream(hip_stream);
     if (!aligned16(in) || !aligned16(out)) return launch_elementwise_rt(in, out, n, f, key, stream);
-    if (f.saturate) return launch_elementwise(in, out, n, rounding, FixedOp<true>{f.grid}, key, stream);
-    return launch_elementwise(in, out, n, rounding, FixedOp<false>{f.grid}, key, stream);
+    return launch_elementwise(in, out, n, rounding, FixedOp{f.grid}, key, stream);
 }
 
 size_t qsim_block_workspace_bytes(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner)

@@ -72,29 +72,30 @@ __device__ __forceinline__ float round_scaled(float y, uint32_t r)
 //
 // Both clamp limits are grid points, rounding is monotone and leaves grid points alone, so clamping
 // the INPUT to [lo, hi] gives the same result as clamping the rounded code.  After the clamp
-// y = |x| / 2^q is at most 2^23.  Without saturation, inputs of 2^(q+24) and above are already on
-// the grid and are returned as they are (so are NaN and Inf, which fail the same comparison).
-// A y that underflows fp32 is below 2^-126: it rounds to zero in every mode either way.
+// y = |x| / 2^q is at most 2^23.  A format that does not saturate has lo = -Inf, hi = +Inf and
+// thr = 2^(q+24): inputs of that size and above are already on the grid and are returned as they
+// are (Inf included).  A saturating format has thr = +Inf, which only an infinite clamped
+// magnitude fails to stay below: -Inf in a block whose most negative code is -Inf.  NaN is always
+// returned as it is.  A y that underflows fp32 is below 2^-126: it rounds to zero in every mode.
+// One code path serves every flag combination; the flags live in the plan's constants.
 // ---------------------------------------------------------------------------------------------
 struct GridPlan {
     int q;                // grid step 2^q
-    float lo, hi;         // saturating: most negative and largest value (grid points)
-    float thr;            // not saturating: 2^(q+24), or +Inf when that is beyond fp32
-    uint32_t keep_class;  // saturating: v_cmp_class mask of inputs returned unchanged (NaN; -Inf when lo is -Inf)
+    float lo, hi;         // most negative and largest value (grid points), or -Inf / +Inf
+    float thr;            // magnitudes not below thr are returned unchanged
 };
 
-constexpr uint32_t kClassNaN = 0x003u;
-constexpr uint32_t kClassNegInf = 0x004u;
+constexpr int kClassNaN = 0x003;
 
-template <int MODE, bool SAT>
+template <int MODE>
 __device__ __forceinline__ uint32_t quantize_to_grid(uint32_t bits, const GridPlan& p, uint32_t r)
 {
     const float x = __uint_as_float(bits);
-    const float a = SAT ? __builtin_fabsf(__builtin_amdgcn_fmed3f(x, p.lo, p.hi)) : __builtin_fabsf(x);
+    const float a = __builtin_fabsf(__builtin_amdgcn_fmed3f(x, p.lo, p.hi));
     const float y = __builtin_ldexpf(a, -p.q);
     const float v = __builtin_ldexpf(round_scaled<MODE>(y, r), p.q);
     const uint32_t res = (__float_as_uint(v) & 0x7fffffffu) | (bits & 0x80000000u);
-    const bool keep = SAT ? __builtin_amdgcn_classf(x, (int)p.keep_class) : !(a < p.thr);
+    const bool keep = __builtin_amdgcn_classf(x, kClassNaN) || !(a < p.thr);
     return keep ? bits : res;
 }
 
@@ -110,28 +111,34 @@ __device__ __forceinline__ GridPlan block_plan(uint32_t max_mag, int wl, int sym
     const uint32_t neg = symmetric ? pos : ((field + 1u) << 23);      // 2^(e_s+1), Inf when e_s = 127
     p.hi = __uint_as_float(pos);
     p.lo = __uint_as_float(neg | 0x80000000u);
-    p.thr = 0.0f;
-    p.keep_class = kClassNaN | (neg == 0x7f800000u ? kClassNegInf : 0u);
+    p.thr = __builtin_inff();
     return p;
 }
 
 // ---------------------------------------------------------------------------------------------
-// Custom floating point (Sec. 3.1 "Number Formats", first paragraph).
+// Custom floating point (Sec. 3.1 "Number Formats", first paragraph).  As above, one code path per
+// form; saturation and flushing are constants of the plan:
+//   max_enc     encoding of the largest value, or of Inf when the format does not saturate
+//   keep_thr    magnitude encodings from here on are returned unchanged: NaN (0x7f800001) when the
+//               format saturates, Inf and NaN (0x7f800000) when it does not
+//   min_normal  encoding of 2^emin when results below it are flushed to zero, else 0
 //
 // "Shift" form: every input that is not flushed loses the same `drop` = 23 - M low fraction bits,
 // so rounding is integer arithmetic on the encoding with a constant mask; a carry runs into the
 // exponent field by itself.  Valid when the format has no binade of its own below fp32's (E = 8
 // with gradual underflow: fp32 denormals share the step of the lowest binade) or when results
-// below 2^emin are flushed.  FTZ = 1: flush.  FTZ = 2: flush, and fp32 denormal inputs (possible
-// survivors only when E = 8) are rounded with their true exponent on a rarely taken side path.
+// below 2^emin are flushed.  With E = 8 and flushing (`denormal_inputs`), fp32 denormal inputs are
+// rounded with their true exponent on a rarely taken side path, since the largest of them can
+// round up to 2^-126 and survive.
 // ---------------------------------------------------------------------------------------------
 struct FloatPlan {
     int drop;             // 23 - man_bits
     int man_bits;
     int emin_field;       // emin + 127: exponent field of the smallest normal binade
-    uint32_t max_enc;     // encoding of the largest value
-    uint32_t min_normal;  // encoding of 2^emin
-    float maxval;         // the largest value
+    uint32_t max_enc;
+    uint32_t keep_thr;
+    uint32_t min_normal;
+    int denormal_inputs;
 };
 
 template <int MODE>
@@ -147,39 +154,38 @@ __device__ __forceinline__ uint32_t round_encoding(uint32_t mag, int drop, uint3
     return (mag + inc) & ~mask;
 }
 
-template <int MODE, bool SAT, int FTZ>
+template <int MODE>
 __device__ __forceinline__ uint32_t quantize_float_shift(uint32_t bits, const FloatPlan& p, uint32_t r)
 {
     const uint32_t mag0 = bits & 0x7fffffffu;
-    const uint32_t mag = SAT ? (mag0 < p.max_enc ? mag0 : p.max_enc) : mag0;      // Inf saturates; without SAT it stays Inf below
+    const uint32_t mag = mag0 < p.max_enc ? mag0 : p.max_enc;
     uint32_t res = p.drop ? round_encoding<MODE>(mag, p.drop, r) : mag;
-    if (FTZ == 2 && mag - 1u < 0x7fffffu) {
+    if (p.denormal_inputs && mag - 1u < 0x7fffffu) {
         // fp32 denormal: keep man_bits below the leading one of the fraction
         const int top = 31 - __builtin_clz(mag);
         const int s = top - p.man_bits;
         res = s > 0 ? round_encoding<MODE>(mag, s, r) : mag;
     }
-    if (FTZ) res = res < p.min_normal ? 0u : res;
+    res = res < p.min_normal ? 0u : res;
     res |= bits & 0x80000000u;
-    return mag0 > 0x7f800000u ? bits : res;                                     // NaN passes through
+    return mag0 >= p.keep_thr ? bits : res;
 }
 
 // "General" form, gradual underflow with E < 8: the grid step depends on the element,
 // 2^(max(e, emin) - M); scale by it, round, scale back.  y < 2^(M+1) <= 2^24.
-template <int MODE, bool SAT>
+template <int MODE>
 __device__ __forceinline__ uint32_t quantize_float_general(uint32_t bits, const FloatPlan& p, uint32_t r)
 {
-    const float x = __uint_as_float(bits);
-    const float a = SAT ? __builtin_fminf(__builtin_fabsf(x), p.maxval) : __builtin_fabsf(x);
-    int field = (int)(__float_as_uint(a) >> 23);
+    const uint32_t mag0 = bits & 0x7fffffffu;
+    const uint32_t mag = mag0 < p.max_enc ? mag0 : p.max_enc;
+    const float a = __uint_as_float(mag);
+    int field = (int)(mag >> 23);
     field = field > p.emin_field ? field : p.emin_field;
     const int q = field - 127 - p.man_bits;
     const float y = __builtin_ldexpf(a, -q);
     const float v = __builtin_ldexpf(round_scaled<MODE>(y, r), q);
     const uint32_t res = (__float_as_uint(v) & 0x7fffffffu) | (bits & 0x80000000u);
-    // NaN always passes; Inf passes unless it saturated to maxval above
-    const bool keep = SAT ? (x != x) : !(a < __builtin_inff());
-    return keep ? bits : res;
+    return mag0 >= p.keep_thr ? bits : res;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -191,9 +197,7 @@ enum { kFloatShift = 0, kFloatGeneral = 1 };
 struct FormatPlan {
     int kind;           // qsim_format::kind
     int mode;           // rounding
-    int saturate;       // float / fixed
     int float_form;     // kFloatShift or kFloatGeneral
-    int ftz;            // shift form: 0, 1, 2 as above
     int wl;             // block: word length
     int symmetric;      // block: symmetric clamp
     int lanes;          // block: lanes (groups of 4 elements) per chunk = L / 4
@@ -202,61 +206,40 @@ struct FormatPlan {
 };
 
 template <int MODE>
-__device__ __forceinline__ uint32_t quantize_float_rt(const FormatPlan& f, uint32_t bits, uint32_t r)
-{
-    if (f.float_form == kFloatGeneral)
-        return f.saturate ? quantize_float_general<MODE, true>(bits, f.flt, r)
-                          : quantize_float_general<MODE, false>(bits, f.flt, r);
-    if (f.saturate) {
-        if (f.ftz == 0) return quantize_float_shift<MODE, true, 0>(bits, f.flt, r);
-        if (f.ftz == 1) return quantize_float_shift<MODE, true, 1>(bits, f.flt, r);
-        return quantize_float_shift<MODE, true, 2>(bits, f.flt, r);
-    }
-    if (f.ftz == 0) return quantize_float_shift<MODE, false, 0>(bits, f.flt, r);
-    if (f.ftz == 1) return quantize_float_shift<MODE, false, 1>(bits, f.flt, r);
-    return quantize_float_shift<MODE, false, 2>(bits, f.flt, r);
-}
-
-template <int MODE>
-__device__ __forceinline__ uint32_t quantize_grid_rt(int saturate, const GridPlan& p, uint32_t bits, uint32_t r)
-{
-    return saturate ? quantize_to_grid<MODE, true>(bits, p, r) : quantize_to_grid<MODE, false>(bits, p, r);
-}
-
-// Quantize the four elements of a group with a float or fixed format chosen at run time.
-__device__ __forceinline__ uint4 quantize_group_rt(const FormatPlan& f, const GridPlan& grid, int grid_saturate,
-                                                   const uint4& v, const Words4& r)
+__device__ __forceinline__ uint4 quantize_group_mode(const FormatPlan& f, const GridPlan& grid, const uint4& v, const Words4& r)
 {
     uint4 o;
-#define QSIM_APPLY4(EXPR_X, EXPR_Y, EXPR_Z, EXPR_W) \
-    do { o.x = EXPR_X; o.y = EXPR_Y; o.z = EXPR_Z; o.w = EXPR_W; } while (0)
-#define QSIM_BY_MODE(FN, ...)                                                                                   \
-    switch (f.mode) {                                                                                           \
-    case QSIM_RN_EVEN:                                                                                          \
-        QSIM_APPLY4(FN<QSIM_RN_EVEN>(__VA_ARGS__, v.x, r.w[0]), FN<QSIM_RN_EVEN>(__VA_ARGS__, v.y, r.w[1]),     \
-                    FN<QSIM_RN_EVEN>(__VA_ARGS__, v.z, r.w[2]), FN<QSIM_RN_EVEN>(__VA_ARGS__, v.w, r.w[3]));    \
-        break;                                                                                                  \
-    case QSIM_RN_AWAY:                                                                                          \
-        QSIM_APPLY4(FN<QSIM_RN_AWAY>(__VA_ARGS__, v.x, r.w[0]), FN<QSIM_RN_AWAY>(__VA_ARGS__, v.y, r.w[1]),     \
-                    FN<QSIM_RN_AWAY>(__VA_ARGS__, v.z, r.w[2]), FN<QSIM_RN_AWAY>(__VA_ARGS__, v.w, r.w[3]));    \
-        break;                                                                                                  \
-    case QSIM_RN_ZERO:                                                                                          \
-        QSIM_APPLY4(FN<QSIM_RN_ZERO>(__VA_ARGS__, v.x, r.w[0]), FN<QSIM_RN_ZERO>(__VA_ARGS__, v.y, r.w[1]),     \
-                    FN<QSIM_RN_ZERO>(__VA_ARGS__, v.z, r.w[2]), FN<QSIM_RN_ZERO>(__VA_ARGS__, v.w, r.w[3]));    \
-        break;                                                                                                  \
-    default:                                                                                                    \
-        QSIM_APPLY4(FN<QSIM_STOCHASTIC>(__VA_ARGS__, v.x, r.w[0]), FN<QSIM_STOCHASTIC>(__VA_ARGS__, v.y, r.w[1]), \
-                    FN<QSIM_STOCHASTIC>(__VA_ARGS__, v.z, r.w[2]), FN<QSIM_STOCHASTIC>(__VA_ARGS__, v.w, r.w[3])); \
-        break;                                                                                                  \
-    }
     if (f.kind == 1) {
-        QSIM_BY_MODE(quantize_float_rt, f)
+        if (f.float_form == kFloatGeneral) {
+            o.x = quantize_float_general<MODE>(v.x, f.flt, r.w[0]);
+            o.y = quantize_float_general<MODE>(v.y, f.flt, r.w[1]);
+            o.z = quantize_float_general<MODE>(v.z, f.flt, r.w[2]);
+            o.w = quantize_float_general<MODE>(v.w, f.flt, r.w[3]);
+        } else {
+            o.x = quantize_float_shift<MODE>(v.x, f.flt, r.w[0]);
+            o.y = quantize_float_shift<MODE>(v.y, f.flt, r.w[1]);
+            o.z = quantize_float_shift<MODE>(v.z, f.flt, r.w[2]);
+            o.w = quantize_float_shift<MODE>(v.w, f.flt, r.w[3]);
+        }
     } else {
-        QSIM_BY_MODE(quantize_grid_rt, grid_saturate, grid)
+        o.x = quantize_to_grid<MODE>(v.x, grid, r.w[0]);
+        o.y = quantize_to_grid<MODE>(v.y, grid, r.w[1]);
+        o.z = quantize_to_grid<MODE>(v.z, grid, r.w[2]);
+        o.w = quantize_to_grid<MODE>(v.w, grid, r.w[3]);
     }
-#undef QSIM_BY_MODE
-#undef QSIM_APPLY4
     return o;
+}
+
+// Quantize the four elements of a group with a float format, or with the given grid (fixed point,
+// or a block's plan), the rounding mode chosen at run time.
+__device__ __forceinline__ uint4 quantize_group_rt(const FormatPlan& f, const GridPlan& grid, const uint4& v, const Words4& r)
+{
+    switch (f.mode) {
+    case QSIM_RN_EVEN: return quantize_group_mode<QSIM_RN_EVEN>(f, grid, v, r);
+    case QSIM_RN_AWAY: return quantize_group_mode<QSIM_RN_AWAY>(f, grid, v, r);
+    case QSIM_RN_ZERO: return quantize_group_mode<QSIM_RN_ZERO>(f, grid, v, r);
+    default:           return quantize_group_mode<QSIM_STOCHASTIC>(f, grid, v, r);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -55,40 +55,37 @@ inline GridPlan fixed_plan(int wl, int fl, uint32_t flags)
 {
     GridPlan p;
     p.q = -fl;
-    const double kmax = ldexp(1.0, wl - 1) - 1.0;
-    const double kneg = (flags & QSIM_SYMMETRIC) ? kmax : ldexp(1.0, wl - 1);
-    p.hi = (float)ldexp(kmax, p.q);                   // exact: at most 23 significant bits
-    p.lo = -(float)ldexp(kneg, p.q);
-    p.thr = (p.q + 24 <= 127) ? (float)ldexp(1.0, p.q + 24) : INFINITY;
-    p.keep_class = kClassNaN;
+    if (flags & QSIM_SATURATE) {
+        const double kmax = ldexp(1.0, wl - 1) - 1.0;
+        const double kneg = (flags & QSIM_SYMMETRIC) ? kmax : ldexp(1.0, wl - 1);
+        p.hi = (float)ldexp(kmax, p.q);               // exact: at most 23 significant bits
+        p.lo = -(float)ldexp(kneg, p.q);
+        p.thr = INFINITY;
+    } else {
+        p.hi = INFINITY;
+        p.lo = -INFINITY;
+        p.thr = (p.q + 24 <= 127) ? (float)ldexp(1.0, p.q + 24) : INFINITY;
+    }
     return p;
 }
 
-inline FloatPlan float_plan(int exp_bits, int man_bits)
+// Float plan and the device form that carries it out.
+inline FloatPlan float_plan(int exp_bits, int man_bits, uint32_t flags, int* form)
 {
     FloatPlan p;
     const int bias = (1 << (exp_bits - 1)) - 1;
     const int emin = 1 - bias;
+    const bool saturate = (flags & QSIM_SATURATE) != 0;
+    const bool subnormal = (flags & QSIM_SUBNORMAL) != 0;
     p.drop = 23 - man_bits;
     p.man_bits = man_bits;
     p.emin_field = emin + 127;
-    p.maxval = (float)ldexp(2.0 - ldexp(1.0, -man_bits), bias);
-    p.max_enc = float_bits(p.maxval);
-    p.min_normal = (uint32_t)p.emin_field << 23;
+    p.max_enc = saturate ? float_bits((float)ldexp(2.0 - ldexp(1.0, -man_bits), bias)) : 0x7f800000u;
+    p.keep_thr = saturate ? 0x7f800001u : 0x7f800000u;
+    p.min_normal = subnormal ? 0u : ((uint32_t)p.emin_field << 23);
+    p.denormal_inputs = (!subnormal && exp_bits == 8) ? 1 : 0;
+    *form = (subnormal && exp_bits < 8) ? kFloatGeneral : kFloatShift;
     return p;
-}
-
-// Which device form carries a float format out, and how it treats results below 2^emin.
-inline void float_strategy(int exp_bits, uint32_t flags, int* form, int* ftz)
-{
-    const bool subnormal = (flags & QSIM_SUBNORMAL) != 0;
-    if (subnormal && exp_bits < 8) {
-        *form = kFloatGeneral;
-        *ftz = 0;
-    } else {
-        *form = kFloatShift;
-        *ftz = subnormal ? 0 : (exp_bits == 8 ? 2 : 1);
-    }
 }
 
 // n must fit the [outer, nblocks, inner] view; only outer == 1 may leave the last block short.
@@ -115,14 +112,11 @@ inline int make_format_plan(const qsim_format* f, FormatPlan* out)
     case 0: break;
     case 1:
         if (!valid_float(f->a, f->b)) return QSIM_ERR_FORMAT;
-        p.flt = float_plan(f->a, f->b);
-        p.saturate = (f->flags & QSIM_SATURATE) ? 1 : 0;
-        float_strategy(f->a, f->flags, &p.float_form, &p.ftz);
+        p.flt = float_plan(f->a, f->b, f->flags, &p.float_form);
         break;
     case 2:
         if (!valid_fixed(f->a, f->b)) return QSIM_ERR_FORMAT;
         p.grid = fixed_plan(f->a, f->b, f->flags);
-        p.saturate = (f->flags & QSIM_SATURATE) ? 1 : 0;
         break;
     case 3:
         if (!valid_block_wl(f->a) || f->b < 4 || f->b > 1024 || (f->b & (f->b - 1)) != 0) return QSIM_ERR_FORMAT;

@@ -54,33 +54,30 @@ __device__ __forceinline__ void store_group(uint32_t* p, uint64_t j, uint64_t en
 // ---------------------------------------------------------------------------------------------
 // Elementwise quantizers with the format resolved at compile time (aligned arrays).
 // ---------------------------------------------------------------------------------------------
-template <bool SAT>
 struct FixedOp {
     GridPlan plan;
     template <int MODE>
     __device__ __forceinline__ uint32_t apply(uint32_t bits, uint32_t r) const
     {
-        return quantize_to_grid<MODE, SAT>(bits, plan, r);
+        return quantize_to_grid<MODE>(bits, plan, r);
     }
 };
 
-template <bool SAT, int FTZ>
 struct FloatShiftOp {
     FloatPlan plan;
     template <int MODE>
     __device__ __forceinline__ uint32_t apply(uint32_t bits, uint32_t r) const
     {
-        return quantize_float_shift<MODE, SAT, FTZ>(bits, plan, r);
+        return quantize_float_shift<MODE>(bits, plan, r);
     }
 };
 
-template <bool SAT>
 struct FloatGeneralOp {
     FloatPlan plan;
     template <int MODE>
     __device__ __forceinline__ uint32_t apply(uint32_t bits, uint32_t r) const
     {
-        return quantize_float_general<MODE, SAT>(bits, plan, r);
+        return quantize_float_general<MODE>(bits, plan, r);
     }
 };
 
@@ -120,7 +117,7 @@ __global__ __launch_bounds__(kThreads) void elementwise_rt_kernel(const uint32_t
     const uint4 v = load_group<false>(in, j, n);
     Words4 r = {{0u, 0u, 0u, 0u}};
     if (f.mode == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
-    store_group<false>(out, j, n, quantize_group_rt(f, f.grid, f.saturate, v, r));
+    store_group<false>(out, j, n, quantize_group_rt(f, f.grid, v, r));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -145,10 +142,10 @@ template <int MODE>
 __device__ __forceinline__ uint4 quantize_group_to_grid(const uint4& v, const GridPlan& p, const Words4& r)
 {
     uint4 o;
-    o.x = quantize_to_grid<MODE, true>(v.x, p, r.w[0]);
-    o.y = quantize_to_grid<MODE, true>(v.y, p, r.w[1]);
-    o.z = quantize_to_grid<MODE, true>(v.z, p, r.w[2]);
-    o.w = quantize_to_grid<MODE, true>(v.w, p, r.w[3]);
+    o.x = quantize_to_grid<MODE>(v.x, p, r.w[0]);
+    o.y = quantize_to_grid<MODE>(v.y, p, r.w[1]);
+    o.z = quantize_to_grid<MODE>(v.z, p, r.w[2]);
+    o.w = quantize_to_grid<MODE>(v.w, p, r.w[3]);
     return o;
 }
 
@@ -243,7 +240,7 @@ __global__ __launch_bounds__(kThreads) void block_rows_kernel(const uint32_t* in
             const uint64_t i = start + t;
             uint32_t r = 0;
             if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
-            out[i] = quantize_to_grid<MODE, true>(in[i], p, r);
+            out[i] = quantize_to_grid<MODE>(in[i], p, r);
         }
     }
 }
@@ -330,7 +327,7 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
             const uint64_t i = flat_index(sg.g, b, t);
             uint32_t r = 0;
             if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
-            out[i] = quantize_to_grid<MODE, true>(in[i], p, r);
+            out[i] = quantize_to_grid<MODE>(in[i], p, r);
         }
     }
 }
@@ -635,9 +632,9 @@ __device__ __forceinline__ uint4 apply_format(const FormatPlan& f, const uint4& 
     if (f.mode == QSIM_STOCHASTIC) r = random_words(j, key, role);
     if (f.kind == 3) {
         const GridPlan p = block_plan(chunk_max(max4_mag(v), f.lanes, lds), f.wl, f.symmetric);
-        return quantize_group_rt(f, p, 1, v, r);
+        return quantize_group_rt(f, p, v, r);
     }
-    return quantize_group_rt(f, f.grid, f.saturate, v, r);
+    return quantize_group_rt(f, f.grid, v, r);
 }
 
 __device__ __forceinline__ uint32_t fma_bits(float a, uint32_t b, uint32_t c)
