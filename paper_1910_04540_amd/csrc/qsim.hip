@@ -62,7 +62,10 @@ static int launch_elementwise_rt(const float* in, float* out, uint64_t n, const 
 struct BlockSchedule {
     bool one_launch;       // contiguous blocks small enough for one team or workgroup each
     SliceGeom sg;          // otherwise: two launches over slices
-    size_t workspace;      // bytes of scratch needed
+    bool column;           // outer > 1 and rows made of whole groups: the column form (aligned arrays)
+    ColumnGeom cg;
+    size_t column_bytes;   // scratch of the column form: column maxima, then block maxima
+    size_t workspace;      // bytes of scratch needed (the largest of the forms the shape may take)
 };
 
 constexpr uint64_t kCachedMaxInner = 16384;      // 256 threads x 16 groups x 4 elements
@@ -70,6 +73,7 @@ constexpr uint32_t kMaxSlices = 1024;
 constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
 constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
+constexpr uint64_t kColumnThreads = 1ull << 19;  // threads the column form aims for
 
 static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner)
 {
@@ -90,6 +94,28 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
     // the single-pass form keeps its counter and one slot per workgroup in the same scratch
     const size_t resident = (size_t)(kSyncSlots0 + kMaxResidentWgs) * sizeof(uint32_t);
     if (outer == 1 && s.workspace < resident) s.workspace = resident;
+    // the column form: rows of whole groups, short enough for 32-bit column arithmetic.  It is for
+    // short blocks (a thread walking down a column jumps a whole row per step, which only pays when
+    // the alternative cannot use whole groups or would do a division per group of a short segment);
+    // long segments stream better through the slice kernels.
+    const unsigned __int128 row = (unsigned __int128)nblocks * inner;
+    if (outer > 1 && row % 4 == 0 && row <= (1ull << 31) && outer <= (1ull << 32) && (inner % 4 != 0 || inner < 64)) {
+        s.column = true;
+        ColumnGeom& cg = s.cg;
+        cg.outer = outer;
+        cg.row_groups = (uint32_t)(row / 4);
+        cg.inner = (uint32_t)inner;
+        cg.nblocks = (uint32_t)nblocks;
+        // enough threads to fill the chip, at least 16 rows per thread when there are that many
+        uint64_t slices = (kColumnThreads + cg.row_groups - 1) / cg.row_groups;
+        const uint64_t most = (outer + 15) / 16;
+        if (slices > most) slices = most;
+        if (slices > 65535) slices = 65535;
+        cg.rows_per_slice = (uint32_t)((outer + slices - 1) / slices);
+        cg.slices = (uint32_t)((outer + cg.rows_per_slice - 1) / cg.rows_per_slice);
+        s.column_bytes = (size_t)cg.slices * (size_t)row * sizeof(uint32_t) + (size_t)nblocks * sizeof(uint32_t);
+        if (s.workspace < s.column_bytes) s.workspace = s.column_bytes;
+    }
     return s;
 }
 
@@ -212,6 +238,16 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
                            partial, s.sg, wl, symmetric, key);
+    } else if (s.column && aligned16(in) && aligned16(out)) {
+        const ColumnGeom& cg = s.cg;
+        uint4* colmax = reinterpret_cast<uint4*>(workspace);
+        uint32_t* blockmax = partial + (size_t)cg.slices * cg.row_groups * 4;
+        const dim3 cgrid((cg.row_groups + kThreads - 1) / kThreads, cg.slices);
+        hipLaunchKernelGGL(block_column_max_kernel, cgrid, dim3(kThreads), 0, stream, pin, colmax, cg);
+        hipLaunchKernelGGL(block_column_fold_kernel, dim3((cg.nblocks + kThreads / 64 - 1) / (kThreads / 64)), dim3(kThreads), 0,
+                           stream, partial, blockmax, cg);
+        hipLaunchKernelGGL((block_column_apply_kernel<MODE>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax, cg, wl,
+                           symmetric, key);
     } else if (vec) {
         hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg, wl,

@@ -332,6 +332,109 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
     }
 }
 
+// Blocks along an inner dimension (outer > 1) when a row of nblocks * inner elements is a whole
+// number of groups and the arrays are aligned: the "column" form.  A thread owns one group of four
+// neighbouring columns and a slice of rows and walks down its rows, so every access is a coalesced
+// dwordx4 along the row, whatever the block length; the block of each of its four columns is
+// fixed, so the index arithmetic (one division per column) is paid once per thread.
+//   pass 1   per-column maxima of every row slice       -> colmax[slice][column]
+//   fold     block maximum = max over slices and over the block's `inner` columns -> blockmax[b]
+//   pass 2   the same walk again: quantize with the plans of the four columns' blocks
+struct ColumnGeom {
+    uint64_t outer;            // rows
+    uint32_t row_groups;       // groups per row = nblocks * inner / 4
+    uint32_t inner;
+    uint32_t nblocks;
+    uint32_t slices;           // row slices
+    uint32_t rows_per_slice;
+};
+
+__global__ __launch_bounds__(kThreads) void block_column_max_kernel(const uint32_t* in, uint4* colmax, ColumnGeom cg)
+{
+    const uint32_t c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= cg.row_groups) return;
+    const uint64_t o0 = (uint64_t)blockIdx.y * cg.rows_per_slice;
+    const uint64_t o1 = (o0 + cg.rows_per_slice < cg.outer) ? o0 + cg.rows_per_slice : cg.outer;
+    const uint4* col = reinterpret_cast<const uint4*>(in) + c;
+    uint4 m = {0u, 0u, 0u, 0u};
+    for (uint64_t o = o0; o < o1; o += 4) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            v[k] = make_uint4(0u, 0u, 0u, 0u);
+            if (o + k < o1) v[k] = col[(o + k) * cg.row_groups];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint32_t a0 = v[k].x & 0x7fffffffu, a1 = v[k].y & 0x7fffffffu;
+            const uint32_t a2 = v[k].z & 0x7fffffffu, a3 = v[k].w & 0x7fffffffu;
+            m.x = m.x > a0 ? m.x : a0;
+            m.y = m.y > a1 ? m.y : a1;
+            m.z = m.z > a2 ? m.z : a2;
+            m.w = m.w > a3 ? m.w : a3;
+        }
+    }
+    colmax[(uint64_t)blockIdx.y * cg.row_groups + c] = m;
+}
+
+// One wavefront per block: lanes stride over the block's slices * inner column maxima.
+__global__ __launch_bounds__(kThreads) void block_column_fold_kernel(const uint32_t* colmax, uint32_t* blockmax, ColumnGeom cg)
+{
+    const uint64_t b = (uint64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    const uint32_t lane = threadIdx.x & 63;
+    uint32_t m = 0;
+    if (b < cg.nblocks) {
+        const uint64_t row = 4ull * cg.row_groups;
+        const uint32_t count = cg.slices * cg.inner;
+        for (uint32_t t = lane; t < count; t += 64) {
+            const uint32_t s = t / cg.inner, i = t - s * cg.inner;
+            const uint32_t a = colmax[s * row + b * cg.inner + i];
+            m = m > a ? m : a;
+        }
+    }
+    m = wave_max(m);
+    if (lane == 0 && b < cg.nblocks) blockmax[b] = m;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint32_t* in, uint32_t* out,
+                                                                      const uint32_t* blockmax, ColumnGeom cg, int wl,
+                                                                      int symmetric, RngKey key)
+{
+    const uint32_t c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= cg.row_groups) return;
+    const uint64_t o0 = (uint64_t)blockIdx.y * cg.rows_per_slice;
+    const uint64_t o1 = (o0 + cg.rows_per_slice < cg.outer) ? o0 + cg.rows_per_slice : cg.outer;
+    const uint32_t b0 = (4u * c) / cg.inner;
+    GridPlan p[4];
+    if (cg.inner % 4 == 0) {
+        p[0] = p[1] = p[2] = p[3] = block_plan(blockmax[b0], wl, symmetric);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) p[e] = block_plan(blockmax[(4u * c + e) / cg.inner], wl, symmetric);
+    }
+    for (uint64_t o = o0; o < o1; o += 4) {
+        uint4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (o + k < o1) v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in) + (o + k) * cg.row_groups + c));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (o + k < o1) {
+                const uint64_t j = (o + k) * cg.row_groups + c;
+                Words4 r = {{0u, 0u, 0u, 0u}};
+                if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+                uint4 q;
+                q.x = quantize_to_grid<MODE>(v[k].x, p[0], r.w[0]);
+                q.y = quantize_to_grid<MODE>(v[k].y, p[1], r.w[1]);
+                q.z = quantize_to_grid<MODE>(v[k].z, p[2], r.w[2]);
+                q.w = quantize_to_grid<MODE>(v[k].w, p[3], r.w[3]);
+                __builtin_nontemporal_store(to_u32x4(q), reinterpret_cast<u32x4*>(out) + j);
+            }
+        }
+    }
+}
+
 // Contiguous blocks spread over several workgroups (outer == 1, inner % 4 == 0, aligned arrays):
 // the streaming forms of the two passes.  Workgroup (s, b) owns slice s of block b in both passes
 // and walks it in steps of 4096 elements with four loads in flight per thread.  Pass 1 writes the

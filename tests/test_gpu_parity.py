@@ -194,7 +194,9 @@ def test_block_contiguous_chunks(n, L, rounding):
 
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
 @pytest.mark.parametrize("shape,dim", [((6, 5, 7), 1), ((6, 5, 7), 2), ((16, 32, 64), 1), ((64, 20, 36), 1),
-                                       ((300, 40), 1), ((8, 3, 1024), 1), ((2, 2, 40000), 1)])
+                                       ((300, 40), 1), ((8, 3, 1024), 1), ((2, 2, 40000), 1), ((50, 8, 3), 1),
+                                       ((40, 6, 6), 1), ((33, 1000, 12), 1), ((1030, 2052), 1), ((5, 64, 14, 14), 1),
+                                       ((3, 2, 4, 2), 2), ((70000, 4), 1), ((17, 2, 2), 1)])
 def test_block_over_an_inner_dimension(shape, dim, rounding):
     g = np.random.Generator(np.random.PCG64(int(np.prod(shape))))
     x = (g.standard_normal(shape) * np.exp2(g.integers(-10, 10, size=shape))).astype(np.float32)
