@@ -142,11 +142,27 @@ typedef struct {
  * quantizes into contiguous chunks of L elements (the last may be short).  Random words use
  * role 0 for the gradient, 1 for the momentum and 2 for the weight.  No dampening, Nesterov
  * momentum or weight decay.  w_master and mom are updated in place; grad is read only.
+ * w_q may also be w_master itself: then no fp32 master copy is kept and the weights are stored in
+ * the weight format (the accumulator is quantized, as the paper's optimizer does by default).
  */
 int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n,
                         float lr, float momentum, const qsim_format* fmt_grad,
                         const qsim_format* fmt_mom, const qsim_format* fmt_weight, uint64_t seed,
                         uint32_t stream_id, void* hip_stream);
+
+/*
+ * The same step over `ntensors` tensors in one launch per 32 tensors (a model's parameters are many,
+ * mostly small tensors; one launch each would be bound by launch latency).  w_master, w_q, grad,
+ * mom and n are HOST arrays of `ntensors` device pointers / element counts; w_q may be NULL (no
+ * quantized copies) and so may any of its entries.  Tensor t is processed exactly as
+ * qsim_quant_sgd_step would with stream_id + t, so results do not depend on how tensors are grouped.
+ * Overlap is checked within each tensor, not between tensors.  Empty tensors are skipped.
+ */
+int qsim_quant_sgd_step_multi(int ntensors, float* const* w_master, float* const* w_q,
+                              const float* const* grad, float* const* mom, const uint64_t* n, float lr,
+                              float momentum, const qsim_format* fmt_grad, const qsim_format* fmt_mom,
+                              const qsim_format* fmt_weight, uint64_t seed, uint32_t stream_id,
+                              void* hip_stream);
 
 /* Static description of a status code (never NULL). */
 const char* qsim_status_string(int status);

@@ -344,7 +344,7 @@ int qsim_ref_quant_sgd_step(float* w_master, float* w_q, const float* grad, floa
     if (!w_master || !grad || !mom) return QSIM_REF_ERR_NULL;
     if (any_overlap(w_master, grad, n) || any_overlap(w_master, mom, n) || any_overlap(grad, mom, n))
         return QSIM_REF_ERR_OVERLAP;
-    if (w_q && (any_overlap(w_q, w_master, n) || any_overlap(w_q, grad, n) || any_overlap(w_q, mom, n)))
+    if (w_q && (partial_overlap(w_q, w_master, n) || any_overlap(w_q, grad, n) || any_overlap(w_q, mom, n)))
         return QSIM_REF_ERR_OVERLAP;
 
     /* gq = Qg(grad): the gradient array is an input only, so its quantized copy is a temporary */
@@ -361,9 +361,9 @@ int qsim_ref_quant_sgd_step(float* w_master, float* w_q, const float* grad, floa
     /* w = fma(-lr, v, w): fp32 master copy, not quantized */
     for (uint64_t i = 0; i < n; ++i) w_master[i] = fmaf(-lr, mom[i], w_master[i]);
 
-    /* w_q = Qw(w) */
+    /* w_q = Qw(w); when w_q is w_master itself the weights are kept in the weight format */
     if (w_q) {
-        memcpy(w_q, w_master, (size_t)n * sizeof(float));
+        if (w_q != w_master) memcpy(w_q, w_master, (size_t)n * sizeof(float));
         quantize_array(w_q, n, fmt_weight, seed, stream_id, 2);
     }
     return QSIM_REF_OK;

@@ -85,7 +85,8 @@
  *     gq = Qg(grad[i])
  *     v  = Qm(fma(momentum, mom[i], gq));        mom[i] = v
  *     w  = fma(-lr, v, w_master[i]);             w_master[i] = w   (fp32 master copy)
- *     w_q[i] = Qw(w)                             (skipped when w_q is NULL)
+ *     w_q[i] = Qw(w)                             (skipped when w_q is NULL; w_q may be w_master
+ *                                                itself: then the weights are kept quantized)
  * No dampening, Nesterov or weight decay.  A block-kind format uses contiguous chunks of L
  * elements of the array it quantizes (for Qm the array of fma results, for Qw the updated w).
  *

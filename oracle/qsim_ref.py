@@ -171,12 +171,14 @@ def block_exponents(x, outer, nblocks, inner) -> np.ndarray:
 
 
 def quant_sgd_step(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format,
-                   fmt_weight: Format, seed=0, stream_id=0, want_wq=True):
-    """Returns (w_master', w_q or None, mom') as new arrays; the inputs are left untouched."""
+                   fmt_weight: Format, seed=0, stream_id=0, want_wq=True, in_place_weights=False):
+    """Returns (w_master', w_q or None, mom') as new arrays; the inputs are left untouched.
+    ``in_place_weights``: pass w_master as w_q too (the returned w_q is then w_master')."""
     w = _f32(w_master).reshape(-1).copy()
     g = _f32(grad).reshape(-1)
     m = _f32(mom).reshape(-1).copy()
-    wq = np.empty_like(w) if want_wq else None
+    wq = w if in_place_weights else (np.empty_like(w) if want_wq else None)
+    want_wq = want_wq or in_place_weights
     null = ctypes.POINTER(ctypes.c_float)()
     _check(lib().qsim_ref_quant_sgd_step(_ptr(w), _ptr(wq) if want_wq else null, _ptr(g), _ptr(m),
                                          w.size, lr, momentum, ctypes.byref(fmt_grad),

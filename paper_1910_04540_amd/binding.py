@@ -20,7 +20,7 @@ KIND_IDENTITY, KIND_FLOAT, KIND_FIXED, KIND_BLOCK = 0, 1, 2, 3
 
 # Every symbol include/qsim.h declares.
 EXPORTS = ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_block_workspace_bytes",
-           "qsim_set_barrier_wait_us", "qsim_quant_sgd_step", "qsim_status_string")
+           "qsim_set_barrier_wait_us", "qsim_quant_sgd_step", "qsim_quant_sgd_step_multi", "qsim_status_string")
 
 
 class Format(ctypes.Structure):
@@ -55,6 +55,11 @@ def lib() -> ctypes.CDLL:
     L.qsim_quant_sgd_step.argtypes = [vp, vp, vp, vp, u64, ctypes.c_float, ctypes.c_float,
                                       ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
                                       u64, u32, vp]
+    pp = ctypes.POINTER(ctypes.c_void_p)
+    L.qsim_quant_sgd_step_multi.argtypes = [ci, pp, pp, pp, pp, ctypes.POINTER(u64), ctypes.c_float, ctypes.c_float,
+                                            ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
+                                            u64, u32, vp]
+    L.qsim_quant_sgd_step_multi.restype = ci
     L.qsim_set_barrier_wait_us.argtypes = [u32]
     L.qsim_set_barrier_wait_us.restype = None
     L.qsim_status_string.argtypes = [ci]
@@ -152,3 +157,24 @@ def quant_sgd_step(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom:
                                      grad.data_ptr(), mom.data_ptr(), n, lr, momentum, ctypes.byref(fmt_grad),
                                      ctypes.byref(fmt_mom), ctypes.byref(fmt_weight), seed, stream_id, _stream()))
     return w_q
+
+
+def quant_sgd_step_multi(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format,
+                         seed=0, stream_id=0, w_q=None):
+    """qsim_quant_sgd_step_multi over lists of tensors (``w_q``: None, or a list whose entries may be None)."""
+    k = len(w_master)
+    if len(grad) != k or len(mom) != k or (w_q is not None and len(w_q) != k):
+        raise ValueError("the tensor lists must have the same length")
+    for t in range(k):
+        _device_f32(w_master[t], "w_master")
+        _device_f32(grad[t], "grad")
+        _device_f32(mom[t], "mom")
+        n = w_master[t].numel()
+        if grad[t].numel() != n or mom[t].numel() != n or (w_q is not None and w_q[t] is not None
+                                                            and _device_f32(w_q[t], "w_q").numel() != n):
+            raise ValueError("all tensors of one parameter must have the same number of elements")
+    ptrs = lambda ts: (ctypes.c_void_p * k)(*[None if x is None else x.data_ptr() for x in ts])
+    sizes = (ctypes.c_uint64 * k)(*[x.numel() for x in w_master])
+    _check(lib().qsim_quant_sgd_step_multi(k, ptrs(w_master), ptrs(w_q) if w_q is not None else None, ptrs(grad),
+                                           ptrs(mom), sizes, lr, momentum, ctypes.byref(fmt_grad), ctypes.byref(fmt_mom),
+                                           ctypes.byref(fmt_weight), seed, stream_id, _stream()))

@@ -340,6 +340,19 @@ int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer,
     }
 }
 
+// Validation of one tensor of the SGD step.  w_q may be NULL or w_master itself.
+static int check_sgd_tensor(const float* w_master, const float* w_q, const float* grad, const float* mom, uint64_t n)
+{
+    if (n > kMaxElements) return QSIM_ERR_SHAPE;
+    if (n == 0) return QSIM_OK;
+    if (!w_master || !grad || !mom) return QSIM_ERR_NULL;
+    if (any_overlap(w_master, grad, n) || any_overlap(w_master, mom, n) || any_overlap(grad, mom, n))
+        return QSIM_ERR_OVERLAP;
+    if (w_q && (partial_overlap(w_q, w_master, n) || any_overlap(w_q, grad, n) || any_overlap(w_q, mom, n)))
+        return QSIM_ERR_OVERLAP;
+    return QSIM_OK;
+}
+
 int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n, float lr,
                         float momentum, const qsim_format* fmt_grad, const qsim_format* fmt_mom,
                         const qsim_format* fmt_weight, uint64_t seed, uint32_t stream_id, void* hip_stream)
@@ -349,13 +362,8 @@ int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* m
     if ((status = make_format_plan(fmt_grad, &fg)) != QSIM_OK) return status;
     if ((status = make_format_plan(fmt_mom, &fm)) != QSIM_OK) return status;
     if ((status = make_format_plan(fmt_weight, &fw)) != QSIM_OK) return status;
-    if (n > kMaxElements) return QSIM_ERR_SHAPE;
+    if ((status = check_sgd_tensor(w_master, w_q, grad, mom, n)) != QSIM_OK) return status;
     if (n == 0) return QSIM_OK;
-    if (!w_master || !grad || !mom) return QSIM_ERR_NULL;
-    if (any_overlap(w_master, grad, n) || any_overlap(w_master, mom, n) || any_overlap(grad, mom, n))
-        return QSIM_ERR_OVERLAP;
-    if (w_q && (any_overlap(w_q, w_master, n) || any_overlap(w_q, grad, n) || any_overlap(w_q, mom, n)))
-        return QSIM_ERR_OVERLAP;
     const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
     const uint64_t groups = (n + 3) / 4;
     const uint64_t tiles = (groups + kThreads - 1) / kThreads;
@@ -368,6 +376,65 @@ int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* m
         hipLaunchKernelGGL((sgd_step_kernel<false>), dim3(blocks), dim3(kThreads), 0, as_stream(hip_stream), u32(w_master),
                            u32(w_q), u32(grad), u32(mom), n, tiles, lr, momentum, fg, fm, fw, key);
     return launch_status();
+}
+
+int qsim_quant_sgd_step_multi(int ntensors, float* const* w_master, float* const* w_q, const float* const* grad,
+                              float* const* mom, const uint64_t* n, float lr, float momentum,
+                              const qsim_format* fmt_grad, const qsim_format* fmt_mom, const qsim_format* fmt_weight,
+                              uint64_t seed, uint32_t stream_id, void* hip_stream)
+{
+    FormatPlan fg, fm, fw;
+    int status;
+    if ((status = make_format_plan(fmt_grad, &fg)) != QSIM_OK) return status;
+    if ((status = make_format_plan(fmt_mom, &fm)) != QSIM_OK) return status;
+    if ((status = make_format_plan(fmt_weight, &fw)) != QSIM_OK) return status;
+    if (ntensors < 0) return QSIM_ERR_SHAPE;
+    if (ntensors == 0) return QSIM_OK;
+    if (!w_master || !grad || !mom || !n) return QSIM_ERR_NULL;
+    for (int t = 0; t < ntensors; ++t) {
+        status = check_sgd_tensor(w_master[t], w_q ? w_q[t] : nullptr, grad[t], mom[t], n[t]);
+        if (status != QSIM_OK) return status;
+    }
+    // one launch per batch of up to kMultiTensors consecutive non-empty tensors (fewer than 2^31
+    // tiles); entry c of a batch is tensor first + c, which is what the kernel adds to the stream
+    int t = 0;
+    while (t < ntensors) {
+        if (n[t] == 0) {
+            ++t;
+            continue;
+        }
+        MultiTensorTable tab;
+        memset(&tab, 0, sizeof(tab));
+        bool vec = true;
+        uint64_t tiles = 0;
+        const int first = t;
+        while (t < ntensors && tab.count < kMultiTensors && n[t] != 0) {
+            const uint64_t groups = (n[t] + 3) / 4;
+            const uint64_t mine = (groups + kThreads - 1) / kThreads;
+            if (tiles + mine > 0x7fffffffull) break;
+            const int c = tab.count++;
+            tab.w_master[c] = u32(w_master[t]);
+            tab.w_q[c] = w_q ? u32(w_q[t]) : nullptr;
+            tab.grad[c] = u32(grad[t]);
+            tab.mom[c] = u32(mom[t]);
+            tab.n[c] = n[t];
+            tab.first_tile[c] = (uint32_t)tiles;
+            tiles += mine;
+            tab.first_tile[c + 1] = (uint32_t)tiles;
+            vec = vec && aligned16(w_master[t]) && aligned16(grad[t]) && aligned16(mom[t]) && (!tab.w_q[c] || aligned16(tab.w_q[c]));
+            ++t;
+        }
+        if (tab.count == 0) return QSIM_ERR_SHAPE;        // unreachable: one tensor has fewer than 2^31 tiles
+        const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id + (uint32_t)first};
+        if (vec)
+            hipLaunchKernelGGL((sgd_multi_kernel<true>), dim3((unsigned)tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, lr,
+                               momentum, fg, fm, fw, key);
+        else
+            hipLaunchKernelGGL((sgd_multi_kernel<false>), dim3((unsigned)tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, lr,
+                               momentum, fg, fm, fw, key);
+        if (hipGetLastError() != hipSuccess) return QSIM_ERR_LAUNCH;
+    }
+    return QSIM_OK;
 }
 
 void qsim_set_barrier_wait_us(uint32_t microseconds) { g_barrier_wait_us.store(microseconds, std::memory_order_relaxed); }

@@ -745,6 +745,39 @@ __device__ __forceinline__ uint32_t fma_bits(float a, uint32_t b, uint32_t c)
     return __float_as_uint(__builtin_fmaf(a, __uint_as_float(b), __uint_as_float(c)));
 }
 
+// One tile of 1024 elements of one tensor.  Called by every thread of the workgroup (a block kind
+// synchronises inside); groups past the end of the array load zeros and store nothing.
+// `w_q` may be NULL (no quantized copy) or equal to `w_master` (the weights themselves are kept in
+// the weight format: only the quantized value is stored).
+template <bool VEC>
+__device__ __forceinline__ void sgd_tile(uint32_t* w_master, uint32_t* w_q, const uint32_t* grad, uint32_t* mom, uint64_t n,
+                                         uint64_t tile, float lr, float momentum, const FormatPlan& fg, const FormatPlan& fm,
+                                         const FormatPlan& fw, const RngKey& key, uint32_t* lds)
+{
+    const uint64_t j = tile * kThreads + threadIdx.x;
+    const uint4 g = load_group<VEC>(grad, j, n);
+    const uint4 v = load_group<VEC>(mom, j, n);
+    const uint4 w = load_group<VEC>(w_master, j, n);
+
+    const uint4 gq = apply_format(fg, g, j, key, 0u, lds);
+    uint4 t;
+    t.x = fma_bits(momentum, v.x, gq.x);
+    t.y = fma_bits(momentum, v.y, gq.y);
+    t.z = fma_bits(momentum, v.z, gq.z);
+    t.w = fma_bits(momentum, v.w, gq.w);
+    const uint4 vq = apply_format(fm, t, j, key, 1u, lds);
+    uint4 wn;
+    wn.x = fma_bits(-lr, vq.x, w.x);
+    wn.y = fma_bits(-lr, vq.y, w.y);
+    wn.z = fma_bits(-lr, vq.z, w.z);
+    wn.w = fma_bits(-lr, vq.w, w.w);
+    // elements past the end are zero up to here (zero loads, and every quantizer maps zero to
+    // zero), so they cannot disturb a chunk maximum
+    store_group<VEC>(mom, j, n, vq);
+    if (w_q != w_master) store_group<VEC>(w_master, j, n, wn);
+    if (w_q) store_group<VEC>(w_q, j, n, apply_format(fw, wn, j, key, 2u, lds));
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void sgd_step_kernel(uint32_t* w_master, uint32_t* w_q, const uint32_t* grad,
                                                             uint32_t* mom, uint64_t n, uint64_t tiles, float lr,
@@ -753,46 +786,39 @@ __global__ __launch_bounds__(kThreads) void sgd_step_kernel(uint32_t* w_master, 
 {
     __shared__ uint32_t lds[kThreads / 64];
     // every thread of a workgroup runs the same number of tiles, so the barriers inside
-    // apply_format are reached by all of them; groups past the end load zeros and store nothing
-    for (uint64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-        const uint64_t j = tile * kThreads + threadIdx.x;
-        const uint4 g = load_group<VEC>(grad, j, n);
-        const uint4 v = load_group<VEC>(mom, j, n);
-        const uint4 w = load_group<VEC>(w_master, j, n);
+    // apply_format are reached by all of them
+    for (uint64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x)
+        sgd_tile<VEC>(w_master, w_q, grad, mom, n, tile, lr, momentum, fg, fm, fw, key, lds);
+}
 
-        const uint4 gq = apply_format(fg, g, j, key, 0u, lds);
-        uint4 t;
-        t.x = fma_bits(momentum, v.x, gq.x);
-        t.y = fma_bits(momentum, v.y, gq.y);
-        t.z = fma_bits(momentum, v.z, gq.z);
-        t.w = fma_bits(momentum, v.w, gq.w);
-        // elements past the end must not disturb a chunk maximum: they are forced to zero
-        const uint64_t i = j * 4;
-        if (i + 4 > n) {
-            if (i + 0 >= n) t.x = 0u;
-            if (i + 1 >= n) t.y = 0u;
-            if (i + 2 >= n) t.z = 0u;
-            if (i + 3 >= n) t.w = 0u;
-        }
-        const uint4 vq = apply_format(fm, t, j, key, 1u, lds);
-        uint4 wn;
-        wn.x = fma_bits(-lr, vq.x, w.x);
-        wn.y = fma_bits(-lr, vq.y, w.y);
-        wn.z = fma_bits(-lr, vq.z, w.z);
-        wn.w = fma_bits(-lr, vq.w, w.w);
-        if (i + 4 > n) {
-            if (i + 0 >= n) wn.x = 0u;
-            if (i + 1 >= n) wn.y = 0u;
-            if (i + 2 >= n) wn.z = 0u;
-            if (i + 3 >= n) wn.w = 0u;
-        }
-        store_group<VEC>(mom, j, n, vq);
-        store_group<VEC>(w_master, j, n, wn);
-        if (w_q) {
-            const uint4 wq = apply_format(fw, wn, j, key, 2u, lds);
-            store_group<VEC>(w_q, j, n, wq);
-        }
-    }
+// The same step over a list of tensors in one launch (a model's parameter tensors are many and
+// mostly small, so one launch per tensor would be bound by launch latency).  The table travels in
+// the kernel arguments; workgroup `blockIdx.x` finds its tensor from the running tile counts.
+// Tensor t draws its random words from stream `key.stream_id + t`.
+constexpr int kMultiTensors = 32;
+
+struct MultiTensorTable {
+    uint32_t* w_master[kMultiTensors];
+    uint32_t* w_q[kMultiTensors];
+    const uint32_t* grad[kMultiTensors];
+    uint32_t* mom[kMultiTensors];
+    uint64_t n[kMultiTensors];
+    uint32_t first_tile[kMultiTensors + 1];     // running sum of tiles
+    int count;
+};
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void sgd_multi_kernel(MultiTensorTable tab, float lr, float momentum, FormatPlan fg,
+                                                             FormatPlan fm, FormatPlan fw, RngKey key)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    const uint32_t tile = blockIdx.x;
+    int t = 0;
+    while (t + 1 < tab.count && tile >= tab.first_tile[t + 1]) ++t;     // wave-uniform scan of at most 32 entries
+    RngKey k = key;
+    k.stream_id = key.stream_id + (uint32_t)t;
+    sgd_tile<VEC>(tab.w_master[t], tab.w_q[t], tab.grad[t], tab.mom[t], tab.n[t], tile - tab.first_tile[t], lr, momentum, fg,
+                  fm, fw, k, lds);
 }
 
 }  // namespace qsim

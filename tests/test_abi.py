@@ -98,5 +98,30 @@ def test_sgd_validation_without_gpu():
     assert call(fm=B.Format(2, 8, 6, 7, 0)) == 3
     assert call(w=None) == 1 and call(g=None) == 1 and call(m=None) == 1
     assert call(g=FAKE) == 5 and call(m=FAKE + 8) == 5 and call(q=FAKE + (3 << 20)) == 5
+    assert call(q=FAKE + 16) == 5                    # w_q may be w_master itself, but not a shifted copy of it
     assert L.qsim_quant_sgd_step(FAKE, None, FAKE + 4096, FAKE + 8192, 64, 0.1, 0.9, None, ctypes.byref(ident),
                                  ctypes.byref(ident), 0, 0, None) == 1
+
+
+def test_sgd_multi_validation_without_gpu():
+    L = B.lib()
+    ident = B.Format(0, 0, 0, 0, 0)
+    vp = ctypes.c_void_p
+
+    def call(ws, gs, ms, ns, qs=None, fmt=ident, count=None):
+        k = len(ns)
+        arr = lambda xs: (vp * k)(*xs) if xs is not None else None
+        return L.qsim_quant_sgd_step_multi(k if count is None else count, arr(ws), arr(qs), arr(gs), arr(ms),
+                                           (ctypes.c_uint64 * k)(*ns), 0.1, 0.9, ctypes.byref(fmt), ctypes.byref(fmt),
+                                           ctypes.byref(fmt), 0, 0, None)
+
+    a, b, c = FAKE, FAKE + (1 << 20), FAKE + (2 << 20)
+    assert call([a], [b], [c], [0]) == 0                          # only empty tensors: nothing to launch
+    assert call([a, None], [b, None], [c, None], [0, 0]) == 0
+    assert call([a], [b], [c], [16], count=0) == 0
+    assert call([a], [b], [c], [16], count=-1) == 4
+    assert call([a, None], [b, b], [c, c], [0, 16]) == 1          # the second tensor has no weights
+    assert call([a, a], [b, a], [c, c], [0, 16]) == 5             # grad aliases the weights
+    assert call([a], [b], [c], [16], fmt=B.Format(3, 8, 100, 0, 0)) == 2
+    assert L.qsim_quant_sgd_step_multi(1, None, None, None, None, None, 0.1, 0.9, ctypes.byref(ident), ctypes.byref(ident),
+                                       ctypes.byref(ident), 0, 0, None) == 1

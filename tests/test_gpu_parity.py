@@ -347,6 +347,49 @@ def test_sgd_without_wq_and_misaligned():
     assert_bit_equal(host(md)[n:], m[n:], "outside mom")
 
 
+def test_sgd_weights_kept_in_the_weight_format():
+    n = 1024 * 4 + 99
+    w, g, m = W.sgd_state(n)
+    f = SGD_FORMATS[0]
+    fo = [_fmt(R, *x) for x in f]
+    fq = [_fmt(Q, *x) for x in f]
+    wr, _, mr = R.quant_sgd_step(w, g, m, 0.1, 0.9, fo[0], fo[1], fo[2], 7, 1, in_place_weights=True)
+    wd, gd, md = dev(w), dev(g), dev(m)
+    Q.quant_sgd_step(wd, gd, md, 0.1, 0.9, fq[0], fq[1], fq[2], 7, 1, w_q=wd)
+    assert_bit_equal(host(wd), wr, "weights stored in the weight format")
+    assert_bit_equal(host(md), mr, "momentum")
+
+
+@pytest.mark.parametrize("formats", [SGD_FORMATS[0], SGD_FORMATS[4], SGD_FORMATS[2]])
+def test_sgd_multi_tensor(formats):
+    """One call over a model-like list of tensors equals one oracle step per tensor with stream_id + t:
+    more than 32 tensors (several launches), empty ones, ragged sizes, an unaligned view, missing w_q."""
+    g0 = np.random.Generator(np.random.PCG64(3))
+    sizes = [int(v) for v in g0.integers(1, 5000, size=40)] + [0, 64, 1024, 4096, 0, 100000, 3, 147 * 64, 512 * 1024 + 5]
+    fo = [_fmt(R, *f) for f in formats]
+    fq = [_fmt(Q, *f) for f in formats]
+    hw, hg, hm, dw, dg, dm, dq = [], [], [], [], [], [], []
+    for t, n in enumerate(sizes):
+        w, g, m = W.sgd_state(n + 1, seeds=(100 + t, 200 + t, 300 + t))
+        off = 1 if t == 5 else 0                      # one tensor is a misaligned view
+        hw.append(w[off:off + n]), hg.append(g[off:off + n]), hm.append(m[off:off + n])
+        dw.append(dev(w)[off:off + n]), dg.append(dev(g)[off:off + n]), dm.append(dev(m)[off:off + n])
+        dq.append(None if t % 7 == 3 else torch.empty(n, device="cuda"))
+    Q.quant_sgd_step_multi(dw, dg, dm, 0.05, 0.9, fq[0], fq[1], fq[2], seed=1234, stream_id=10, w_q=dq)
+    for t, n in enumerate(sizes):
+        wr, wqr, mr = R.quant_sgd_step(hw[t], hg[t], hm[t], 0.05, 0.9, fo[0], fo[1], fo[2], 1234, 10 + t)
+        assert_bit_equal(host(dm[t]), mr, f"momentum of tensor {t} (n={n})")
+        assert_bit_equal(host(dw[t]), wr, f"weights of tensor {t} (n={n})")
+        if dq[t] is not None:
+            assert_bit_equal(host(dq[t]), wqr, f"quantized weights of tensor {t} (n={n})")
+    # no quantized copies at all
+    dw2 = [dev(x) for x in hw]
+    dm2 = [dev(x) for x in hm]
+    Q.quant_sgd_step_multi(dw2, dg, dm2, 0.05, 0.9, fq[0], fq[1], fq[2], seed=1234, stream_id=10)
+    for t in (0, 17, 40, 45, 48):
+        assert_bit_equal(host(dw2[t]), host(dw[t]), f"tensor {t} without w_q")
+
+
 # ------------------------------------------------------------------------------------------------
 # the benchmark's workloads at full size
 # ------------------------------------------------------------------------------------------------

@@ -86,6 +86,20 @@ def test_step_is_the_composition_of_the_pinned_quantizers(fg, fm, fw, n):
     assert_bit_equal(w3, w2, "w without w_q") and assert_bit_equal(m3, m2, "mom without w_q")
 
 
+def test_weights_kept_in_the_weight_format():
+    """w_q = w_master: the stored weights are Qw of the fp32 update, and the next step starts from them."""
+    w, g, m = W.sgd_state(777)
+    fg, fm, fw = R.Format(1, 5, 2, STOCHASTIC, SATURATE | SUBNORMAL), R.Format(2, 16, 12, STOCHASTIC, SATURATE), R.Format(3, 8, 64, RN_EVEN, 0)
+    w1, wq1, m1 = R.quant_sgd_step(w, g, m, 0.1, 0.9, fg, fm, fw, 5, 2)
+    a1, aq1, am1 = R.quant_sgd_step(w, g, m, 0.1, 0.9, fg, fm, fw, 5, 2, in_place_weights=True)
+    assert_bit_equal(a1, wq1, "stored weights are the quantized ones")
+    assert_bit_equal(am1, m1, "momentum unaffected")
+    assert aq1 is a1
+    a2, _, _ = R.quant_sgd_step(a1, g, am1, 0.1, 0.9, fg, fm, fw, 5, 3, in_place_weights=True)
+    w2, wq2, _ = R.quant_sgd_step(wq1, g, m1, 0.1, 0.9, fg, fm, fw, 5, 3)
+    assert_bit_equal(a2, wq2, "second step from quantized weights")
+
+
 def test_validation():
     w, g, m = W.sgd_state(64)
     bad = [R.Format(4, 0, 0, 0, 0), R.Format(1, 9, 2, 0, 0), R.Format(2, 30, 2, 0, 0), R.Format(3, 8, 100, 0, 0),
