@@ -195,6 +195,24 @@ def main() -> int:
             extra={"note": "grad float(5,2) stochastic, momentum fixed(16,12) stochastic, weight block8 per 256 nearest"})
         del sets
         torch.cuda.empty_cache()
+
+        # the same step over the 161 parameter tensors of a ResNet-50: one multi-tensor call against
+        # one call per tensor
+        sizes = W.resnet50_parameter_sizes()
+        total = sum(sizes)
+        flat = [torch.from_numpy(a[:total].copy()).cuda() for a in (w, g, m)] + [torch.empty(total, device="cuda")]
+        lists = [list(torch.split(f, sizes)) for f in flat]
+        table = Q.SgdTensorList(lists[0], lists[1], lists[2], lists[3])
+        run("quant_sgd_step_multi_resnet50_161_tensors", lambda k: table.step(0.1, 0.9, fg, fm, fw, 1234, k + 2), total,
+            bpe=SGD_BYTES_PER_PARAM, extra={"note": "one call, three launches of up to 64 tensors"})
+
+        def per_tensor(k):
+            for t in range(len(sizes)):
+                Q.quant_sgd_step(lists[0][t], lists[1][t], lists[2][t], 0.1, 0.9, fg, fm, fw, 1234, k + 2 + t, w_q=lists[3][t])
+
+        run("quant_sgd_step_per_tensor_resnet50_161_calls", per_tensor, total, bpe=SGD_BYTES_PER_PARAM)
+        del flat, lists
+        torch.cuda.empty_cache()
         result["formats"] = formats
 
     # ---- CPU baseline: the oracle as it stands, on the host cores ------------------------------

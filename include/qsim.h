@@ -151,7 +151,7 @@ int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* m
                         uint32_t stream_id, void* hip_stream);
 
 /*
- * The same step over `ntensors` tensors in one launch per 32 tensors (a model's parameters are many,
+ * The same step over `ntensors` tensors in one launch per 64 tensors (a model's parameters are many,
  * mostly small tensors; one launch each would be bound by launch latency).  w_master, w_q, grad,
  * mom and n are HOST arrays of `ntensors` device pointers / element counts; w_q may be NULL (no
  * quantized copies) and so may any of its entries.  Tensor t is processed exactly as

@@ -159,22 +159,37 @@ def quant_sgd_step(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom:
     return w_q
 
 
+class SgdTensorList:
+    """The pointer tables of qsim_quant_sgd_step_multi, marshalled once for a fixed list of tensors
+    (a model's parameters, gradients, momentum buffers and optional quantized copies), so that a
+    training loop pays for the conversion to C arrays once and not every step."""
+
+    def __init__(self, w_master, grad, mom, w_q=None):
+        k = len(w_master)
+        if len(grad) != k or len(mom) != k or (w_q is not None and len(w_q) != k):
+            raise ValueError("the tensor lists must have the same length")
+        for t in range(k):
+            _device_f32(w_master[t], "w_master")
+            _device_f32(grad[t], "grad")
+            _device_f32(mom[t], "mom")
+            n = w_master[t].numel()
+            if grad[t].numel() != n or mom[t].numel() != n or (w_q is not None and w_q[t] is not None
+                                                                and _device_f32(w_q[t], "w_q").numel() != n):
+                raise ValueError("all tensors of one parameter must have the same number of elements")
+        self._keep = (list(w_master), list(grad), list(mom), None if w_q is None else list(w_q))   # keeps the memory alive
+        ptrs = lambda ts: (ctypes.c_void_p * k)(*[None if x is None else x.data_ptr() for x in ts])
+        self.count = k
+        self.w_master, self.grad, self.mom = ptrs(w_master), ptrs(grad), ptrs(mom)
+        self.w_q = ptrs(w_q) if w_q is not None else None
+        self.sizes = (ctypes.c_uint64 * k)(*[x.numel() for x in w_master])
+
+    def step(self, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format, seed=0, stream_id=0) -> None:
+        _check(lib().qsim_quant_sgd_step_multi(self.count, self.w_master, self.w_q, self.grad, self.mom, self.sizes, lr,
+                                               momentum, ctypes.byref(fmt_grad), ctypes.byref(fmt_mom),
+                                               ctypes.byref(fmt_weight), seed, stream_id, _stream()))
+
+
 def quant_sgd_step_multi(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format,
                          seed=0, stream_id=0, w_q=None):
     """qsim_quant_sgd_step_multi over lists of tensors (``w_q``: None, or a list whose entries may be None)."""
-    k = len(w_master)
-    if len(grad) != k or len(mom) != k or (w_q is not None and len(w_q) != k):
-        raise ValueError("the tensor lists must have the same length")
-    for t in range(k):
-        _device_f32(w_master[t], "w_master")
-        _device_f32(grad[t], "grad")
-        _device_f32(mom[t], "mom")
-        n = w_master[t].numel()
-        if grad[t].numel() != n or mom[t].numel() != n or (w_q is not None and w_q[t] is not None
-                                                            and _device_f32(w_q[t], "w_q").numel() != n):
-            raise ValueError("all tensors of one parameter must have the same number of elements")
-    ptrs = lambda ts: (ctypes.c_void_p * k)(*[None if x is None else x.data_ptr() for x in ts])
-    sizes = (ctypes.c_uint64 * k)(*[x.numel() for x in w_master])
-    _check(lib().qsim_quant_sgd_step_multi(k, ptrs(w_master), ptrs(w_q) if w_q is not None else None, ptrs(grad),
-                                           ptrs(mom), sizes, lr, momentum, ctypes.byref(fmt_grad), ctypes.byref(fmt_mom),
-                                           ctypes.byref(fmt_weight), seed, stream_id, _stream()))
+    SgdTensorList(w_master, grad, mom, w_q).step(lr, momentum, fmt_grad, fmt_mom, fmt_weight, seed, stream_id)

@@ -795,7 +795,7 @@ __global__ __launch_bounds__(kThreads) void sgd_step_kernel(uint32_t* w_master, 
 // mostly small, so one launch per tensor would be bound by launch latency).  The table travels in
 // the kernel arguments; workgroup `blockIdx.x` finds its tensor from the running tile counts.
 // Tensor t draws its random words from stream `key.stream_id + t`.
-constexpr int kMultiTensors = 32;
+constexpr int kMultiTensors = 64;
 
 struct MultiTensorTable {
     uint32_t* w_master[kMultiTensors];
@@ -814,7 +814,7 @@ __global__ __launch_bounds__(kThreads) void sgd_multi_kernel(MultiTensorTable ta
     __shared__ uint32_t lds[kThreads / 64];
     const uint32_t tile = blockIdx.x;
     int t = 0;
-    while (t + 1 < tab.count && tile >= tab.first_tile[t + 1]) ++t;     // wave-uniform scan of at most 32 entries
+    while (t + 1 < tab.count && tile >= tab.first_tile[t + 1]) ++t;     // wave-uniform scan of at most 64 entries
     RngKey k = key;
     k.stream_id = key.stream_id + (uint32_t)t;
     sgd_tile<VEC>(tab.w_master[t], tab.w_q[t], tab.grad[t], tab.mom[t], tab.n[t], tile - tab.first_tile[t], lr, momentum, fg,

@@ -83,6 +83,25 @@ def sgd_state(n: int = N_PARAMS, seeds=(6, 7, 8)):
     return w.astype(np.float32), g.astype(np.float32), m.astype(np.float32)
 
 
+def resnet50_parameter_sizes() -> list:
+    """Element counts of the parameter tensors of a ResNet-50 (bottleneck stages of 3, 4, 6 and 3
+    blocks, widths 64 to 512 with expansion 4, batch-norm scale and shift after every convolution,
+    a 1000-way classifier): 161 tensors, 25,557,032 parameters.  Used to shape the multi-tensor
+    optimizer step like a real model: a few large tensors and many tiny ones."""
+    sizes = [64 * 3 * 7 * 7, 64, 64]
+    inplanes = 64
+    for planes, blocks in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for blk in range(blocks):
+            sizes += [planes * inplanes, planes, planes]                 # 1x1 reduce + norm
+            sizes += [planes * planes * 9, planes, planes]               # 3x3 + norm
+            sizes += [4 * planes * planes, 4 * planes, 4 * planes]       # 1x1 expand + norm
+            if blk == 0:
+                sizes += [4 * planes * inplanes, 4 * planes, 4 * planes]  # projection shortcut + norm
+            inplanes = 4 * planes
+    sizes += [1000 * 2048, 1000]
+    return sizes
+
+
 def all_exponents_probe(dropped_bits: int, seed: int = 11) -> np.ndarray:
     """Every (sign, exponent field, leading mantissa bits) combined with the low-bit patterns that
     decide a rounding (zero, one, just below/at/above half, all ones, a few random ones).
