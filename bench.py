@@ -153,6 +153,17 @@ def main() -> int:
         run("float_e5m2_nearest_even_1Mi", lambda k: Q.float_quantize(small, 5, 2, Q.RN_EVEN, Q.SATURATE, out=small_out),
             small.numel(), extra={"note": "launch-latency bound, cache resident"})
 
+        # the same small call captured 16 times in a HIP graph: what remains when launch overhead is amortised
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(16):
+                Q.float_quantize(small, 5, 2, Q.RN_EVEN, Q.SATURATE, out=small_out)
+        _, e = _time_launches(lambda k: graph.replay(), max(10, reps // 4), 10, torch)
+        name, d = _entry("float_e5m2_nearest_even_1Mi_in_a_graph_of_16", small.numel(), BYTES_PER_ELEMENT, e,
+                         max(10, reps // 4) * 16, {"note": "per call, graph replay; cache resident"})
+        formats[name] = d
+        del graph
+
         a_in, a_out = _rotating(W.relu_activations().reshape(-1), torch)
         na = a_in[0].numel()
         run("float_e8m7_stochastic_activations", lambda k: Q.float_quantize(

@@ -43,15 +43,15 @@
  * E exponent bits (2..8), M mantissa bits (1..23), IEEE-like layout: bias = 2^(E-1) - 1,
  * emax = bias, emin = 1 - bias (the all-ones exponent code is reserved, so that (5,10) is
  * binary16 and (8,7) is bfloat16, both named by the paper), maxval = (2 - 2^-M) * 2^emax.
- * The paper's bound "fewer than 8 / fewer than 23 bits" is read inclusively because it lists
- * bfloat16 (E = 8) as supported.
+ * The paper's bound (exponent below 8 bits, mantissa below 23) is read inclusively because it
+ * lists bfloat16 (E = 8) as supported.
  *     e = floor(log2 |x|)                      (true exponent, also for fp32 denormals)
  *     QSIM_SUBNORMAL set:   q = max(e, emin) - M      (gradual underflow)
  *     QSIM_SUBNORMAL clear: q = e - M; after rounding, a magnitude < 2^emin becomes zero
- *                           (the paper's default: denormals are not simulated)
+ *                           (the paper's default: it leaves denormals out)
  *     v = P(|x|, q) * 2^q                      (a carry into the next binade is automatic)
  *     QSIM_SATURATE set:   v > maxval  ->  v = maxval
- *     QSIM_SATURATE clear: the exponent is unbounded above (Inf is not simulated); only a
+ *     QSIM_SATURATE clear: the exponent is unbounded above (the paper has no Inf); only a
  *                          value above the carrier's largest finite number becomes +-Inf
  *     out = sign(x) * v
  *

@@ -1,0 +1,63 @@
+"""The entry points allocate nothing and never synchronise, so a sequence of calls can be captured
+in a HIP graph and replayed; every replay must give what eager calls give on the same inputs."""
+import numpy as np
+import pytest
+
+from helpers import assert_bit_equal
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from paper_1910_04540_amd import binding as Q       # noqa: E402
+from paper_1910_04540_amd import workloads as W     # noqa: E402
+
+
+def test_graph_replays_match_eager_calls():
+    if not torch.cuda.is_available():
+        pytest.fail("needs a GPU")
+    n, rows, cols = 50000, 24, 4096
+    nw = 1 << 18
+    x = torch.empty(n, device="cuda")
+    mat = torch.empty(rows * cols, device="cuda")
+    whole = torch.empty(nw, device="cuda")
+    w, g, m = (torch.empty(n, device="cuda") for _ in range(3))
+    out = {k: torch.empty_like(v) for k, v in (("fixed", x), ("float", x), ("rows", mat), ("whole", whole))}
+    wq = torch.empty(n, device="cuda")
+    ws = torch.empty(Q.block_workspace_bytes(nw, 1, 1, nw), dtype=torch.uint8, device="cuda")
+    fg, fm, fw = Q.Format(1, 5, 2, 3, 3), Q.Format(2, 16, 12, 3, 1), Q.Format(3, 8, 256, 0, 0)
+
+    def calls(o, wt, mt, wqt):
+        Q.fixed_quantize(x, 8, 6, Q.STOCHASTIC, Q.SATURATE, 1234, 1, out=o["fixed"])
+        Q.float_quantize(x, 5, 2, Q.RN_EVEN, Q.SATURATE | Q.SUBNORMAL, out=o["float"])
+        Q.block_quantize(mat, 1, rows, cols, 8, Q.STOCHASTIC, 0, 7, 2, out=o["rows"])
+        Q.block_quantize(whole, 1, 1, nw, 8, Q.STOCHASTIC, 0, 7, 3, out=o["whole"], workspace=ws)
+        Q.quant_sgd_step(wt, g, mt, 0.1, 0.9, fg, fm, fw, 99, 4, w_q=wqt)
+
+    def fill(seed):
+        x.copy_(torch.from_numpy(W.uniform_with_outliers(n, seed=seed)))
+        mat.copy_(torch.from_numpy(W.row_scaled_matrix(rows, cols, seed=seed + 1).reshape(-1)))
+        whole.copy_(torch.from_numpy(W.row_scaled_matrix(1, nw, seed=seed + 2).reshape(-1)))
+        a, b, c = W.sgd_state(n, seeds=(seed + 3, seed + 4, seed + 5))
+        w.copy_(torch.from_numpy(a)), g.copy_(torch.from_numpy(b)), m.copy_(torch.from_numpy(c))
+
+    fill(1)
+    calls(out, w.clone(), m.clone(), wq)            # warm-up outside the capture (first-use queries happen here)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        calls(out, w, m, wq)
+    for replay in range(3):
+        fill(10 * replay + 20)
+        w0, m0 = w.clone(), m.clone()
+        eager = {k: torch.empty_like(v) for k, v in out.items()}
+        ew, em, ewq = w0.clone(), m0.clone(), torch.empty_like(wq)
+        calls(eager, ew, em, ewq)                   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in out:
+            assert_bit_equal(out[k].cpu().numpy(), eager[k].cpu().numpy(), f"{k}, replay {replay}")
+        assert_bit_equal(w.cpu().numpy(), ew.cpu().numpy(), f"weights, replay {replay}")
+        assert_bit_equal(m.cpu().numpy(), em.cpu().numpy(), f"momentum, replay {replay}")
+        assert_bit_equal(wq.cpu().numpy(), ewq.cpu().numpy(), f"quantized weights, replay {replay}")
