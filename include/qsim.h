@@ -140,8 +140,8 @@ typedef struct {
  *     w_q[i]    = Qw(w)                              (skipped when w_q is NULL)
  * Both fma are single-rounding fp32 operations.  A block-kind format groups the array it
  * quantizes into contiguous chunks of L elements (the last may be short).  Random words use
- * role 0 for the gradient, 1 for the momentum and 2 for the weight.  No dampening, Nesterov
- * momentum or weight decay.  w_master and mom are updated in place; grad is read only.
+ * role 0 for the gradient, 1 for the momentum and 2 for the weight.  Weight decay, dampening and
+ * Nesterov momentum are in qsim_quant_sgd_step_ex.  w_master and mom are updated in place; grad is read only.
  * w_q may also be w_master itself: then no fp32 master copy is kept and the weights are stored in
  * the weight format (the accumulator is quantized, as the paper's optimizer does by default).
  */
@@ -163,6 +163,33 @@ int qsim_quant_sgd_step_multi(int ntensors, float* const* w_master, float* const
                               float momentum, const qsim_format* fmt_grad, const qsim_format* fmt_mom,
                               const qsim_format* fmt_weight, uint64_t seed, uint32_t stream_id,
                               void* hip_stream);
+
+/*
+ * The optional terms of PyTorch-style SGD in the fused step (NULL or all zero = the plain step).
+ * Each is one fp32 operation per element, placed between the quantizers as follows:
+ *     gq = Qg(grad[i])
+ *     d  = fma(weight_decay, w_master[i], gq)                    skipped when weight_decay == 0
+ *     v  = Qm(fma(momentum, mom[i], (1 - dampening) * d))        the product skipped when dampening == 0
+ *     w  = fma(-lr, nesterov ? fma(momentum, v, d) : v, w_master[i])
+ *     w_q[i] = Qw(w)
+ * 1 - dampening is formed in fp32.  Weight decay acts on the weight the optimizer holds (w_master).
+ */
+typedef struct {
+    float weight_decay;
+    float dampening;
+    int nesterov;       /* 0 or 1 */
+} qsim_sgd_options;
+
+int qsim_quant_sgd_step_ex(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n, float lr,
+                           float momentum, const qsim_sgd_options* options, const qsim_format* fmt_grad,
+                           const qsim_format* fmt_mom, const qsim_format* fmt_weight, uint64_t seed,
+                           uint32_t stream_id, void* hip_stream);
+int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* const* w_q,
+                                 const float* const* grad, float* const* mom, const uint64_t* n, float lr,
+                                 float momentum, const qsim_sgd_options* options,
+                                 const qsim_format* fmt_grad, const qsim_format* fmt_mom,
+                                 const qsim_format* fmt_weight, uint64_t seed, uint32_t stream_id,
+                                 void* hip_stream);
 
 /* Static description of a status code (never NULL). */
 const char* qsim_status_string(int status);

@@ -331,10 +331,10 @@ static void quantize_array(float* x, uint64_t n, const qsim_ref_format* f, uint6
     }
 }
 
-int qsim_ref_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n,
-                            float lr, float momentum, const qsim_ref_format* fmt_grad,
-                            const qsim_ref_format* fmt_mom, const qsim_ref_format* fmt_weight,
-                            uint64_t seed, uint32_t stream_id)
+int qsim_ref_quant_sgd_step_ex(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n,
+                               float lr, float momentum, const qsim_ref_sgd_options* opt,
+                               const qsim_ref_format* fmt_grad, const qsim_ref_format* fmt_mom,
+                               const qsim_ref_format* fmt_weight, uint64_t seed, uint32_t stream_id)
 {
     int status = QSIM_REF_OK;
     if (!valid_format(fmt_grad, &status) || !valid_format(fmt_mom, &status) ||
@@ -346,20 +346,35 @@ int qsim_ref_quant_sgd_step(float* w_master, float* w_q, const float* grad, floa
         return QSIM_REF_ERR_OVERLAP;
     if (w_q && (partial_overlap(w_q, w_master, n) || any_overlap(w_q, grad, n) || any_overlap(w_q, mom, n)))
         return QSIM_REF_ERR_OVERLAP;
+    const float weight_decay = opt ? opt->weight_decay : 0.0f;
+    const float dampening = opt ? opt->dampening : 0.0f;
+    const int nesterov = opt ? opt->nesterov : 0;
 
     /* gq = Qg(grad): the gradient array is an input only, so its quantized copy is a temporary */
-    float* gq = (float*)malloc((size_t)n * sizeof(float));
-    if (!gq) return QSIM_REF_ERR_ALLOC;
-    memcpy(gq, grad, (size_t)n * sizeof(float));
-    quantize_array(gq, n, fmt_grad, seed, stream_id, 0);
+    float* d = (float*)malloc((size_t)n * sizeof(float));
+    if (!d) return QSIM_REF_ERR_ALLOC;
+    memcpy(d, grad, (size_t)n * sizeof(float));
+    quantize_array(d, n, fmt_grad, seed, stream_id, 0);
 
-    /* v = Qm(fma(momentum, mom, gq)) */
-    for (uint64_t i = 0; i < n; ++i) mom[i] = fmaf(momentum, mom[i], gq[i]);
+    /* d = gq + weight_decay * w  (on the weight the optimizer holds) */
+    if (weight_decay != 0.0f)
+        for (uint64_t i = 0; i < n; ++i) d[i] = fmaf(weight_decay, w_master[i], d[i]);
+
+    /* v = Qm(momentum * v + (1 - dampening) * d) */
+    if (dampening != 0.0f) {
+        const float keep = 1.0f - dampening;
+        for (uint64_t i = 0; i < n; ++i) mom[i] = fmaf(momentum, mom[i], keep * d[i]);
+    } else {
+        for (uint64_t i = 0; i < n; ++i) mom[i] = fmaf(momentum, mom[i], d[i]);
+    }
     quantize_array(mom, n, fmt_mom, seed, stream_id, 1);
-    free(gq);
 
-    /* w = fma(-lr, v, w): fp32 master copy, not quantized */
-    for (uint64_t i = 0; i < n; ++i) w_master[i] = fmaf(-lr, mom[i], w_master[i]);
+    /* w = w - lr * v, or with Nesterov momentum w - lr * (d + momentum * v): fp32, not quantized */
+    if (nesterov)
+        for (uint64_t i = 0; i < n; ++i) w_master[i] = fmaf(-lr, fmaf(momentum, mom[i], d[i]), w_master[i]);
+    else
+        for (uint64_t i = 0; i < n; ++i) w_master[i] = fmaf(-lr, mom[i], w_master[i]);
+    free(d);
 
     /* w_q = Qw(w); when w_q is w_master itself the weights are kept in the weight format */
     if (w_q) {
@@ -367,4 +382,13 @@ int qsim_ref_quant_sgd_step(float* w_master, float* w_q, const float* grad, floa
         quantize_array(w_q, n, fmt_weight, seed, stream_id, 2);
     }
     return QSIM_REF_OK;
+}
+
+int qsim_ref_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n,
+                            float lr, float momentum, const qsim_ref_format* fmt_grad,
+                            const qsim_ref_format* fmt_mom, const qsim_ref_format* fmt_weight,
+                            uint64_t seed, uint32_t stream_id)
+{
+    return qsim_ref_quant_sgd_step_ex(w_master, w_q, grad, mom, n, lr, momentum, NULL, fmt_grad, fmt_mom,
+                                      fmt_weight, seed, stream_id);
 }

@@ -87,8 +87,13 @@
  *     w  = fma(-lr, v, w_master[i]);             w_master[i] = w   (fp32 master copy)
  *     w_q[i] = Qw(w)                             (skipped when w_q is NULL; w_q may be w_master
  *                                                itself: then the weights are kept quantized)
- * No dampening, Nesterov or weight decay.  A block-kind format uses contiguous chunks of L
- * elements of the array it quantizes (for Qm the array of fma results, for Qw the updated w).
+ * A block-kind format uses contiguous chunks of L elements of the array it quantizes (for Qm the
+ * array of fma results, for Qw the updated w).  The step follows the convention of PyTorch's SGD;
+ * its three optional terms (qsim_ref_sgd_options) are, each one fp32 operation per line:
+ *     d  = fma(weight_decay, w_master[i], gq)                 (weight decay, before the momentum)
+ *     v  = Qm(fma(momentum, mom[i], (1 - dampening) * d))     (dampening; 1 - dampening in fp32)
+ *     w  = fma(-lr, fma(momentum, v, d), w_master[i])         (Nesterov momentum)
+ * A term whose option is zero is skipped altogether (no multiplication by one, no addition of zero).
  *
  * Return value of every function: a QSIM_* status, 0 = success.  The validation rules are those
  * of the GPU library's header.
@@ -148,6 +153,17 @@ int qsim_ref_block_quantize(const float* in, float* out, uint64_t n, uint64_t ou
 int qsim_ref_block_exponents(const float* in, uint64_t n, uint64_t outer, uint64_t nblocks,
                              uint64_t inner, int* e_s);
 
+/* Options of the step; NULL means all zero (plain SGD with momentum). */
+typedef struct {
+    float weight_decay;   /* d = gq + weight_decay * w                              */
+    float dampening;      /* v = Qm(momentum * v + (1 - dampening) * d)             */
+    int nesterov;         /* w -= lr * (d + momentum * v)  instead of  w -= lr * v  */
+} qsim_ref_sgd_options;
+
+int qsim_ref_quant_sgd_step_ex(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n,
+                               float lr, float momentum, const qsim_ref_sgd_options* opt,
+                               const qsim_ref_format* fmt_grad, const qsim_ref_format* fmt_mom,
+                               const qsim_ref_format* fmt_weight, uint64_t seed, uint32_t stream_id);
 int qsim_ref_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n,
                             float lr, float momentum, const qsim_ref_format* fmt_grad,
                             const qsim_ref_format* fmt_mom, const qsim_ref_format* fmt_weight,

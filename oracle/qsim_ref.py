@@ -36,6 +36,10 @@ class Format(ctypes.Structure):
                 ("rounding", ctypes.c_int), ("flags", ctypes.c_uint32)]
 
 
+class SgdOptions(ctypes.Structure):
+    _fields_ = [("weight_decay", ctypes.c_float), ("dampening", ctypes.c_float), ("nesterov", ctypes.c_int)]
+
+
 _lib = None
 
 
@@ -67,8 +71,11 @@ def lib() -> ctypes.CDLL:
     L.qsim_ref_quant_sgd_step.argtypes = [fp, fp, fp, fp, u64, ctypes.c_float, ctypes.c_float,
                                           ctypes.POINTER(Format), ctypes.POINTER(Format),
                                           ctypes.POINTER(Format), u64, u32]
+    L.qsim_ref_quant_sgd_step_ex.argtypes = [fp, fp, fp, fp, u64, ctypes.c_float, ctypes.c_float,
+                                             ctypes.POINTER(SgdOptions), ctypes.POINTER(Format),
+                                             ctypes.POINTER(Format), ctypes.POINTER(Format), u64, u32]
     for name in ("float_quantize_at", "float_quantize", "fixed_quantize_at", "fixed_quantize",
-                 "block_quantize", "block_exponents", "quant_sgd_step"):
+                 "block_quantize", "block_exponents", "quant_sgd_step", "quant_sgd_step_ex"):
         getattr(L, "qsim_ref_" + name).restype = ci
     _lib = L
     return L
@@ -171,17 +178,20 @@ def block_exponents(x, outer, nblocks, inner) -> np.ndarray:
 
 
 def quant_sgd_step(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format,
-                   fmt_weight: Format, seed=0, stream_id=0, want_wq=True, in_place_weights=False):
+                   fmt_weight: Format, seed=0, stream_id=0, want_wq=True, in_place_weights=False,
+                   options: SgdOptions = None):
     """Returns (w_master', w_q or None, mom') as new arrays; the inputs are left untouched.
-    ``in_place_weights``: pass w_master as w_q too (the returned w_q is then w_master')."""
+    ``in_place_weights``: pass w_master as w_q too (the returned w_q is then w_master').
+    ``options``: weight decay, dampening, Nesterov momentum (None = plain step)."""
     w = _f32(w_master).reshape(-1).copy()
     g = _f32(grad).reshape(-1)
     m = _f32(mom).reshape(-1).copy()
     wq = w if in_place_weights else (np.empty_like(w) if want_wq else None)
     want_wq = want_wq or in_place_weights
     null = ctypes.POINTER(ctypes.c_float)()
-    _check(lib().qsim_ref_quant_sgd_step(_ptr(w), _ptr(wq) if want_wq else null, _ptr(g), _ptr(m),
-                                         w.size, lr, momentum, ctypes.byref(fmt_grad),
-                                         ctypes.byref(fmt_mom), ctypes.byref(fmt_weight), seed,
-                                         stream_id))
+    opt = ctypes.byref(options) if options is not None else None
+    _check(lib().qsim_ref_quant_sgd_step_ex(_ptr(w), _ptr(wq) if want_wq else null, _ptr(g), _ptr(m),
+                                            w.size, lr, momentum, opt, ctypes.byref(fmt_grad),
+                                            ctypes.byref(fmt_mom), ctypes.byref(fmt_weight), seed,
+                                            stream_id))
     return w, wq, m

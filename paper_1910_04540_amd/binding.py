@@ -20,13 +20,19 @@ KIND_IDENTITY, KIND_FLOAT, KIND_FIXED, KIND_BLOCK = 0, 1, 2, 3
 
 # Every symbol include/qsim.h declares.
 EXPORTS = ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_block_workspace_bytes",
-           "qsim_set_barrier_wait_us", "qsim_quant_sgd_step", "qsim_quant_sgd_step_multi", "qsim_status_string")
+           "qsim_set_barrier_wait_us", "qsim_quant_sgd_step", "qsim_quant_sgd_step_multi", "qsim_quant_sgd_step_ex",
+           "qsim_quant_sgd_step_multi_ex", "qsim_status_string")
 
 
 class Format(ctypes.Structure):
     """qsim_format: kind, a, b, rounding, flags."""
     _fields_ = [("kind", ctypes.c_int), ("a", ctypes.c_int), ("b", ctypes.c_int),
                 ("rounding", ctypes.c_int), ("flags", ctypes.c_uint32)]
+
+
+class SgdOptions(ctypes.Structure):
+    """qsim_sgd_options: weight_decay, dampening, nesterov."""
+    _fields_ = [("weight_decay", ctypes.c_float), ("dampening", ctypes.c_float), ("nesterov", ctypes.c_int)]
 
 
 class QsimError(RuntimeError):
@@ -60,6 +66,15 @@ def lib() -> ctypes.CDLL:
                                             ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
                                             u64, u32, vp]
     L.qsim_quant_sgd_step_multi.restype = ci
+    po = ctypes.POINTER(SgdOptions)
+    L.qsim_quant_sgd_step_ex.argtypes = [vp, vp, vp, vp, u64, ctypes.c_float, ctypes.c_float, po,
+                                         ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
+                                         u64, u32, vp]
+    L.qsim_quant_sgd_step_ex.restype = ci
+    L.qsim_quant_sgd_step_multi_ex.argtypes = [ci, pp, pp, pp, pp, ctypes.POINTER(u64), ctypes.c_float, ctypes.c_float, po,
+                                               ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
+                                               u64, u32, vp]
+    L.qsim_quant_sgd_step_multi_ex.restype = ci
     L.qsim_set_barrier_wait_us.argtypes = [u32]
     L.qsim_set_barrier_wait_us.restype = None
     L.qsim_status_string.argtypes = [ci]
@@ -145,17 +160,18 @@ def block_quantize(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed
 
 
 def quant_sgd_step(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format,
-                   seed=0, stream_id=0, w_q=None):
-    """qsim_quant_sgd_step: updates ``w_master`` and ``mom`` in place, fills ``w_q`` when given."""
+                   seed=0, stream_id=0, w_q=None, options: SgdOptions = None):
+    """qsim_quant_sgd_step(_ex): updates ``w_master`` and ``mom`` in place, fills ``w_q`` when given."""
     _device_f32(w_master, "w_master")
     _device_f32(grad, "grad")
     _device_f32(mom, "mom")
     n = w_master.numel()
     if grad.numel() != n or mom.numel() != n or (w_q is not None and _device_f32(w_q, "w_q").numel() != n):
         raise ValueError("all tensors of the step must have the same number of elements")
-    _check(lib().qsim_quant_sgd_step(w_master.data_ptr(), w_q.data_ptr() if w_q is not None else None,
-                                     grad.data_ptr(), mom.data_ptr(), n, lr, momentum, ctypes.byref(fmt_grad),
-                                     ctypes.byref(fmt_mom), ctypes.byref(fmt_weight), seed, stream_id, _stream()))
+    _check(lib().qsim_quant_sgd_step_ex(w_master.data_ptr(), w_q.data_ptr() if w_q is not None else None,
+                                        grad.data_ptr(), mom.data_ptr(), n, lr, momentum,
+                                        ctypes.byref(options) if options is not None else None, ctypes.byref(fmt_grad),
+                                        ctypes.byref(fmt_mom), ctypes.byref(fmt_weight), seed, stream_id, _stream()))
     return w_q
 
 
@@ -183,13 +199,15 @@ class SgdTensorList:
         self.w_q = ptrs(w_q) if w_q is not None else None
         self.sizes = (ctypes.c_uint64 * k)(*[x.numel() for x in w_master])
 
-    def step(self, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format, seed=0, stream_id=0) -> None:
-        _check(lib().qsim_quant_sgd_step_multi(self.count, self.w_master, self.w_q, self.grad, self.mom, self.sizes, lr,
-                                               momentum, ctypes.byref(fmt_grad), ctypes.byref(fmt_mom),
-                                               ctypes.byref(fmt_weight), seed, stream_id, _stream()))
+    def step(self, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format, seed=0, stream_id=0,
+             options: SgdOptions = None) -> None:
+        _check(lib().qsim_quant_sgd_step_multi_ex(self.count, self.w_master, self.w_q, self.grad, self.mom, self.sizes, lr,
+                                                  momentum, ctypes.byref(options) if options is not None else None,
+                                                  ctypes.byref(fmt_grad), ctypes.byref(fmt_mom), ctypes.byref(fmt_weight),
+                                                  seed, stream_id, _stream()))
 
 
 def quant_sgd_step_multi(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format,
-                         seed=0, stream_id=0, w_q=None):
-    """qsim_quant_sgd_step_multi over lists of tensors (``w_q``: None, or a list whose entries may be None)."""
-    SgdTensorList(w_master, grad, mom, w_q).step(lr, momentum, fmt_grad, fmt_mom, fmt_weight, seed, stream_id)
+                         seed=0, stream_id=0, w_q=None, options: SgdOptions = None):
+    """qsim_quant_sgd_step_multi(_ex) over lists of tensors (``w_q``: None, or a list whose entries may be None)."""
+    SgdTensorList(w_master, grad, mom, w_q).step(lr, momentum, fmt_grad, fmt_mom, fmt_weight, seed, stream_id, options)

@@ -353,9 +353,40 @@ static int check_sgd_tensor(const float* w_master, const float* w_q, const float
     return QSIM_OK;
 }
 
+static SgdHyper make_hyper(float lr, float momentum, const qsim_sgd_options* opt)
+{
+    SgdHyper h;
+    h.lr = lr;
+    h.momentum = momentum;
+    h.weight_decay = opt ? opt->weight_decay : 0.0f;
+    h.keep = 1.0f - (opt ? opt->dampening : 0.0f);
+    h.has_decay = (opt && opt->weight_decay != 0.0f) ? 1 : 0;
+    h.has_dampening = (opt && opt->dampening != 0.0f) ? 1 : 0;
+    h.nesterov = (opt && opt->nesterov) ? 1 : 0;
+    return h;
+}
+
 int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n, float lr,
                         float momentum, const qsim_format* fmt_grad, const qsim_format* fmt_mom,
                         const qsim_format* fmt_weight, uint64_t seed, uint32_t stream_id, void* hip_stream)
+{
+    return qsim_quant_sgd_step_ex(w_master, w_q, grad, mom, n, lr, momentum, nullptr, fmt_grad, fmt_mom, fmt_weight, seed,
+                                  stream_id, hip_stream);
+}
+
+int qsim_quant_sgd_step_multi(int ntensors, float* const* w_master, float* const* w_q, const float* const* grad,
+                              float* const* mom, const uint64_t* n, float lr, float momentum,
+                              const qsim_format* fmt_grad, const qsim_format* fmt_mom, const qsim_format* fmt_weight,
+                              uint64_t seed, uint32_t stream_id, void* hip_stream)
+{
+    return qsim_quant_sgd_step_multi_ex(ntensors, w_master, w_q, grad, mom, n, lr, momentum, nullptr, fmt_grad, fmt_mom,
+                                        fmt_weight, seed, stream_id, hip_stream);
+}
+
+int qsim_quant_sgd_step_ex(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n, float lr,
+                           float momentum, const qsim_sgd_options* options, const qsim_format* fmt_grad,
+                           const qsim_format* fmt_mom, const qsim_format* fmt_weight, uint64_t seed,
+                           uint32_t stream_id, void* hip_stream)
 {
     FormatPlan fg, fm, fw;
     int status;
@@ -369,19 +400,21 @@ int qsim_quant_sgd_step(float* w_master, float* w_q, const float* grad, float* m
     const uint64_t tiles = (groups + kThreads - 1) / kThreads;
     const unsigned blocks = (unsigned)(tiles < 0x7fffffffull ? tiles : 0x7fffffffull);
     const bool vec = aligned16(w_master) && aligned16(grad) && aligned16(mom) && (!w_q || aligned16(w_q));
+    const SgdHyper h = make_hyper(lr, momentum, options);
     if (vec)
         hipLaunchKernelGGL((sgd_step_kernel<true>), dim3(blocks), dim3(kThreads), 0, as_stream(hip_stream), u32(w_master),
-                           u32(w_q), u32(grad), u32(mom), n, tiles, lr, momentum, fg, fm, fw, key);
+                           u32(w_q), u32(grad), u32(mom), n, tiles, h, fg, fm, fw, key);
     else
         hipLaunchKernelGGL((sgd_step_kernel<false>), dim3(blocks), dim3(kThreads), 0, as_stream(hip_stream), u32(w_master),
-                           u32(w_q), u32(grad), u32(mom), n, tiles, lr, momentum, fg, fm, fw, key);
+                           u32(w_q), u32(grad), u32(mom), n, tiles, h, fg, fm, fw, key);
     return launch_status();
 }
 
-int qsim_quant_sgd_step_multi(int ntensors, float* const* w_master, float* const* w_q, const float* const* grad,
-                              float* const* mom, const uint64_t* n, float lr, float momentum,
-                              const qsim_format* fmt_grad, const qsim_format* fmt_mom, const qsim_format* fmt_weight,
-                              uint64_t seed, uint32_t stream_id, void* hip_stream)
+int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* const* w_q, const float* const* grad,
+                                 float* const* mom, const uint64_t* n, float lr, float momentum,
+                                 const qsim_sgd_options* options, const qsim_format* fmt_grad,
+                                 const qsim_format* fmt_mom, const qsim_format* fmt_weight, uint64_t seed,
+                                 uint32_t stream_id, void* hip_stream)
 {
     FormatPlan fg, fm, fw;
     int status;
@@ -395,6 +428,7 @@ int qsim_quant_sgd_step_multi(int ntensors, float* const* w_master, float* const
         status = check_sgd_tensor(w_master[t], w_q ? w_q[t] : nullptr, grad[t], mom[t], n[t]);
         if (status != QSIM_OK) return status;
     }
+    const SgdHyper h = make_hyper(lr, momentum, options);
     // one launch per batch of up to kMultiTensors consecutive non-empty tensors (fewer than 2^31
     // tiles); entry c of a batch is tensor first + c, which is what the kernel adds to the stream
     int t = 0;
@@ -427,11 +461,11 @@ int qsim_quant_sgd_step_multi(int ntensors, float* const* w_master, float* const
         if (tab.count == 0) return QSIM_ERR_SHAPE;        // unreachable: one tensor has fewer than 2^31 tiles
         const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id + (uint32_t)first};
         if (vec)
-            hipLaunchKernelGGL((sgd_multi_kernel<true>), dim3((unsigned)tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, lr,
-                               momentum, fg, fm, fw, key);
+            hipLaunchKernelGGL((sgd_multi_kernel<true>), dim3((unsigned)tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
+                               fg, fm, fw, key);
         else
-            hipLaunchKernelGGL((sgd_multi_kernel<false>), dim3((unsigned)tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, lr,
-                               momentum, fg, fm, fw, key);
+            hipLaunchKernelGGL((sgd_multi_kernel<false>), dim3((unsigned)tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
+                               fg, fm, fw, key);
         if (hipGetLastError() != hipSuccess) return QSIM_ERR_LAUNCH;
     }
     return QSIM_OK;

@@ -745,13 +745,25 @@ __device__ __forceinline__ uint32_t fma_bits(float a, uint32_t b, uint32_t c)
     return __float_as_uint(__builtin_fmaf(a, __uint_as_float(b), __uint_as_float(c)));
 }
 
+// Scalars of the step (Sec. 3.1 "Front-end interface": the optimizer update the quantizers wrap).
+struct SgdHyper {
+    float lr, momentum;
+    float weight_decay;   // used when has_decay
+    float keep;           // 1 - dampening in fp32, used when has_dampening
+    int has_decay, has_dampening, nesterov;
+};
+
 // One tile of 1024 elements of one tensor.  Called by every thread of the workgroup (a block kind
 // synchronises inside); groups past the end of the array load zeros and store nothing.
 // `w_q` may be NULL (no quantized copy) or equal to `w_master` (the weights themselves are kept in
 // the weight format: only the quantized value is stored).
+// Per element, every line one fp32 operation:
+//   gq = Qg(g);  d = fma(weight_decay, w, gq);  v = Qm(fma(momentum, v, keep * d));
+//   w = fma(-lr, nesterov ? fma(momentum, v, d) : v, w);  w_q = Qw(w)
+// where the weight-decay, dampening and Nesterov terms are skipped when their option is off.
 template <bool VEC>
 __device__ __forceinline__ void sgd_tile(uint32_t* w_master, uint32_t* w_q, const uint32_t* grad, uint32_t* mom, uint64_t n,
-                                         uint64_t tile, float lr, float momentum, const FormatPlan& fg, const FormatPlan& fm,
+                                         uint64_t tile, const SgdHyper& h, const FormatPlan& fg, const FormatPlan& fm,
                                          const FormatPlan& fw, const RngKey& key, uint32_t* lds)
 {
     const uint64_t j = tile * kThreads + threadIdx.x;
@@ -759,20 +771,39 @@ __device__ __forceinline__ void sgd_tile(uint32_t* w_master, uint32_t* w_q, cons
     const uint4 v = load_group<VEC>(mom, j, n);
     const uint4 w = load_group<VEC>(w_master, j, n);
 
-    const uint4 gq = apply_format(fg, g, j, key, 0u, lds);
-    uint4 t;
-    t.x = fma_bits(momentum, v.x, gq.x);
-    t.y = fma_bits(momentum, v.y, gq.y);
-    t.z = fma_bits(momentum, v.z, gq.z);
-    t.w = fma_bits(momentum, v.w, gq.w);
+    uint4 d = apply_format(fg, g, j, key, 0u, lds);
+    if (h.has_decay) {
+        d.x = fma_bits(h.weight_decay, w.x, d.x);
+        d.y = fma_bits(h.weight_decay, w.y, d.y);
+        d.z = fma_bits(h.weight_decay, w.z, d.z);
+        d.w = fma_bits(h.weight_decay, w.w, d.w);
+    }
+    uint4 t = d;
+    if (h.has_dampening) {
+        t.x = __float_as_uint(h.keep * __uint_as_float(d.x));
+        t.y = __float_as_uint(h.keep * __uint_as_float(d.y));
+        t.z = __float_as_uint(h.keep * __uint_as_float(d.z));
+        t.w = __float_as_uint(h.keep * __uint_as_float(d.w));
+    }
+    t.x = fma_bits(h.momentum, v.x, t.x);
+    t.y = fma_bits(h.momentum, v.y, t.y);
+    t.z = fma_bits(h.momentum, v.z, t.z);
+    t.w = fma_bits(h.momentum, v.w, t.w);
     const uint4 vq = apply_format(fm, t, j, key, 1u, lds);
+    uint4 step = vq;
+    if (h.nesterov) {
+        step.x = fma_bits(h.momentum, vq.x, d.x);
+        step.y = fma_bits(h.momentum, vq.y, d.y);
+        step.z = fma_bits(h.momentum, vq.z, d.z);
+        step.w = fma_bits(h.momentum, vq.w, d.w);
+    }
     uint4 wn;
-    wn.x = fma_bits(-lr, vq.x, w.x);
-    wn.y = fma_bits(-lr, vq.y, w.y);
-    wn.z = fma_bits(-lr, vq.z, w.z);
-    wn.w = fma_bits(-lr, vq.w, w.w);
-    // elements past the end are zero up to here (zero loads, and every quantizer maps zero to
-    // zero), so they cannot disturb a chunk maximum
+    wn.x = fma_bits(-h.lr, step.x, w.x);
+    wn.y = fma_bits(-h.lr, step.y, w.y);
+    wn.z = fma_bits(-h.lr, step.z, w.z);
+    wn.w = fma_bits(-h.lr, step.w, w.w);
+    // elements past the end are zero up to here (zero loads, and every operation above maps zeros
+    // to zero), so they cannot disturb a chunk maximum
     store_group<VEC>(mom, j, n, vq);
     if (w_q != w_master) store_group<VEC>(w_master, j, n, wn);
     if (w_q) store_group<VEC>(w_q, j, n, apply_format(fw, wn, j, key, 2u, lds));
@@ -780,15 +811,14 @@ __device__ __forceinline__ void sgd_tile(uint32_t* w_master, uint32_t* w_q, cons
 
 template <bool VEC>
 __global__ __launch_bounds__(kThreads) void sgd_step_kernel(uint32_t* w_master, uint32_t* w_q, const uint32_t* grad,
-                                                            uint32_t* mom, uint64_t n, uint64_t tiles, float lr,
-                                                            float momentum, FormatPlan fg, FormatPlan fm, FormatPlan fw,
-                                                            RngKey key)
+                                                            uint32_t* mom, uint64_t n, uint64_t tiles, SgdHyper h,
+                                                            FormatPlan fg, FormatPlan fm, FormatPlan fw, RngKey key)
 {
     __shared__ uint32_t lds[kThreads / 64];
     // every thread of a workgroup runs the same number of tiles, so the barriers inside
     // apply_format are reached by all of them
     for (uint64_t tile = blockIdx.x; tile < tiles; tile += gridDim.x)
-        sgd_tile<VEC>(w_master, w_q, grad, mom, n, tile, lr, momentum, fg, fm, fw, key, lds);
+        sgd_tile<VEC>(w_master, w_q, grad, mom, n, tile, h, fg, fm, fw, key, lds);
 }
 
 // The same step over a list of tensors in one launch (a model's parameter tensors are many and
@@ -808,8 +838,8 @@ struct MultiTensorTable {
 };
 
 template <bool VEC>
-__global__ __launch_bounds__(kThreads) void sgd_multi_kernel(MultiTensorTable tab, float lr, float momentum, FormatPlan fg,
-                                                             FormatPlan fm, FormatPlan fw, RngKey key)
+__global__ __launch_bounds__(kThreads) void sgd_multi_kernel(MultiTensorTable tab, SgdHyper h, FormatPlan fg, FormatPlan fm,
+                                                             FormatPlan fw, RngKey key)
 {
     __shared__ uint32_t lds[kThreads / 64];
     const uint32_t tile = blockIdx.x;
@@ -817,8 +847,8 @@ __global__ __launch_bounds__(kThreads) void sgd_multi_kernel(MultiTensorTable ta
     while (t + 1 < tab.count && tile >= tab.first_tile[t + 1]) ++t;     // wave-uniform scan of at most 64 entries
     RngKey k = key;
     k.stream_id = key.stream_id + (uint32_t)t;
-    sgd_tile<VEC>(tab.w_master[t], tab.w_q[t], tab.grad[t], tab.mom[t], tab.n[t], tile - tab.first_tile[t], lr, momentum, fg,
-                  fm, fw, k, lds);
+    sgd_tile<VEC>(tab.w_master[t], tab.w_q[t], tab.grad[t], tab.mom[t], tab.n[t], tile - tab.first_tile[t], h, fg, fm, fw, k,
+                  lds);
 }
 
 }  // namespace qsim

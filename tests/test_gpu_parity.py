@@ -347,6 +347,27 @@ def test_sgd_without_wq_and_misaligned():
     assert_bit_equal(host(md)[n:], m[n:], "outside mom")
 
 
+@pytest.mark.parametrize("wd,damp,nesterov", [(5e-4, 0.0, 0), (0.0, 0.25, 0), (0.0, 0.0, 1), (1e-2, 0.5, 1)])
+@pytest.mark.parametrize("formats", [SGD_FORMATS[0], SGD_FORMATS[2], SGD_FORMATS[4]])
+def test_sgd_options(formats, wd, damp, nesterov):
+    """Weight decay, dampening and Nesterov momentum, single tensor and multi-tensor."""
+    n = 1024 * 3 + 333
+    w, g, m = W.sgd_state(n)
+    fo = [_fmt(R, *f) for f in formats]
+    fq = [_fmt(Q, *f) for f in formats]
+    wr, wqr, mr = R.quant_sgd_step(w, g, m, 0.1, 0.9, fo[0], fo[1], fo[2], 1234, 6, options=R.SgdOptions(wd, damp, nesterov))
+    wd_, gd, md, qd = dev(w), dev(g), dev(m), torch.empty(n, device="cuda")
+    Q.quant_sgd_step(wd_, gd, md, 0.1, 0.9, fq[0], fq[1], fq[2], 1234, 6, w_q=qd, options=Q.SgdOptions(wd, damp, nesterov))
+    assert_bit_equal(host(md), mr, "momentum")
+    assert_bit_equal(host(wd_), wr, "weights")
+    assert_bit_equal(host(qd), wqr, "quantized weights")
+    # the same tensor as entry 1 of a list: stream 5 + 1
+    w2, g2, m2 = [dev(w[:100]), dev(w)], [dev(g[:100]), dev(g)], [dev(m[:100]), dev(m)]
+    Q.quant_sgd_step_multi(w2, g2, m2, 0.1, 0.9, fq[0], fq[1], fq[2], 1234, 5, options=Q.SgdOptions(wd, damp, nesterov))
+    assert_bit_equal(host(w2[1]), wr, "weights through the multi-tensor call")
+    assert_bit_equal(host(m2[1]), mr, "momentum through the multi-tensor call")
+
+
 def test_sgd_weights_kept_in_the_weight_format():
     n = 1024 * 4 + 99
     w, g, m = W.sgd_state(n)

@@ -100,6 +100,71 @@ def test_weights_kept_in_the_weight_format():
     assert_bit_equal(a2, wq2, "second step from quantized weights")
 
 
+@pytest.mark.parametrize("wd,damp,nesterov", [(5e-4, 0.0, 0), (0.0, 0.25, 0), (0.0, 0.0, 1), (5e-4, 0.0, 1), (1e-2, 0.5, 0)])
+def test_options_one_correctly_rounded_operation_per_line(wd, damp, nesterov):
+    """Weight decay, dampening and Nesterov momentum with identity formats, each line of the header
+    checked as a single correctly rounded fp32 operation in exact rational arithmetic."""
+    n = 300
+    w, g, m = W.sgd_state(n)
+    lr, mu = np.float32(0.1), np.float32(0.9)
+    F = f32_to_fraction
+    opt = R.SgdOptions(wd, damp, nesterov)
+    w2, _, m2 = R.quant_sgd_step(w, g, m, lr, mu, IDENT, IDENT, IDENT, options=opt)
+    wd32, keep = np.float32(wd), np.float32(np.float32(1.0) - np.float32(damp))
+    for i in range(n):
+        d = round_fraction_to_f32(F(wd32) * F(w[i]) + F(g[i])) if wd else g[i]
+        t = round_fraction_to_f32(F(keep) * F(d)) if damp else d
+        v = round_fraction_to_f32(F(mu) * F(m[i]) + F(t))
+        step = round_fraction_to_f32(F(mu) * F(v) + F(d)) if nesterov else v
+        wn = round_fraction_to_f32(F(w[i]) - F(lr) * F(step))
+        assert m2[i] == v and w2[i] == wn, (i, m2[i], v, w2[i], wn)
+
+
+@pytest.mark.parametrize("wd,damp,nesterov", [(0.0, 0.0, False), (5e-4, 0.0, False), (5e-4, 0.0, True), (1e-3, 0.3, False)])
+def test_options_follow_pytorch_sgd(wd, damp, nesterov):
+    """Five steps with identity formats track torch.optim.SGD (an independent implementation of the
+    same update rule) to within a few roundings: pins the order of the terms and their signs."""
+    torch = pytest.importorskip("torch")
+    n = 2000
+    w, _, _ = W.sgd_state(n)
+    p = torch.nn.Parameter(torch.from_numpy(w.copy()))
+    opt = torch.optim.SGD([p], lr=0.05, momentum=0.9, weight_decay=wd, dampening=damp, nesterov=nesterov)
+    wr, mr = w.copy(), np.zeros(n, dtype=np.float32)
+    for step in range(5):
+        g = W.sgd_state(n, seeds=(50 + step, 60 + step, 70 + step))[1] * np.float32(30.0)
+        p.grad = torch.from_numpy(g.copy())
+        opt.step()
+        if step == 0 and damp:
+            # PyTorch seeds the momentum buffer with the undamped gradient on its first step
+            mr = (g + np.float32(wd) * wr).astype(np.float32) if wd else g.copy()
+            wr = (wr - np.float32(0.05) * mr).astype(np.float32)
+            continue
+        wr, _, mr = R.quant_sgd_step(wr, g, mr, 0.05, 0.9, IDENT, IDENT, IDENT, options=R.SgdOptions(wd, damp, int(nesterov)),
+                                     want_wq=False)
+    np.testing.assert_allclose(wr, p.detach().numpy(), rtol=2e-5, atol=1e-7)
+    assert np.abs(wr - w).max() > 1e-3          # the weights did move
+
+
+def test_options_with_quantizers_compose():
+    """With formats, the options sit between the pinned quantizers exactly as the header says."""
+    n = 1500
+    w, g, m = W.sgd_state(n)
+    fg, fm, fw = R.Format(1, 5, 2, STOCHASTIC, SATURATE | SUBNORMAL), R.Format(2, 16, 12, STOCHASTIC, SATURATE), R.Format(3, 8, 256, RN_EVEN, 0)
+    lr, mu, wd, damp = np.float32(0.1), np.float32(0.9), np.float32(5e-4), np.float32(0.125)
+    F = f32_to_fraction
+    fma = lambda a, b, c: np.array([round_fraction_to_f32(F(a) * F(x) + F(y)) for x, y in zip(b, c)], dtype=np.float32)
+    gq = R.float_quantize(g, 5, 2, STOCHASTIC, SATURATE | SUBNORMAL, 9, 4)
+    d = fma(wd, w, gq)
+    t = (np.float32(np.float32(1) - damp) * d).astype(np.float32)
+    w2, wq, m2 = R.quant_sgd_step(w, g, m, lr, mu, fg, fm, fw, 9, 4, options=R.SgdOptions(wd, damp, 1))
+    words = R.random_words(9, 4, 1, n)
+    v = np.array([R.fixed_scalar(x, 16, 12, STOCHASTIC, SATURATE, int(r)) for x, r in zip(fma(mu, m, t), words)], dtype=np.float32)
+    assert_bit_equal(m2, v, "momentum")
+    wn = fma(-lr, fma(mu, v, d), w)
+    assert_bit_equal(w2, wn, "weights (Nesterov)")
+    assert_bit_equal(wq, R.block_quantize(wn, 1, (n + 255) // 256, 256, 8, RN_EVEN), "quantized weights")
+
+
 def test_validation():
     w, g, m = W.sgd_state(64)
     bad = [R.Format(4, 0, 0, 0, 0), R.Format(1, 9, 2, 0, 0), R.Format(2, 30, 2, 0, 0), R.Format(3, 8, 100, 0, 0),
