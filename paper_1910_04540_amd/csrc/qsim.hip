@@ -26,9 +26,9 @@ static int launch_elementwise_mode(const float* in, float* out, uint64_t n, cons
                                    hipStream_t stream)
 {
     const uint64_t groups = (n + 3) / 4;
-    const uint64_t blocks = (groups + kThreads * kUnroll - 1) / (kThreads * kUnroll);
-    hipLaunchKernelGGL((elementwise_kernel<Op, MODE, kUnroll>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, u32(in),
-                       u32(out), n, groups, op, key);
+    const uint64_t blocks = (groups + kStreamThreads * kUnroll - 1) / (kStreamThreads * kUnroll);
+    hipLaunchKernelGGL((elementwise_kernel<Op, MODE, kUnroll>), dim3((unsigned)blocks), dim3(kStreamThreads), 0, stream,
+                       u32(in), u32(out), n, groups, op, key);
     return launch_status();
 }
 
@@ -283,7 +283,8 @@ int qsim_float_quantize(const float* in, float* out, uint64_t n, int exp_bits, i
     hipStream_t stream = as_stream(hip_stream);
     if (!aligned16(in) || !aligned16(out)) return launch_elementwise_rt(in, out, n, f, key, stream);
     if (f.float_form == kFloatGeneral) return launch_elementwise(in, out, n, rounding, FloatGeneralOp{f.flt}, key, stream);
-    return launch_elementwise(in, out, n, rounding, FloatShiftOp{f.flt}, key, stream);
+    if (f.flt.denormal_inputs) return launch_elementwise(in, out, n, rounding, FloatShiftOp<true>{f.flt}, key, stream);
+    return launch_elementwise(in, out, n, rounding, FloatShiftOp<false>{f.flt}, key, stream);
 }
 
 int qsim_fixed_quantize(const float* in, float* out, uint64_t n, int wl, int fl, int rounding, uint32_t flags,

@@ -154,13 +154,15 @@ __device__ __forceinline__ uint32_t round_encoding(uint32_t mag, int drop, uint3
     return (mag + inc) & ~mask;
 }
 
-template <int MODE>
+// DENORMAL_INPUTS is a template parameter because the side path, once compiled in, is executed
+// under a lane mask for every element (about 40 instructions per group), denormal or not.
+template <int MODE, bool DENORMAL_INPUTS>
 __device__ __forceinline__ uint32_t quantize_float_shift(uint32_t bits, const FloatPlan& p, uint32_t r)
 {
     const uint32_t mag0 = bits & 0x7fffffffu;
     const uint32_t mag = mag0 < p.max_enc ? mag0 : p.max_enc;
     uint32_t res = p.drop ? round_encoding<MODE>(mag, p.drop, r) : mag;
-    if (p.denormal_inputs && mag - 1u < 0x7fffffu) {
+    if (DENORMAL_INPUTS && mag - 1u < 0x7fffffu) {
         // fp32 denormal: keep man_bits below the leading one of the fraction
         const int top = 31 - __builtin_clz(mag);
         const int s = top - p.man_bits;
@@ -215,11 +217,16 @@ __device__ __forceinline__ uint4 quantize_group_mode(const FormatPlan& f, const 
             o.y = quantize_float_general<MODE>(v.y, f.flt, r.w[1]);
             o.z = quantize_float_general<MODE>(v.z, f.flt, r.w[2]);
             o.w = quantize_float_general<MODE>(v.w, f.flt, r.w[3]);
+        } else if (f.flt.denormal_inputs) {
+            o.x = quantize_float_shift<MODE, true>(v.x, f.flt, r.w[0]);
+            o.y = quantize_float_shift<MODE, true>(v.y, f.flt, r.w[1]);
+            o.z = quantize_float_shift<MODE, true>(v.z, f.flt, r.w[2]);
+            o.w = quantize_float_shift<MODE, true>(v.w, f.flt, r.w[3]);
         } else {
-            o.x = quantize_float_shift<MODE>(v.x, f.flt, r.w[0]);
-            o.y = quantize_float_shift<MODE>(v.y, f.flt, r.w[1]);
-            o.z = quantize_float_shift<MODE>(v.z, f.flt, r.w[2]);
-            o.w = quantize_float_shift<MODE>(v.w, f.flt, r.w[3]);
+            o.x = quantize_float_shift<MODE, false>(v.x, f.flt, r.w[0]);
+            o.y = quantize_float_shift<MODE, false>(v.y, f.flt, r.w[1]);
+            o.z = quantize_float_shift<MODE, false>(v.z, f.flt, r.w[2]);
+            o.w = quantize_float_shift<MODE, false>(v.w, f.flt, r.w[3]);
         }
     } else {
         o.x = quantize_to_grid<MODE>(v.x, grid, r.w[0]);
