@@ -88,6 +88,9 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+    if not os.path.exists(Q.LIB_PATH):          # load what is built; build only when nothing is
+        from paper_1910_04540_amd import build as hip_build
+        hip_build.build()
     Q.lib()
     torch.cuda.set_device(0)
 
@@ -118,7 +121,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32",
+        "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": "fixed_point_quantize 64Mi fp32 (90% U[-4,4) + 10% N(0,sd 10)), wl=8 fl=6, "
                                "stochastic (Philox seed 1234), saturate", "elements": n,

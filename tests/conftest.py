@@ -16,3 +16,13 @@ def pytest_configure(config):
 @pytest.fixture(scope="session")
 def golden_dir():
     return os.path.join(ROOT, "tests", "golden")
+
+
+@pytest.fixture(scope="session", autouse=True)
+def _built_libraries():
+    """Tests load what is built; they build only when nothing is there (a fresh checkout keeps no
+    binaries).  The oracle's loader does the same for its own shared object."""
+    lib = os.path.join(ROOT, "paper_1910_04540_amd", "libqsim.so")
+    if not os.path.exists(lib):
+        from paper_1910_04540_amd import build as hip_build
+        hip_build.build()
