@@ -15,7 +15,7 @@
  *     `workspace`.
  *   - in == out (exactly the same array) is allowed; any other overlap between arrays of one
  *     call is rejected with QSIM_ERR_OVERLAP.
- *   - n == 0 is a successful no-op.  n is limited to 2^40 elements.
+ *   - n == 0 is a successful no-op.  n is limited to 2^38 elements.
  *   - Return value: a QSIM_* status; 0 = success.  Arguments are validated in the order
  *     rounding, format/flags, shape, n == 0, null pointers, overlap, workspace; nothing is
  *     launched when validation fails.  No exception or abort crosses this boundary.

@@ -17,6 +17,19 @@ static int launch_status() { return hipGetLastError() == hipSuccess ? QSIM_OK : 
 static const uint32_t* u32(const float* p) { return reinterpret_cast<const uint32_t*>(p); }
 static uint32_t* u32(float* p) { return reinterpret_cast<uint32_t*>(p); }
 
+// Grid of `blocks` workgroups folded over x and y (see linear_block()); blocks <= kGridX * 65535.
+static dim3 folded(uint64_t blocks)
+{
+    if (blocks <= kGridX) return dim3((unsigned)blocks);
+    return dim3(kGridX, (unsigned)((blocks + kGridX - 1) / kGridX));
+}
+// The same over x and z, with y given (see linear_block_xz()).
+static dim3 folded_xz(uint64_t blocks, unsigned y)
+{
+    if (blocks <= kGridX) return dim3((unsigned)blocks, y);
+    return dim3(kGridX, y, (unsigned)((blocks + kGridX - 1) / kGridX));
+}
+
 // Groups per thread of the elementwise kernels.
 constexpr int kUnroll = 1;
 
@@ -27,7 +40,7 @@ static int launch_elementwise_mode(const float* in, float* out, uint64_t n, cons
 {
     const uint64_t groups = (n + 3) / 4;
     const uint64_t blocks = (groups + kStreamThreads * kUnroll - 1) / (kStreamThreads * kUnroll);
-    hipLaunchKernelGGL((elementwise_kernel<Op, MODE, kUnroll>), dim3((unsigned)blocks), dim3(kStreamThreads), 0, stream,
+    hipLaunchKernelGGL((elementwise_kernel<Op, MODE, kUnroll>), folded(blocks), dim3(kStreamThreads), 0, stream,
                        u32(in), u32(out), n, groups, op, key);
     return launch_status();
 }
@@ -50,7 +63,7 @@ static int launch_elementwise_rt(const float* in, float* out, uint64_t n, const 
 {
     const uint64_t groups = (n + 3) / 4;
     const uint64_t blocks = (groups + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL(elementwise_rt_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, u32(in), u32(out), n,
+    hipLaunchKernelGGL(elementwise_rt_kernel, folded(blocks), dim3(kThreads), 0, stream, u32(in), u32(out), n,
                        groups, f, key);
     return launch_status();
 }
@@ -74,6 +87,7 @@ constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
 constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
 constexpr uint64_t kColumnThreads = 1ull << 19;  // threads the column form aims for
+constexpr uint64_t kMultiTiles = 1ull << 30;     // tiles of one multi-tensor launch (running counts are 32-bit)
 
 static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner)
 {
@@ -194,7 +208,7 @@ static void launch_block_cached(const uint32_t* in, uint32_t* out, const BlockGe
 {
     const uint64_t teams_per_wg = WHOLE ? 1 : (uint64_t)(kThreads >> team_log2);
     const uint64_t blocks = (g.nblocks + teams_per_wg - 1) / teams_per_wg;
-    hipLaunchKernelGGL((block_cached_kernel<MODE, GPT, WHOLE>), dim3((unsigned)blocks), dim3(kThreads), 0, stream, in, out, g,
+    hipLaunchKernelGGL((block_cached_kernel<MODE, GPT, WHOLE>), folded(blocks), dim3(kThreads), 0, stream, in, out, g,
                        team_log2, wl, symmetric, key);
 }
 
@@ -223,13 +237,13 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
             else if (per_lane <= 8) launch_block_cached<MODE, 8, true>(pin, pout, g, 8, wl, symmetric, key, stream);
             else launch_block_cached<MODE, 16, true>(pin, pout, g, 8, wl, symmetric, key, stream);
         } else {
-            hipLaunchKernelGGL((block_rows_kernel<MODE, false>), dim3((unsigned)g.nblocks), dim3(kThreads), 0, stream, pin,
+            hipLaunchKernelGGL((block_rows_kernel<MODE, false>), folded(g.nblocks), dim3(kThreads), 0, stream, pin,
                                pout, g, wl, symmetric, key);
         }
         return launch_status();
     }
     uint32_t* partial = reinterpret_cast<uint32_t*>(workspace);
-    const dim3 grid((unsigned)g.nblocks, s.sg.slices);
+    const dim3 grid = folded_xz(g.nblocks, s.sg.slices);
     if (vec && g.outer == 1) {
         // single pass when the blocks fit in the chip's registers, else the streaming two-pass form:
         // blocks on grid.y (folded when there are more than 65535), slices on grid.x
@@ -244,7 +258,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         uint32_t* blockmax = partial + (size_t)cg.slices * cg.row_groups * 4;
         const dim3 cgrid((cg.row_groups + kThreads - 1) / kThreads, cg.slices);
         hipLaunchKernelGGL(block_column_max_kernel, cgrid, dim3(kThreads), 0, stream, pin, colmax, cg);
-        hipLaunchKernelGGL(block_column_fold_kernel, dim3((cg.nblocks + kThreads / 64 - 1) / (kThreads / 64)), dim3(kThreads), 0,
+        hipLaunchKernelGGL(block_column_fold_kernel, folded((cg.nblocks + kThreads / 64 - 1) / (kThreads / 64)), dim3(kThreads), 0,
                            stream, partial, blockmax, cg);
         hipLaunchKernelGGL((block_column_apply_kernel<MODE>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax, cg, wl,
                            symmetric, key);
@@ -399,7 +413,7 @@ int qsim_quant_sgd_step_ex(float* w_master, float* w_q, const float* grad, float
     const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
     const uint64_t groups = (n + 3) / 4;
     const uint64_t tiles = (groups + kThreads - 1) / kThreads;
-    const unsigned blocks = (unsigned)(tiles < 0x7fffffffull ? tiles : 0x7fffffffull);
+    const unsigned blocks = (unsigned)(tiles < kGridX ? tiles : kGridX);       // the kernel strides over the tiles
     const bool vec = aligned16(w_master) && aligned16(grad) && aligned16(mom) && (!w_q || aligned16(w_q));
     const SgdHyper h = make_hyper(lr, momentum, options);
     if (vec)
@@ -446,7 +460,7 @@ int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* co
         while (t < ntensors && tab.count < kMultiTensors && n[t] != 0) {
             const uint64_t groups = (n[t] + 3) / 4;
             const uint64_t mine = (groups + kThreads - 1) / kThreads;
-            if (tiles + mine > 0x7fffffffull) break;
+            if (tiles + mine > kMultiTiles) break;
             const int c = tab.count++;
             tab.w_master[c] = u32(w_master[t]);
             tab.w_q[c] = w_q ? u32(w_q[t]) : nullptr;
@@ -459,13 +473,20 @@ int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* co
             vec = vec && aligned16(w_master[t]) && aligned16(grad[t]) && aligned16(mom[t]) && (!tab.w_q[c] || aligned16(tab.w_q[c]));
             ++t;
         }
-        if (tab.count == 0) return QSIM_ERR_SHAPE;        // unreachable: one tensor has fewer than 2^31 tiles
+        if (tab.count == 0) {
+            // a single tensor too large for a batch: the one-tensor kernel strides over its tiles
+            status = qsim_quant_sgd_step_ex(w_master[t], w_q ? w_q[t] : nullptr, grad[t], mom[t], n[t], lr, momentum, options,
+                                            fmt_grad, fmt_mom, fmt_weight, seed, stream_id + (uint32_t)t, hip_stream);
+            if (status != QSIM_OK) return status;
+            ++t;
+            continue;
+        }
         const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id + (uint32_t)first};
         if (vec)
-            hipLaunchKernelGGL((sgd_multi_kernel<true>), dim3((unsigned)tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
+            hipLaunchKernelGGL((sgd_multi_kernel<true>), folded(tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
                                fg, fm, fw, key);
         else
-            hipLaunchKernelGGL((sgd_multi_kernel<false>), dim3((unsigned)tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
+            hipLaunchKernelGGL((sgd_multi_kernel<false>), folded(tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
                                fg, fm, fw, key);
         if (hipGetLastError() != hipSuccess) return QSIM_ERR_LAUNCH;
     }

@@ -11,7 +11,7 @@
 
 namespace qsim {
 
-constexpr uint64_t kMaxElements = 1ull << 40;
+constexpr uint64_t kMaxElements = 1ull << 38;   // keeps every grid below 2^31 workgroups
 
 inline bool valid_rounding(int r) { return r >= QSIM_RN_EVEN && r <= QSIM_STOCHASTIC; }
 inline bool valid_flags(uint32_t f) { return (f & ~(QSIM_SATURATE | QSIM_SUBNORMAL | QSIM_SYMMETRIC)) == 0; }

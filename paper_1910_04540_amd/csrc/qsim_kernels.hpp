@@ -15,6 +15,13 @@ namespace qsim {
 
 constexpr int kThreads = 256;
 
+// A dispatch cannot hold 2^32 work-items or more in one dimension, so grids proportional to the
+// tensor are folded over x and y (over x and z where y already carries slices): x never exceeds
+// kGridX workgroups, and a kernel takes its workgroup number from linear_block().
+constexpr unsigned kGridX = 1u << 20;
+__device__ __forceinline__ uint64_t linear_block() { return (uint64_t)blockIdx.y * gridDim.x + blockIdx.x; }
+__device__ __forceinline__ uint64_t linear_block_xz() { return (uint64_t)blockIdx.z * gridDim.x + blockIdx.x; }
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint4 to_uint4(const u32x4& v) { return make_uint4(v.x, v.y, v.z, v.w); }
@@ -90,7 +97,7 @@ template <class Op, int MODE, int UNROLL>
 __global__ __launch_bounds__(kStreamThreads) void elementwise_kernel(const uint32_t* in, uint32_t* out, uint64_t n,
                                                                      uint64_t groups, Op op, RngKey key)
 {
-    const uint64_t base = (uint64_t)blockIdx.x * (kStreamThreads * UNROLL) + threadIdx.x;
+    const uint64_t base = linear_block() * (kStreamThreads * UNROLL) + threadIdx.x;
     uint4 v[UNROLL];
 #pragma unroll
     for (int k = 0; k < UNROLL; ++k) {
@@ -117,7 +124,7 @@ __global__ __launch_bounds__(kStreamThreads) void elementwise_kernel(const uint3
 __global__ __launch_bounds__(kThreads) void elementwise_rt_kernel(const uint32_t* in, uint32_t* out, uint64_t n,
                                                                   uint64_t groups, FormatPlan f, RngKey key)
 {
-    const uint64_t j = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+    const uint64_t j = linear_block() * kThreads + threadIdx.x;
     if (j >= groups) return;
     const uint4 v = load_group<false>(in, j, n);
     Words4 r = {{0u, 0u, 0u, 0u}};
@@ -172,7 +179,7 @@ __global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* 
     const int team = 1 << team_log2;
     const int teams_per_wg = WHOLE_WORKGROUP ? 1 : (kThreads >> team_log2);
     const int lane = WHOLE_WORKGROUP ? (int)threadIdx.x : ((int)threadIdx.x & (team - 1));
-    const uint64_t b = (uint64_t)blockIdx.x * teams_per_wg + (WHOLE_WORKGROUP ? 0 : ((int)threadIdx.x >> team_log2));
+    const uint64_t b = linear_block() * teams_per_wg + (WHOLE_WORKGROUP ? 0 : ((int)threadIdx.x >> team_log2));
     // a team past the last block keeps all its lanes running with nothing to load or store, so the
     // cross-lane operations below always see a full wavefront
     const uint64_t start = b < g.nblocks ? b * g.inner : g.n;
@@ -212,7 +219,8 @@ __global__ __launch_bounds__(kThreads) void block_rows_kernel(const uint32_t* in
                                                               int symmetric, RngKey key)
 {
     __shared__ uint32_t lds[kThreads / 64];
-    const uint64_t b = blockIdx.x;
+    const uint64_t b = linear_block();
+    if (b >= g.nblocks) return;                       // the whole workgroup leaves together
     const uint64_t start = b * g.inner;
     const uint64_t len = (g.n - start < g.inner) ? g.n - start : g.inner;
     uint32_t m = 0;
@@ -280,7 +288,8 @@ template <bool VEC>
 __global__ __launch_bounds__(kThreads) void block_partial_max_kernel(const uint32_t* in, uint32_t* partial, SliceGeom sg)
 {
     __shared__ uint32_t lds[kThreads / 64];
-    const uint64_t b = blockIdx.x;
+    const uint64_t b = linear_block_xz();
+    if (b >= sg.g.nblocks) return;                    // the whole workgroup leaves together
     const uint64_t len = block_length(sg, b);
     const uint64_t t0 = (uint64_t)blockIdx.y * sg.slice_len;
     const uint64_t t1 = (t0 + sg.slice_len < len) ? t0 + sg.slice_len : len;
@@ -309,7 +318,8 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
                                                                SliceGeom sg, int wl, int symmetric, RngKey key)
 {
     __shared__ uint32_t lds[kThreads / 64];
-    const uint64_t b = blockIdx.x;
+    const uint64_t b = linear_block_xz();
+    if (b >= sg.g.nblocks) return;                    // the whole workgroup leaves together
     uint32_t m = 0;
     for (uint32_t s = threadIdx.x; s < sg.slices; s += kThreads) {
         const uint32_t a = partial[b * sg.slices + s];
@@ -385,7 +395,7 @@ __global__ __launch_bounds__(kThreads) void block_column_max_kernel(const uint32
 // One wavefront per block: lanes stride over the block's slices * inner column maxima.
 __global__ __launch_bounds__(kThreads) void block_column_fold_kernel(const uint32_t* colmax, uint32_t* blockmax, ColumnGeom cg)
 {
-    const uint64_t b = (uint64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    const uint64_t b = linear_block() * (kThreads / 64) + (threadIdx.x >> 6);
     const uint32_t lane = threadIdx.x & 63;
     uint32_t m = 0;
     if (b < cg.nblocks) {
@@ -847,7 +857,8 @@ __global__ __launch_bounds__(kThreads) void sgd_multi_kernel(MultiTensorTable ta
                                                              FormatPlan fw, RngKey key)
 {
     __shared__ uint32_t lds[kThreads / 64];
-    const uint32_t tile = blockIdx.x;
+    const uint32_t tile = (uint32_t)linear_block();
+    if (tile >= tab.first_tile[tab.count]) return;     // the whole workgroup leaves together
     int t = 0;
     while (t + 1 < tab.count && tile >= tab.first_tile[t + 1]) ++t;     // wave-uniform scan of at most 64 entries
     RngKey k = key;

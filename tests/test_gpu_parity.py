@@ -88,6 +88,57 @@ def test_fixed_sizes_alignment_and_inplace(n):
         assert_bit_equal(full[off + n:], x[off + n:], "after the view")
 
 
+def test_indices_beyond_32_bits():
+    """2^34 + 4100 elements (64 GiB, quantized in place): element indices need 35 bits and the Philox
+    counter's high word becomes non-zero.  Checked on windows around the 2^32 and 2^34 boundaries and
+    at both ends against the oracle, which is given the window's offset."""
+    n = (1 << 34) + 4100
+    free, _ = torch.cuda.mem_get_info()
+    if free < n * 4 + (4 << 30):
+        pytest.skip("not enough free device memory for a 64 GiB tensor")
+    base = dev(W.uniform_with_outliers(1 << 26, seed=5))
+    x = torch.empty(n, device="cuda")
+    for k in range(n // base.numel()):
+        x[k * base.numel():(k + 1) * base.numel()] = base
+    x[(n // base.numel()) * base.numel():] = base[: n % base.numel()]
+    x[(1 << 32) - 5: (1 << 32) + 5] = torch.linspace(-2.5, 2.5, 10, device="cuda")
+    windows = [(0, 2048), ((1 << 32) - 1000, 2000), ((1 << 33) + 12345, 1111), ((1 << 34) - 3000, 3000 + 4100)]
+    before = [(o, host(x[o:o + c])) for o, c in windows]
+    Q.fixed_quantize(x, 8, 6, STOCHASTIC, SATURATE, seed=1234, stream_id=3, out=x)
+    lib = R.lib()
+    import ctypes
+    for o, inp in before:
+        want = np.empty_like(inp)
+        fp = ctypes.POINTER(ctypes.c_float)
+        assert lib.qsim_ref_fixed_quantize_at(inp.ctypes.data_as(fp), want.ctypes.data_as(fp), inp.size, o, 8, 6,
+                                              STOCHASTIC, SATURATE, 1234, 3) == 0
+        assert_bit_equal(host(x[o:o + inp.size]), want, f"window at {o}")
+    del x
+    torch.cuda.empty_cache()
+
+
+def test_many_small_blocks_beyond_32_bits():
+    """2^32 + 64 elements in chunks of 16 (268 million blocks, a grid folded over two dimensions),
+    nearest rounding in place; windows of whole chunks against the oracle."""
+    n = (1 << 32) + 64
+    free, _ = torch.cuda.mem_get_info()
+    if free < n * 4 + (4 << 30):
+        pytest.skip("not enough free device memory for a 16 GiB tensor")
+    g0 = np.random.Generator(np.random.PCG64(2))
+    base = dev((W.normal_tensor(1 << 24, seed=9) * np.exp2(g0.integers(-20, 20, 1 << 24))).astype(np.float32))
+    x = torch.empty(n, device="cuda")
+    for k in range(n // base.numel()):
+        x[k * base.numel():(k + 1) * base.numel()] = base
+    x[(n // base.numel()) * base.numel():] = base[: n % base.numel()]
+    windows = [(0, 1600), ((1 << 31) - 160, 320), ((1 << 32) - 1600, 1664)]
+    before = [(o, host(x[o:o + c])) for o, c in windows]
+    Q.block_quantize(x, 1, n // 16, 16, 8, RN_EVEN, out=x)
+    for o, inp in before:
+        assert_bit_equal(host(x[o:o + inp.size]), R.block_quantize(inp, 1, inp.size // 16, 16, 8, RN_EVEN), f"window at {o}")
+    del x
+    torch.cuda.empty_cache()
+
+
 def test_seed_and_stream_select_the_words():
     x = dev(W.uniform_with_outliers(1 << 14, seed=3))
     a = host(Q.fixed_quantize(x, 8, 6, STOCHASTIC, SATURATE, seed=1, stream_id=0))
