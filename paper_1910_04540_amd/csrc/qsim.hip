@@ -237,7 +237,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
             else if (per_lane <= 8) launch_block_cached<MODE, 8, true>(pin, pout, g, 8, wl, symmetric, key, stream);
             else launch_block_cached<MODE, 16, true>(pin, pout, g, 8, wl, symmetric, key, stream);
         } else {
-            hipLaunchKernelGGL((block_rows_kernel<MODE, false>), folded(g.nblocks), dim3(kThreads), 0, stream, pin,
+            hipLaunchKernelGGL((block_rows_kernel<MODE>), folded(g.nblocks), dim3(kThreads), 0, stream, pin,
                                pout, g, wl, symmetric, key);
         }
         return launch_status();

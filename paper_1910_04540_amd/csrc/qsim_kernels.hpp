@@ -212,9 +212,10 @@ __global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* 
     }
 }
 
-// One contiguous block per workgroup (outer == 1), any length and alignment: the block is read
-// twice by the same workgroup, the second time out of cache.
-template <int MODE, bool VEC>
+// One contiguous block of up to 16,384 elements per workgroup (outer == 1) when the arrays are not
+// aligned or the block length is not a multiple of four: dword accesses; the block is read twice by
+// the same workgroup, the second time out of cache.
+template <int MODE>
 __global__ __launch_bounds__(kThreads) void block_rows_kernel(const uint32_t* in, uint32_t* out, BlockGeom g, int wl,
                                                               int symmetric, RngKey key)
 {
@@ -224,37 +225,16 @@ __global__ __launch_bounds__(kThreads) void block_rows_kernel(const uint32_t* in
     const uint64_t start = b * g.inner;
     const uint64_t len = (g.n - start < g.inner) ? g.n - start : g.inner;
     uint32_t m = 0;
-    if (VEC) {
-        // start is a multiple of four, so groups are those of the whole array
-        const uint64_t j0 = start / 4, groups = (len + 3) / 4;
-        for (uint64_t t = threadIdx.x; t < groups; t += kThreads) {
-            const uint64_t i = (j0 + t) * 4;
-            uint4 v = {0u, 0u, 0u, 0u};
-            if (i + 4 <= start + len) v = *reinterpret_cast<const uint4*>(in + i);     // cached on purpose
-            else v = load_group<false>(in, j0 + t, start + len);
-            const uint32_t gm = max4_mag(v);
-            m = m > gm ? m : gm;
-        }
-        const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
-        for (uint64_t t = threadIdx.x; t < groups; t += kThreads) {
-            const uint64_t j = j0 + t;
-            const uint4 v = load_group<true>(in, j, start + len);
-            Words4 r = {{0u, 0u, 0u, 0u}};
-            if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
-            store_group<true>(out, j, start + len, quantize_group_to_grid<MODE>(v, p, r));
-        }
-    } else {
-        for (uint64_t t = threadIdx.x; t < len; t += kThreads) {
-            const uint32_t a = in[start + t] & 0x7fffffffu;
-            m = m > a ? m : a;
-        }
-        const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
-        for (uint64_t t = threadIdx.x; t < len; t += kThreads) {
-            const uint64_t i = start + t;
-            uint32_t r = 0;
-            if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
-            out[i] = quantize_to_grid<MODE>(in[i], p, r);
-        }
+    for (uint64_t t = threadIdx.x; t < len; t += kThreads) {
+        const uint32_t a = in[start + t] & 0x7fffffffu;
+        m = m > a ? m : a;
+    }
+    const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
+    for (uint64_t t = threadIdx.x; t < len; t += kThreads) {
+        const uint64_t i = start + t;
+        uint32_t r = 0;
+        if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
+        out[i] = quantize_to_grid<MODE>(in[i], p, r);
     }
 }
 
