@@ -190,12 +190,21 @@ __global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* 
     const int stride = WHOLE_WORKGROUP ? kThreads : team;
 
     uint4 v[GPT];
-    uint32_t m = 0;
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const int t = lane + k * stride;
         v[k] = make_uint4(0u, 0u, 0u, 0u);
         if (t < groups) v[k] = load_group<true>(in, j0 + t, end);
+    }
+    // stochastic rounding: the random words of the first groups are drawn while the loads are in
+    // flight (they do not depend on the data), the rest after the reduction
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 4 ? GPT : 4) : 0;
+    Words4 early[PRE > 0 ? PRE : 1];
+#pragma unroll
+    for (int k = 0; k < PRE; ++k) early[k] = random_words(j0 + (uint64_t)(lane + k * stride), key, 0u);
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
         const uint32_t gm = max4_mag(v[k]);
         m = m > gm ? m : gm;
     }
@@ -206,7 +215,8 @@ __global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* 
         const int t = lane + k * stride;
         if (t < groups) {
             Words4 r = {{0u, 0u, 0u, 0u}};
-            if (MODE == QSIM_STOCHASTIC) r = random_words(j0 + t, key, 0u);
+            if (k < PRE) r = early[k];
+            else if (MODE == QSIM_STOCHASTIC) r = random_words(j0 + t, key, 0u);
             store_group<true>(out, j0 + t, end, quantize_group_to_grid<MODE>(v[k], p, r));
         }
     }
