@@ -217,8 +217,10 @@ def main() -> int:
         flat = [torch.from_numpy(a[:total].copy()).cuda() for a in (w, g, m)] + [torch.empty(total, device="cuda")]
         lists = [list(torch.split(f, sizes)) for f in flat]
         table = Q.SgdTensorList(lists[0], lists[1], lists[2], lists[3])
-        run("quant_sgd_step_multi_resnet50_161_tensors", lambda k: table.step(0.1, 0.9, fg, fm, fw, 1234, k + 2), total,
-            bpe=SGD_BYTES_PER_PARAM, extra={"note": "one call, three launches of up to 64 tensors"})
+        run("quant_sgd_step_table_resnet50_161_tensors", lambda k: table.step(0.1, 0.9, fg, fm, fw, 1234, k + 2), total,
+            bpe=SGD_BYTES_PER_PARAM, extra={"note": "one call, one launch: the list is a table in device memory"})
+        run("quant_sgd_step_multi_resnet50_161_tensors", lambda k: table.step_batched(0.1, 0.9, fg, fm, fw, 1234, k + 2), total,
+            bpe=SGD_BYTES_PER_PARAM, extra={"note": "one call, three launches of up to 64 tensors (pointer arrays)"})
 
         def per_tensor(k):
             for t in range(len(sizes)):

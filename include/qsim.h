@@ -11,8 +11,8 @@
  *     (qsim_format) are HOST pointers, read before the call returns.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued on it and the call returns without synchronising.
- *   - The library allocates and frees nothing.  Scratch memory, where needed, is the caller's
- *     `workspace`.
+ *   - The library allocates and frees no device memory.  Scratch memory and tables, where needed,
+ *     are the caller's (`workspace`, `table_device`).
  *   - in == out (exactly the same array) is allowed; any other overlap between arrays of one
  *     call is rejected with QSIM_ERR_OVERLAP.
  *   - n == 0 is a successful no-op.  n is limited to 2^38 elements.
@@ -190,6 +190,44 @@ int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* co
                                  const qsim_format* fmt_grad, const qsim_format* fmt_mom,
                                  const qsim_format* fmt_weight, uint64_t seed, uint32_t stream_id,
                                  void* hip_stream);
+
+/*
+ * The same step over a FIXED list of tensors of any length in ONE launch (an optimizer steps the
+ * same parameter, gradient and momentum tensors every iteration): the list is written once into a
+ * table in device memory, and every later step only names the table.
+ *
+ *   qsim_sgd_table_bytes   size of the table for these element counts (0 for an empty list, and
+ *                          for a list qsim_sgd_table_build would reject with QSIM_ERR_SHAPE).
+ *   qsim_sgd_table_build   validates the list exactly as qsim_quant_sgd_step_multi does, writes the
+ *                          table into `table_device` (DEVICE memory of the caller, 16-byte aligned,
+ *                          at least qsim_sgd_table_bytes; else QSIM_ERR_WORKSPACE) with a copy on
+ *                          `hip_stream`, WAITS for that copy, and fills the host descriptor *table.
+ *                          More than 2^32 - 1 tiles of 1024 elements in total: QSIM_ERR_SHAPE.
+ *   qsim_quant_sgd_step_table   tensor t of the list is processed exactly as qsim_quant_sgd_step_ex
+ *                          would with stream_id + t (t counts empty tensors too), so the result is
+ *                          that of qsim_quant_sgd_step_multi_ex on the same list.
+ *
+ * The caller keeps the table's memory and the tensors alive and unchanged in place while the
+ * descriptor is in use; a descriptor not filled by qsim_sgd_table_build is QSIM_ERR_NULL /
+ * QSIM_ERR_WORKSPACE at best and undefined otherwise.  An empty list (or only empty tensors) builds
+ * a descriptor whose step is a no-op.
+ */
+typedef struct {
+    const void* device;     /* the table (device memory of the caller) */
+    size_t bytes;           /* its size */
+    uint32_t tiles;         /* workgroups of one step */
+    int32_t count;          /* non-empty tensors */
+    int32_t aligned;        /* 1 when every array is 16-byte aligned */
+} qsim_sgd_table;
+
+size_t qsim_sgd_table_bytes(int ntensors, const uint64_t* n);
+int qsim_sgd_table_build(int ntensors, float* const* w_master, float* const* w_q, const float* const* grad,
+                         float* const* mom, const uint64_t* n, void* table_device, size_t table_bytes,
+                         void* hip_stream, qsim_sgd_table* table);
+int qsim_quant_sgd_step_table(const qsim_sgd_table* table, float lr, float momentum,
+                              const qsim_sgd_options* options, const qsim_format* fmt_grad,
+                              const qsim_format* fmt_mom, const qsim_format* fmt_weight, uint64_t seed,
+                              uint32_t stream_id, void* hip_stream);
 
 /* Static description of a status code (never NULL). */
 const char* qsim_status_string(int status);

@@ -21,7 +21,8 @@ KIND_IDENTITY, KIND_FLOAT, KIND_FIXED, KIND_BLOCK = 0, 1, 2, 3
 # Every symbol include/qsim.h declares.
 EXPORTS = ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_block_workspace_bytes",
            "qsim_set_barrier_wait_us", "qsim_quant_sgd_step", "qsim_quant_sgd_step_multi", "qsim_quant_sgd_step_ex",
-           "qsim_quant_sgd_step_multi_ex", "qsim_status_string")
+           "qsim_quant_sgd_step_multi_ex", "qsim_sgd_table_bytes", "qsim_sgd_table_build", "qsim_quant_sgd_step_table",
+           "qsim_status_string")
 
 
 class Format(ctypes.Structure):
@@ -33,6 +34,12 @@ class Format(ctypes.Structure):
 class SgdOptions(ctypes.Structure):
     """qsim_sgd_options: weight_decay, dampening, nesterov."""
     _fields_ = [("weight_decay", ctypes.c_float), ("dampening", ctypes.c_float), ("nesterov", ctypes.c_int)]
+
+
+class SgdTable(ctypes.Structure):
+    """qsim_sgd_table: device, bytes, tiles, count, aligned."""
+    _fields_ = [("device", ctypes.c_void_p), ("bytes", ctypes.c_size_t), ("tiles", ctypes.c_uint32),
+                ("count", ctypes.c_int32), ("aligned", ctypes.c_int32)]
 
 
 class QsimError(RuntimeError):
@@ -75,6 +82,14 @@ def lib() -> ctypes.CDLL:
                                                ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
                                                u64, u32, vp]
     L.qsim_quant_sgd_step_multi_ex.restype = ci
+    L.qsim_sgd_table_bytes.argtypes = [ci, ctypes.POINTER(u64)]
+    L.qsim_sgd_table_bytes.restype = sz
+    L.qsim_sgd_table_build.argtypes = [ci, pp, pp, pp, pp, ctypes.POINTER(u64), vp, sz, vp, ctypes.POINTER(SgdTable)]
+    L.qsim_sgd_table_build.restype = ci
+    L.qsim_quant_sgd_step_table.argtypes = [ctypes.POINTER(SgdTable), ctypes.c_float, ctypes.c_float, po,
+                                            ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
+                                            u64, u32, vp]
+    L.qsim_quant_sgd_step_table.restype = ci
     L.qsim_set_barrier_wait_us.argtypes = [u32]
     L.qsim_set_barrier_wait_us.restype = None
     L.qsim_status_string.argtypes = [ci]
@@ -183,9 +198,13 @@ def quant_sgd_step(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom:
 
 
 class SgdTensorList:
-    """The pointer tables of qsim_quant_sgd_step_multi, marshalled once for a fixed list of tensors
-    (a model's parameters, gradients, momentum buffers and optional quantized copies), so that a
-    training loop pays for the conversion to C arrays once and not every step."""
+    """A fixed list of tensors (a model's parameters, gradients, momentum buffers and optional
+    quantized copies), marshalled once: the pointer arrays of qsim_quant_sgd_step_multi, and the
+    device table of qsim_sgd_table_build, so that a training loop pays for neither every step.
+
+    ``step`` is one launch for the whole list (qsim_quant_sgd_step_table); ``step_batched`` passes
+    the pointer arrays (qsim_quant_sgd_step_multi_ex, one launch per 64 tensors).  Both give the
+    same result."""
 
     def __init__(self, w_master, grad, mom, w_q=None):
         k = len(w_master)
@@ -205,9 +224,31 @@ class SgdTensorList:
         self.w_master, self.grad, self.mom = ptrs(w_master), ptrs(grad), ptrs(mom)
         self.w_q = ptrs(w_q) if w_q is not None else None
         self.sizes = (ctypes.c_uint64 * k)(*[x.numel() for x in w_master])
+        self.table = None            # built by the first step()
+        self._table_memory = None
+
+    def _build_table(self) -> None:
+        k = self.count
+        table = SgdTable()
+        need = int(lib().qsim_sgd_table_bytes(k, self.sizes))
+        if need:
+            self._table_memory = torch.empty(need, dtype=torch.uint8, device=self._keep[0][0].device)
+        _check(lib().qsim_sgd_table_build(k, self.w_master, self.w_q, self.grad, self.mom, self.sizes,
+                                          self._table_memory.data_ptr() if need else None, need, _stream(),
+                                          ctypes.byref(table)))
+        self.table = table
 
     def step(self, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format, seed=0, stream_id=0,
              options: SgdOptions = None) -> None:
+        if self.table is None:
+            self._build_table()
+        _check(lib().qsim_quant_sgd_step_table(ctypes.byref(self.table), lr, momentum,
+                                               ctypes.byref(options) if options is not None else None,
+                                               ctypes.byref(fmt_grad), ctypes.byref(fmt_mom), ctypes.byref(fmt_weight),
+                                               seed, stream_id, _stream()))
+
+    def step_batched(self, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format, seed=0, stream_id=0,
+                     options: SgdOptions = None) -> None:
         _check(lib().qsim_quant_sgd_step_multi_ex(self.count, self.w_master, self.w_q, self.grad, self.mom, self.sizes, lr,
                                                   momentum, ctypes.byref(options) if options is not None else None,
                                                   ctypes.byref(fmt_grad), ctypes.byref(fmt_mom), ctypes.byref(fmt_weight),
@@ -217,4 +258,4 @@ class SgdTensorList:
 def quant_sgd_step_multi(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format,
                          seed=0, stream_id=0, w_q=None, options: SgdOptions = None):
     """qsim_quant_sgd_step_multi(_ex) over lists of tensors (``w_q``: None, or a list whose entries may be None)."""
-    SgdTensorList(w_master, grad, mom, w_q).step(lr, momentum, fmt_grad, fmt_mom, fmt_weight, seed, stream_id, options)
+    SgdTensorList(w_master, grad, mom, w_q).step_batched(lr, momentum, fmt_grad, fmt_mom, fmt_weight, seed, stream_id, options)

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <vector>
 
 #include "qsim.h"
 #include "qsim_device.hpp"
@@ -491,6 +492,115 @@ int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* co
         if (hipGetLastError() != hipSuccess) return QSIM_ERR_LAUNCH;
     }
     return QSIM_OK;
+}
+
+// Tiles of one list, or 0 when a tensor or the total is too large.
+static bool table_tiles(int ntensors, const uint64_t* n, uint64_t* tiles, int* count)
+{
+    *tiles = 0;
+    *count = 0;
+    for (int t = 0; t < ntensors; ++t) {
+        if (n[t] > kMaxElements) return false;
+        if (n[t] == 0) continue;
+        *tiles += ((n[t] + 3) / 4 + kThreads - 1) / kThreads;
+        ++*count;
+    }
+    return *tiles <= 0xFFFFFFFFull;
+}
+
+static size_t table_owner_offset(int count) { return ((size_t)count * sizeof(SgdTableEntry) + 15) & ~(size_t)15; }
+
+size_t qsim_sgd_table_bytes(int ntensors, const uint64_t* n)
+{
+    uint64_t tiles;
+    int count;
+    if (ntensors <= 0 || !n || !table_tiles(ntensors, n, &tiles, &count) || count == 0) return 0;
+    return table_owner_offset(count) + (((size_t)tiles * sizeof(uint32_t) + 15) & ~(size_t)15);
+}
+
+int qsim_sgd_table_build(int ntensors, float* const* w_master, float* const* w_q, const float* const* grad,
+                         float* const* mom, const uint64_t* n, void* table_device, size_t table_bytes,
+                         void* hip_stream, qsim_sgd_table* table)
+{
+    if (!table) return QSIM_ERR_NULL;
+    memset(table, 0, sizeof(*table));
+    if (ntensors < 0) return QSIM_ERR_SHAPE;
+    if (ntensors == 0) return QSIM_OK;
+    if (!w_master || !grad || !mom || !n) return QSIM_ERR_NULL;
+    uint64_t tiles;
+    int count;
+    if (!table_tiles(ntensors, n, &tiles, &count)) return QSIM_ERR_SHAPE;
+    for (int t = 0; t < ntensors; ++t) {
+        const int status = check_sgd_tensor(w_master[t], w_q ? w_q[t] : nullptr, grad[t], mom[t], n[t]);
+        if (status != QSIM_OK) return status;
+    }
+    if (count == 0) return QSIM_OK;
+    const size_t need = qsim_sgd_table_bytes(ntensors, n);
+    if (!table_device || !aligned16(table_device) || table_bytes < need) return QSIM_ERR_WORKSPACE;
+
+    std::vector<unsigned char> host(need, 0);
+    SgdTableEntry* entries = reinterpret_cast<SgdTableEntry*>(host.data());
+    uint32_t* owner = reinterpret_cast<uint32_t*>(host.data() + table_owner_offset(count));
+    bool vec = true;
+    uint32_t tile = 0;
+    int c = 0;
+    for (int t = 0; t < ntensors; ++t) {
+        if (n[t] == 0) continue;
+        SgdTableEntry& e = entries[c];
+        e.w_master = u32(w_master[t]);
+        e.w_q = w_q ? u32(w_q[t]) : nullptr;
+        e.grad = u32(grad[t]);
+        e.mom = u32(mom[t]);
+        e.n = n[t];
+        e.first_tile = tile;
+        e.position = (uint32_t)t;
+        vec = vec && aligned16(w_master[t]) && aligned16(grad[t]) && aligned16(mom[t]) && (!e.w_q || aligned16(e.w_q));
+        const uint32_t mine = (uint32_t)(((n[t] + 3) / 4 + kThreads - 1) / kThreads);
+        for (uint32_t k = 0; k < mine; ++k) owner[tile + k] = (uint32_t)c;
+        tile += mine;
+        ++c;
+    }
+    // the host copy lives only until this function returns, so the copy is waited for
+    if (hipMemcpyAsync(table_device, host.data(), need, hipMemcpyHostToDevice, as_stream(hip_stream)) != hipSuccess ||
+        hipStreamSynchronize(as_stream(hip_stream)) != hipSuccess) {
+        (void)hipGetLastError();
+        return QSIM_ERR_LAUNCH;
+    }
+    table->device = table_device;
+    table->bytes = need;
+    table->tiles = (uint32_t)tiles;
+    table->count = count;
+    table->aligned = vec ? 1 : 0;
+    return QSIM_OK;
+}
+
+int qsim_quant_sgd_step_table(const qsim_sgd_table* table, float lr, float momentum, const qsim_sgd_options* options,
+                              const qsim_format* fmt_grad, const qsim_format* fmt_mom, const qsim_format* fmt_weight,
+                              uint64_t seed, uint32_t stream_id, void* hip_stream)
+{
+    FormatPlan fg, fm, fw;
+    int status;
+    if ((status = make_format_plan(fmt_grad, &fg)) != QSIM_OK) return status;
+    if ((status = make_format_plan(fmt_mom, &fm)) != QSIM_OK) return status;
+    if ((status = make_format_plan(fmt_weight, &fw)) != QSIM_OK) return status;
+    if (!table) return QSIM_ERR_NULL;
+    if (table->count == 0 || table->tiles == 0) return QSIM_OK;
+    if (!table->device) return QSIM_ERR_NULL;
+    if (table->count < 0 || !aligned16(table->device) ||
+        table->bytes < table_owner_offset(table->count) + (size_t)table->tiles * sizeof(uint32_t))
+        return QSIM_ERR_WORKSPACE;
+    const SgdHyper h = make_hyper(lr, momentum, options);
+    const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    const SgdTableEntry* entries = static_cast<const SgdTableEntry*>(table->device);
+    const uint32_t* owner =
+        reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(table->device) + table_owner_offset(table->count));
+    if (table->aligned)
+        hipLaunchKernelGGL((sgd_table_kernel<true>), folded(table->tiles), dim3(kThreads), 0, as_stream(hip_stream), entries,
+                           owner, table->tiles, h, fg, fm, fw, key);
+    else
+        hipLaunchKernelGGL((sgd_table_kernel<false>), folded(table->tiles), dim3(kThreads), 0, as_stream(hip_stream), entries,
+                           owner, table->tiles, h, fg, fm, fw, key);
+    return launch_status();
 }
 
 void qsim_set_barrier_wait_us(uint32_t microseconds) { g_barrier_wait_us.store(microseconds, std::memory_order_relaxed); }

@@ -857,4 +857,33 @@ __global__ __launch_bounds__(kThreads) void sgd_multi_kernel(MultiTensorTable ta
                   lds);
 }
 
+// The same step over a list of any length, in one launch: the table lives in device memory
+// (written once by the host for a fixed list of tensors, as an optimizer's is) instead of the
+// kernel arguments.  `owner[tile]` names the entry a tile of 1024 elements belongs to, so a
+// workgroup finds its tensor with two dependent uniform loads, whatever the length of the list.
+struct SgdTableEntry {
+    uint32_t* w_master;
+    uint32_t* w_q;
+    const uint32_t* grad;
+    uint32_t* mom;
+    uint64_t n;
+    uint32_t first_tile;    // number of tiles of the entries before this one
+    uint32_t position;      // index of the tensor in the caller's list: added to the stream id
+};
+static_assert(sizeof(SgdTableEntry) == 48, "the host lays the table out by this size");
+
+template <bool VEC>
+__global__ __launch_bounds__(kThreads) void sgd_table_kernel(const SgdTableEntry* __restrict__ entries,
+                                                             const uint32_t* __restrict__ owner, uint32_t tiles, SgdHyper h,
+                                                             FormatPlan fg, FormatPlan fm, FormatPlan fw, RngKey key)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    const uint64_t tile = linear_block();
+    if (tile >= tiles) return;     // the whole workgroup leaves together
+    const SgdTableEntry e = entries[owner[tile]];
+    RngKey k = key;
+    k.stream_id = key.stream_id + e.position;
+    sgd_tile<VEC>(e.w_master, e.w_q, e.grad, e.mom, e.n, tile - e.first_tile, h, fg, fm, fw, k, lds);
+}
+
 }  // namespace qsim

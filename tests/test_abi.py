@@ -125,3 +125,52 @@ def test_sgd_multi_validation_without_gpu():
     assert call([a], [b], [c], [16], fmt=B.Format(3, 8, 100, 0, 0)) == 2
     assert L.qsim_quant_sgd_step_multi(1, None, None, None, None, None, 0.1, 0.9, ctypes.byref(ident), ctypes.byref(ident),
                                        ctypes.byref(ident), 0, 0, None) == 1
+
+
+def test_sgd_table_validation_without_gpu():
+    L = B.lib()
+    ident = B.Format(0, 0, 0, 0, 0)
+    vp, u64 = ctypes.c_void_p, ctypes.c_uint64
+    sizes = lambda ns: (u64 * len(ns))(*ns)
+
+    # 48 bytes per non-empty tensor (rounded up to 16), 4 bytes per tile of 1024 elements (rounded up to 16)
+    assert L.qsim_sgd_table_bytes(0, None) == 0
+    assert L.qsim_sgd_table_bytes(2, sizes([0, 0])) == 0
+    assert L.qsim_sgd_table_bytes(1, sizes([1])) == 48 + 16
+    assert L.qsim_sgd_table_bytes(3, sizes([1024, 0, 1025])) == 96 + 16
+    assert L.qsim_sgd_table_bytes(3, sizes([1024, 5, 1024 * 9 + 1])) == 144 + 48
+    assert L.qsim_sgd_table_bytes(1, sizes([(1 << 38) + 1])) == 0
+    assert L.qsim_sgd_table_bytes(17, sizes([1 << 38] * 17)) == 0           # 17 * 2^28 tiles do not fit 32 bits
+
+    def build(ws, gs, ms, ns, qs=None, mem=FAKE + (8 << 20), mem_bytes=1 << 20, count=None, table=True):
+        k = len(ns)
+        arr = lambda xs: (vp * k)(*xs) if xs is not None else None
+        t = B.SgdTable()
+        st = L.qsim_sgd_table_build(k if count is None else count, arr(ws), arr(qs), arr(gs), arr(ms), sizes(ns), mem,
+                                    mem_bytes, None, ctypes.byref(t) if table else None)
+        return st, t
+
+    a, b, c = FAKE, FAKE + (1 << 20), FAKE + (2 << 20)
+    assert build([a], [b], [c], [16], table=False)[0] == 1
+    assert build([a], [b], [c], [16], count=-1)[0] == 4
+    st, t = build([a], [b], [c], [16], count=0)
+    assert st == 0 and t.count == 0 and t.tiles == 0
+    st, t = build([a, None], [b, None], [c, None], [0, 0])                  # only empty tensors
+    assert st == 0 and t.count == 0
+    assert build([a, None], [b, b], [c, c], [0, 16])[0] == 1
+    assert build([a, a], [b, a], [c, c], [0, 16])[0] == 5
+    assert build([a], [b], [c], [(1 << 38) + 1])[0] == 4
+    assert build([a], [b], [c], [16], mem=None)[0] == 6
+    assert build([a], [b], [c], [16], mem=FAKE + (8 << 20) + 4)[0] == 6     # misaligned table memory
+    assert build([a], [b], [c], [16], mem_bytes=63)[0] == 6
+
+    def step(t, fmt=ident):
+        return L.qsim_quant_sgd_step_table(ctypes.byref(t) if t is not None else None, 0.1, 0.9, None, ctypes.byref(fmt),
+                                           ctypes.byref(fmt), ctypes.byref(fmt), 0, 0, None)
+
+    assert step(B.SgdTable()) == 0                                          # an empty list: nothing to launch
+    assert step(None) == 1
+    assert step(B.SgdTable(), fmt=B.Format(3, 8, 100, 0, 0)) == 2
+    assert step(B.SgdTable(None, 0, 1, 1, 1)) == 1
+    assert step(B.SgdTable(FAKE, 48, 1, 1, 1)) == 6                         # too small for one entry and one tile
+    assert step(B.SgdTable(FAKE + 8, 64, 1, 1, 1)) == 6

@@ -61,3 +61,37 @@ def test_graph_replays_match_eager_calls():
         assert_bit_equal(w.cpu().numpy(), ew.cpu().numpy(), f"weights, replay {replay}")
         assert_bit_equal(m.cpu().numpy(), em.cpu().numpy(), f"momentum, replay {replay}")
         assert_bit_equal(wq.cpu().numpy(), ewq.cpu().numpy(), f"quantized weights, replay {replay}")
+
+
+def test_graph_replays_the_table_step():
+    """The device-table step is one kernel launch, so it can be captured once its table is built
+    (building copies from the host and waits, which a capture cannot hold)."""
+    if not torch.cuda.is_available():
+        pytest.fail("needs a GPU")
+    sizes = [5000, 1, 0, 1024, 70001, 333]
+    total = sum(sizes)
+    w, g, m = (torch.empty(total, device="cuda") for _ in range(3))
+    fg, fm, fw = Q.Format(1, 5, 2, 3, 3), Q.Format(2, 16, 12, 3, 1), Q.Format(3, 8, 256, 0, 0)
+    split = lambda t: list(torch.split(t, sizes))
+    captured = Q.SgdTensorList(split(w), split(g), split(m))
+
+    def fill(seed):
+        a, b, c = W.sgd_state(total, seeds=(seed, seed + 1, seed + 2))
+        w.copy_(torch.from_numpy(a)), g.copy_(torch.from_numpy(b)), m.copy_(torch.from_numpy(c))
+
+    fill(1)
+    captured.step(0.1, 0.9, fg, fm, fw, 5, 9)       # builds the table
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        captured.step(0.1, 0.9, fg, fm, fw, 5, 9)
+    for replay in range(3):
+        fill(50 + 3 * replay)
+        ew, em = w.clone(), m.clone()
+        Q.SgdTensorList(split(ew), split(g), split(em)).step_batched(0.1, 0.9, fg, fm, fw, 5, 9)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_bit_equal(w.cpu().numpy(), ew.cpu().numpy(), f"weights, replay {replay}")
+        assert_bit_equal(m.cpu().numpy(), em.cpu().numpy(), f"momentum, replay {replay}")

@@ -417,6 +417,16 @@ def test_sgd_options(formats, wd, damp, nesterov):
     Q.quant_sgd_step_multi(w2, g2, m2, 0.1, 0.9, fq[0], fq[1], fq[2], 1234, 5, options=Q.SgdOptions(wd, damp, nesterov))
     assert_bit_equal(host(w2[1]), wr, "weights through the multi-tensor call")
     assert_bit_equal(host(m2[1]), mr, "momentum through the multi-tensor call")
+    # and through the device table, every tensor aligned, several steps on one table
+    w3, g3, m3 = [dev(w[:100]), dev(w)], [dev(g[:100]), dev(g)], [dev(m[:100]), dev(m)]
+    lst = Q.SgdTensorList(w3, g3, m3)
+    lst.step(0.1, 0.9, fq[0], fq[1], fq[2], 1234, 5, options=Q.SgdOptions(wd, damp, nesterov))
+    assert_bit_equal(host(w3[1]), wr, "weights through the table")
+    assert_bit_equal(host(m3[1]), mr, "momentum through the table")
+    wr2, _, mr2 = R.quant_sgd_step(wr, g, mr, 0.1, 0.9, fo[0], fo[1], fo[2], 1234, 8, options=R.SgdOptions(wd, damp, nesterov))
+    lst.step(0.1, 0.9, fq[0], fq[1], fq[2], 1234, 7, options=Q.SgdOptions(wd, damp, nesterov))
+    assert_bit_equal(host(w3[1]), wr2, "weights after a second step on the same table")
+    assert_bit_equal(host(m3[1]), mr2, "momentum after a second step on the same table")
 
 
 def test_sgd_weights_kept_in_the_weight_format():
@@ -432,10 +442,16 @@ def test_sgd_weights_kept_in_the_weight_format():
     assert_bit_equal(host(md), mr, "momentum")
 
 
+@pytest.mark.parametrize("entry", ["arrays", "table"])
 @pytest.mark.parametrize("formats", [SGD_FORMATS[0], SGD_FORMATS[4], SGD_FORMATS[2]])
-def test_sgd_multi_tensor(formats):
+def test_sgd_multi_tensor(formats, entry):
     """One call over a model-like list of tensors equals one oracle step per tensor with stream_id + t:
-    more than 64 tensors (several launches), empty ones, ragged sizes, an unaligned view, missing w_q."""
+    more than 64 tensors (several launches of the pointer-array entry, one of the device-table entry),
+    empty ones, ragged sizes, an unaligned view, missing w_q."""
+    def multi(ws, gs, ms, *args, w_q=None, **kw):
+        lst = Q.SgdTensorList(ws, gs, ms, w_q)
+        (lst.step if entry == "table" else lst.step_batched)(*args, **kw)
+
     g0 = np.random.Generator(np.random.PCG64(3))
     sizes = [int(v) for v in g0.integers(1, 5000, size=90)] + [0, 64, 1024, 4096, 0, 100000, 3, 147 * 64, 512 * 1024 + 5]
     fo = [_fmt(R, *f) for f in formats]
@@ -447,7 +463,7 @@ def test_sgd_multi_tensor(formats):
         hw.append(w[off:off + n]), hg.append(g[off:off + n]), hm.append(m[off:off + n])
         dw.append(dev(w)[off:off + n]), dg.append(dev(g)[off:off + n]), dm.append(dev(m)[off:off + n])
         dq.append(None if t % 7 == 3 else torch.empty(n, device="cuda"))
-    Q.quant_sgd_step_multi(dw, dg, dm, 0.05, 0.9, fq[0], fq[1], fq[2], seed=1234, stream_id=10, w_q=dq)
+    multi(dw, dg, dm, 0.05, 0.9, fq[0], fq[1], fq[2], seed=1234, stream_id=10, w_q=dq)
     for t, n in enumerate(sizes):
         wr, wqr, mr = R.quant_sgd_step(hw[t], hg[t], hm[t], 0.05, 0.9, fo[0], fo[1], fo[2], 1234, 10 + t)
         assert_bit_equal(host(dm[t]), mr, f"momentum of tensor {t} (n={n})")
@@ -457,7 +473,7 @@ def test_sgd_multi_tensor(formats):
     # no quantized copies at all
     dw2 = [dev(x) for x in hw]
     dm2 = [dev(x) for x in hm]
-    Q.quant_sgd_step_multi(dw2, dg, dm2, 0.05, 0.9, fq[0], fq[1], fq[2], seed=1234, stream_id=10)
+    multi(dw2, dg, dm2, 0.05, 0.9, fq[0], fq[1], fq[2], seed=1234, stream_id=10)
     for t in (0, 17, 40, 63, 64, 90, 95, 98):
         assert_bit_equal(host(dw2[t]), host(dw[t]), f"tensor {t} without w_q")
 
