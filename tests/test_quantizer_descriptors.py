@@ -26,3 +26,20 @@ def test_flags_and_rounding_names():
     q = Z.Quantizer(Z.FixedPoint(8, 6), None, "stochastic", "nearest", seed=4)
     assert (q.forward_rounding, q.backward_rounding, q.seed, q.calls) == (3, 0, 4, 0)
     assert "FixedPoint" in repr(q)
+
+
+def test_formats_of_the_sgd_step():
+    from paper_1910_04540_amd import binding as B
+    from paper_1910_04540_amd.optim import sgd_format
+
+    def fields(f):
+        return (f.kind, f.a, f.b, f.rounding, f.flags)
+
+    assert fields(sgd_format(None)) == (B.KIND_IDENTITY, 0, 0, 0, 0)
+    assert fields(sgd_format(Z.FloatingPoint(5, 2, subnormal=True), "stochastic")) == (B.KIND_FLOAT, 5, 2, 3, 3)
+    assert fields(sgd_format(Z.FixedPoint(16, 12), "nearest_away")) == (B.KIND_FIXED, 16, 12, 1, 1)
+    assert fields(sgd_format(Z.BlockFloatingPoint(8, symmetric=True), "nearest", chunk=128)) == (B.KIND_BLOCK, 8, 128, 0, 4)
+    with pytest.raises(ValueError):
+        sgd_format(Z.BlockFloatingPoint(8, dim=0))
+    with pytest.raises(TypeError):
+        sgd_format("fp16")
