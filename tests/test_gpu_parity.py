@@ -529,3 +529,24 @@ def test_full_workload_5_sgd(n):
     assert_bit_equal(host(md), mr, "momentum")
     assert_bit_equal(host(wd), wr, "master weights")
     assert_bit_equal(host(qd), wqr, "quantized weights")
+
+
+def test_full_workload_5_sgd_over_a_resnet50_parameter_list():
+    """The 161 parameter tensors of a ResNet-50 (25.6 M parameters) in one table step, as bench.py times it."""
+    sizes = W.resnet50_parameter_sizes()
+    total = sum(sizes)
+    w, g, m = W.sgd_state(total)
+    fmts = SGD_FORMATS[0]
+    fo = [_fmt(R, *f) for f in fmts]
+    fq = [_fmt(Q, *f) for f in fmts]
+    flat = [dev(w), dev(g), dev(m), torch.empty(total, device="cuda")]
+    lists = [list(torch.split(f, sizes)) for f in flat]
+    Q.SgdTensorList(lists[0], lists[1], lists[2], lists[3]).step(0.1, 0.9, fq[0], fq[1], fq[2], 1234, 2)
+    gw, gm, gq = host(flat[0]), host(flat[2]), host(flat[3])
+    lo = 0
+    for t, n in enumerate(sizes):
+        wr, wqr, mr = R.quant_sgd_step(w[lo:lo + n], g[lo:lo + n], m[lo:lo + n], 0.1, 0.9, fo[0], fo[1], fo[2], 1234, 2 + t)
+        assert_bit_equal(gm[lo:lo + n], mr, f"momentum of tensor {t} (n={n})")
+        assert_bit_equal(gw[lo:lo + n], wr, f"weights of tensor {t} (n={n})")
+        assert_bit_equal(gq[lo:lo + n], wqr, f"quantized weights of tensor {t} (n={n})")
+        lo += n
