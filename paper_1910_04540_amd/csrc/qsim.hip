@@ -1,6 +1,7 @@
 // libqsim: the C-ABI entry points (include/qsim.h).  Each validates its arguments on the host,
 // resolves the format into a device plan, picks the kernel variant and enqueues it on the caller's
-// stream.  Nothing here allocates or synchronises.
+// stream.  No entry point allocates device memory, and none synchronises except
+// qsim_sgd_table_build, which waits for its own copy of the table.
 #include <hip/hip_runtime.h>
 
 #include <atomic>
