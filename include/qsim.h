@@ -192,6 +192,55 @@ int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* co
                                  void* hip_stream);
 
 /*
+ * Shards.  When the arrays of a call hold elements index0 .. index0 + n - 1 of a larger tensor (one
+ * GPU's share of it), the `_at` forms key the random words by the element's index in the WHOLE
+ * tensor, so the shards of a tensor, quantized separately in any split, give exactly what one call
+ * on the whole tensor gives.  index0 must be a multiple of 4 and at most 2^62 (QSIM_ERR_SHAPE
+ * otherwise); everything else is as in the plain form, which is the `_at` form with index0 == 0.
+ *
+ *   qsim_float_quantize_at, qsim_fixed_quantize_at   any split at multiples of 4.
+ *   qsim_block_quantize_at   the shard holds WHOLE blocks (rows of a per-row format); the shape
+ *                            arguments describe the shard.
+ *   qsim_quant_sgd_step_at   a shard of the parameters; index0 must also be a multiple of the chunk
+ *                            length of every block format, so that the shard holds whole chunks.
+ *
+ * Blocks that are split over shards (the whole tensor as one block, blocks along a dimension that is
+ * sharded) need the block maxima of all shards before anything can be rounded:
+ *
+ *   qsim_block_max   block_max[b] = the largest |x| of block b within THIS array, as the bit pattern
+ *                    of that fp32 magnitude (so the maximum over shards is the elementwise maximum
+ *                    of these unsigned integers: a max-all-reduce of nblocks words); 0 for an empty
+ *                    range.  block_max: nblocks words of device memory.  workspace as for
+ *                    qsim_block_quantize with the same shape.  n == 0 is QSIM_ERR_SHAPE here.
+ *   qsim_block_quantize_with_max   the second half: quantizes with the given block maxima (device
+ *                    memory, nblocks words, read only) instead of the array's own.
+ *
+ * With block_max from qsim_block_max on the same array and index0 == 0 the pair gives exactly what
+ * qsim_block_quantize gives.
+ */
+int qsim_float_quantize_at(const float* in, float* out, uint64_t n, uint64_t index0, int exp_bits,
+                           int man_bits, int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id,
+                           void* hip_stream);
+int qsim_fixed_quantize_at(const float* in, float* out, uint64_t n, uint64_t index0, int wl, int fl,
+                           int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id,
+                           void* hip_stream);
+int qsim_block_quantize_at(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks,
+                           uint64_t inner, uint64_t index0, int wl, int rounding, uint32_t flags,
+                           uint64_t seed, uint32_t stream_id, void* workspace, size_t workspace_bytes,
+                           void* hip_stream);
+int qsim_quant_sgd_step_at(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n,
+                           uint64_t index0, float lr, float momentum, const qsim_sgd_options* options,
+                           const qsim_format* fmt_grad, const qsim_format* fmt_mom,
+                           const qsim_format* fmt_weight, uint64_t seed, uint32_t stream_id,
+                           void* hip_stream);
+int qsim_block_max(const float* in, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner,
+                   uint32_t* block_max, void* workspace, size_t workspace_bytes, void* hip_stream);
+int qsim_block_quantize_with_max(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks,
+                                 uint64_t inner, uint64_t index0, int wl, int rounding, uint32_t flags,
+                                 uint64_t seed, uint32_t stream_id, const uint32_t* block_max,
+                                 void* hip_stream);
+
+/*
  * The same step over a FIXED list of tensors of any length in ONE launch (an optimizer steps the
  * same parameter, gradient and momentum tensors every iteration): the list is written once into a
  * table in device memory, and every later step only names the table.

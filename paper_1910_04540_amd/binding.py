@@ -22,7 +22,8 @@ KIND_IDENTITY, KIND_FLOAT, KIND_FIXED, KIND_BLOCK = 0, 1, 2, 3
 EXPORTS = ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_block_workspace_bytes",
            "qsim_set_barrier_wait_us", "qsim_quant_sgd_step", "qsim_quant_sgd_step_multi", "qsim_quant_sgd_step_ex",
            "qsim_quant_sgd_step_multi_ex", "qsim_sgd_table_bytes", "qsim_sgd_table_build", "qsim_quant_sgd_step_table",
-           "qsim_status_string")
+           "qsim_float_quantize_at", "qsim_fixed_quantize_at", "qsim_block_quantize_at", "qsim_quant_sgd_step_at",
+           "qsim_block_max", "qsim_block_quantize_with_max", "qsim_status_string")
 
 
 class Format(ctypes.Structure):
@@ -63,6 +64,11 @@ def lib() -> ctypes.CDLL:
     L.qsim_float_quantize.argtypes = [vp, vp, u64, ci, ci, ci, u32, u64, u32, vp]
     L.qsim_fixed_quantize.argtypes = [vp, vp, u64, ci, ci, ci, u32, u64, u32, vp]
     L.qsim_block_quantize.argtypes = [vp, vp, u64, u64, u64, u64, ci, ci, u32, u64, u32, vp, sz, vp]
+    L.qsim_float_quantize_at.argtypes = [vp, vp, u64, u64, ci, ci, ci, u32, u64, u32, vp]
+    L.qsim_fixed_quantize_at.argtypes = [vp, vp, u64, u64, ci, ci, ci, u32, u64, u32, vp]
+    L.qsim_block_quantize_at.argtypes = [vp, vp, u64, u64, u64, u64, u64, ci, ci, u32, u64, u32, vp, sz, vp]
+    L.qsim_block_max.argtypes = [vp, u64, u64, u64, u64, vp, vp, sz, vp]
+    L.qsim_block_quantize_with_max.argtypes = [vp, vp, u64, u64, u64, u64, u64, ci, ci, u32, u64, u32, vp, vp]
     L.qsim_block_workspace_bytes.argtypes = [u64, u64, u64, u64]
     L.qsim_block_workspace_bytes.restype = sz
     L.qsim_quant_sgd_step.argtypes = [vp, vp, vp, vp, u64, ctypes.c_float, ctypes.c_float,
@@ -78,6 +84,9 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
                                          u64, u32, vp]
     L.qsim_quant_sgd_step_ex.restype = ci
+    L.qsim_quant_sgd_step_at.argtypes = [vp, vp, vp, vp, u64, u64, ctypes.c_float, ctypes.c_float, po,
+                                         ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
+                                         u64, u32, vp]
     L.qsim_quant_sgd_step_multi_ex.argtypes = [ci, pp, pp, pp, pp, ctypes.POINTER(u64), ctypes.c_float, ctypes.c_float, po,
                                                ctypes.POINTER(Format), ctypes.POINTER(Format), ctypes.POINTER(Format),
                                                u64, u32, vp]
@@ -94,7 +103,9 @@ def lib() -> ctypes.CDLL:
     L.qsim_set_barrier_wait_us.restype = None
     L.qsim_status_string.argtypes = [ci]
     L.qsim_status_string.restype = ctypes.c_char_p
-    for name in ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_quant_sgd_step"):
+    for name in ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", "qsim_quant_sgd_step",
+                 "qsim_float_quantize_at", "qsim_fixed_quantize_at", "qsim_block_quantize_at", "qsim_quant_sgd_step_at",
+                 "qsim_block_max", "qsim_block_quantize_with_max"):
         getattr(L, name).restype = ci
     _lib = L
     return L
@@ -135,21 +146,30 @@ def _out_like(x: torch.Tensor, out) -> torch.Tensor:
     return out
 
 
-def float_quantize(x, exp_bits, man_bits, rounding=RN_EVEN, flags=SATURATE, seed=0, stream_id=0, out=None):
-    """qsim_float_quantize on a device tensor; returns the output tensor (``out`` may be ``x``)."""
+def float_quantize(x, exp_bits, man_bits, rounding=RN_EVEN, flags=SATURATE, seed=0, stream_id=0, out=None, index0=0):
+    """qsim_float_quantize on a device tensor; returns the output tensor (``out`` may be ``x``).
+    ``index0``: position of ``x[0]`` in the whole tensor when ``x`` is a shard (qsim_float_quantize_at)."""
     _device_f32(x, "x")
     out = _out_like(x, out)
-    _check(lib().qsim_float_quantize(x.data_ptr(), out.data_ptr(), x.numel(), exp_bits, man_bits, rounding, flags,
-                                     seed, stream_id, _stream()))
+    if index0:
+        _check(lib().qsim_float_quantize_at(x.data_ptr(), out.data_ptr(), x.numel(), index0, exp_bits, man_bits, rounding,
+                                            flags, seed, stream_id, _stream()))
+    else:
+        _check(lib().qsim_float_quantize(x.data_ptr(), out.data_ptr(), x.numel(), exp_bits, man_bits, rounding, flags,
+                                         seed, stream_id, _stream()))
     return out
 
 
-def fixed_quantize(x, wl, fl, rounding=RN_EVEN, flags=SATURATE, seed=0, stream_id=0, out=None):
-    """qsim_fixed_quantize on a device tensor."""
+def fixed_quantize(x, wl, fl, rounding=RN_EVEN, flags=SATURATE, seed=0, stream_id=0, out=None, index0=0):
+    """qsim_fixed_quantize on a device tensor (``index0``: qsim_fixed_quantize_at)."""
     _device_f32(x, "x")
     out = _out_like(x, out)
-    _check(lib().qsim_fixed_quantize(x.data_ptr(), out.data_ptr(), x.numel(), wl, fl, rounding, flags, seed,
-                                     stream_id, _stream()))
+    if index0:
+        _check(lib().qsim_fixed_quantize_at(x.data_ptr(), out.data_ptr(), x.numel(), index0, wl, fl, rounding, flags, seed,
+                                            stream_id, _stream()))
+    else:
+        _check(lib().qsim_fixed_quantize(x.data_ptr(), out.data_ptr(), x.numel(), wl, fl, rounding, flags, seed,
+                                         stream_id, _stream()))
     return out
 
 
@@ -162,36 +182,71 @@ def block_workspace_bytes(n, outer, nblocks, inner) -> int:
     return int(lib().qsim_block_workspace_bytes(n, outer, nblocks, inner))
 
 
+def _workspace(x, outer, nblocks, inner, workspace):
+    need = block_workspace_bytes(x.numel(), outer, nblocks, inner)
+    if not need:
+        return 0, 0, None
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size(), workspace
+
+
 def block_quantize(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed=0, stream_id=0, out=None,
-                   workspace=None):
+                   workspace=None, index0=0):
     """qsim_block_quantize on a device tensor viewed as [outer, nblocks, inner].
 
     ``workspace``: a device tensor of at least ``block_workspace_bytes(...)`` bytes; allocated
-    through torch when omitted and needed."""
+    through torch when omitted and needed.  ``index0``: position of ``x[0]`` in the whole tensor
+    when ``x`` is a shard of whole blocks (qsim_block_quantize_at)."""
     _device_f32(x, "x")
     out = _out_like(x, out)
-    need = block_workspace_bytes(x.numel(), outer, nblocks, inner)
-    ws_ptr, ws_bytes = 0, 0
-    if need:
-        if workspace is None:
-            workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
-        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel() * workspace.element_size()
-    _check(lib().qsim_block_quantize(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, wl, rounding,
-                                     flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
+    ws_ptr, ws_bytes, workspace = _workspace(x, outer, nblocks, inner, workspace)
+    if index0:
+        _check(lib().qsim_block_quantize_at(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, index0, wl,
+                                            rounding, flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
+    else:
+        _check(lib().qsim_block_quantize(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, wl, rounding,
+                                         flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
+    return out
+
+
+def block_max(x, outer, nblocks, inner, out=None, workspace=None):
+    """qsim_block_max: the largest magnitude of every block within ``x``, as int32 bit patterns of
+    fp32 magnitudes (non-negative, so ``torch.maximum`` of two results is the maximum over both)."""
+    _device_f32(x, "x")
+    if out is None:
+        out = torch.empty(nblocks, dtype=torch.int32, device=x.device)
+    elif not out.is_cuda or out.dtype != torch.int32 or not out.is_contiguous() or out.numel() != nblocks:
+        raise TypeError("out must be a contiguous int32 tensor of nblocks elements on the GPU")
+    ws_ptr, ws_bytes, workspace = _workspace(x, outer, nblocks, inner, workspace)
+    _check(lib().qsim_block_max(x.data_ptr(), x.numel(), outer, nblocks, inner, out.data_ptr(), ws_ptr, ws_bytes, _stream()))
+    return out
+
+
+def block_quantize_with_max(x, outer, nblocks, inner, wl, maxima, rounding=RN_EVEN, flags=0, seed=0, stream_id=0,
+                            out=None, index0=0):
+    """qsim_block_quantize_with_max: ``maxima`` is an int32 device tensor of nblocks block maxima."""
+    _device_f32(x, "x")
+    out = _out_like(x, out)
+    if not maxima.is_cuda or maxima.dtype != torch.int32 or not maxima.is_contiguous() or maxima.numel() != nblocks:
+        raise TypeError("maxima must be a contiguous int32 tensor of nblocks elements on the GPU")
+    _check(lib().qsim_block_quantize_with_max(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, index0, wl,
+                                              rounding, flags, seed, stream_id, maxima.data_ptr(), _stream()))
     return out
 
 
 def quant_sgd_step(w_master, grad, mom, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format,
-                   seed=0, stream_id=0, w_q=None, options: SgdOptions = None):
-    """qsim_quant_sgd_step(_ex): updates ``w_master`` and ``mom`` in place, fills ``w_q`` when given."""
+                   seed=0, stream_id=0, w_q=None, options: SgdOptions = None, index0=0):
+    """qsim_quant_sgd_step_at: updates ``w_master`` and ``mom`` in place, fills ``w_q`` when given.
+    ``index0``: position of the arrays' first element in the whole parameter tensor when they are a shard."""
     _device_f32(w_master, "w_master")
     _device_f32(grad, "grad")
     _device_f32(mom, "mom")
     n = w_master.numel()
     if grad.numel() != n or mom.numel() != n or (w_q is not None and _device_f32(w_q, "w_q").numel() != n):
         raise ValueError("all tensors of the step must have the same number of elements")
-    _check(lib().qsim_quant_sgd_step_ex(w_master.data_ptr(), w_q.data_ptr() if w_q is not None else None,
-                                        grad.data_ptr(), mom.data_ptr(), n, lr, momentum,
+    _check(lib().qsim_quant_sgd_step_at(w_master.data_ptr(), w_q.data_ptr() if w_q is not None else None,
+                                        grad.data_ptr(), mom.data_ptr(), n, index0, lr, momentum,
                                         ctypes.byref(options) if options is not None else None, ctypes.byref(fmt_grad),
                                         ctypes.byref(fmt_mom), ctypes.byref(fmt_weight), seed, stream_id, _stream()))
     return w_q

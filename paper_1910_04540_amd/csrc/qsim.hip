@@ -16,6 +16,10 @@ namespace qsim {
 
 static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 static int launch_status() { return hipGetLastError() == hipSuccess ? QSIM_OK : QSIM_ERR_LAUNCH; }
+static RngKey make_key(uint64_t seed, uint32_t stream_id, uint64_t index0)
+{
+    return RngKey{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id, index0 / 4};
+}
 static const uint32_t* u32(const float* p) { return reinterpret_cast<const uint32_t*>(p); }
 static uint32_t* u32(float* p) { return reinterpret_cast<uint32_t*>(p); }
 
@@ -266,13 +270,39 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                            symmetric, key);
     } else if (vec) {
         hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, pin, partial, s.sg);
-        hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg, wl,
-                           symmetric, key);
+        hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg.slices,
+                           s.sg, wl, symmetric, key);
     } else {
         hipLaunchKernelGGL((block_partial_max_kernel<false>), grid, dim3(kThreads), 0, stream, pin, partial, s.sg);
-        hipLaunchKernelGGL((block_apply_kernel<MODE, false>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg, wl,
-                           symmetric, key);
+        hipLaunchKernelGGL((block_apply_kernel<MODE, false>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg.slices,
+                           s.sg, wl, symmetric, key);
     }
+    return launch_status();
+}
+
+// Slices of the two-pass form for any shape: the schedule's, or one slice per block for the small
+// contiguous blocks the schedule handles in one launch.
+static SliceGeom two_pass_geometry(const BlockSchedule& s)
+{
+    SliceGeom sg = s.sg;
+    if (s.one_launch) {
+        sg.slices = 1;
+        sg.slice_len = (sg.block_len + kTileLen - 1) / kTileLen * kTileLen;
+    }
+    return sg;
+}
+
+template <int MODE>
+static int launch_block_given_max(const float* in, float* out, const SliceGeom& sg, int wl, int symmetric, const RngKey& key,
+                                  const uint32_t* block_max, hipStream_t stream)
+{
+    const dim3 grid = folded_xz(sg.g.nblocks, sg.slices);
+    if (aligned16(in) && aligned16(out) && sg.g.inner % 4 == 0)
+        hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, u32(in), u32(out), block_max, 1u,
+                           sg, wl, symmetric, key);
+    else
+        hipLaunchKernelGGL((block_apply_kernel<MODE, false>), grid, dim3(kThreads), 0, stream, u32(in), u32(out), block_max,
+                           1u, sg, wl, symmetric, key);
     return launch_status();
 }
 
@@ -285,9 +315,15 @@ extern "C" {
 int qsim_float_quantize(const float* in, float* out, uint64_t n, int exp_bits, int man_bits, int rounding,
                         uint32_t flags, uint64_t seed, uint32_t stream_id, void* hip_stream)
 {
+    return qsim_float_quantize_at(in, out, n, 0, exp_bits, man_bits, rounding, flags, seed, stream_id, hip_stream);
+}
+
+int qsim_float_quantize_at(const float* in, float* out, uint64_t n, uint64_t index0, int exp_bits, int man_bits,
+                           int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id, void* hip_stream)
+{
     if (!valid_rounding(rounding)) return QSIM_ERR_ROUNDING;
     if (!valid_float(exp_bits, man_bits) || !valid_flags(flags)) return QSIM_ERR_FORMAT;
-    if (n > kMaxElements) return QSIM_ERR_SHAPE;
+    if (n > kMaxElements || !valid_index0(index0)) return QSIM_ERR_SHAPE;
     if (n == 0) return QSIM_OK;
     if (!in || !out) return QSIM_ERR_NULL;
     if (partial_overlap(in, out, n)) return QSIM_ERR_OVERLAP;
@@ -295,7 +331,7 @@ int qsim_float_quantize(const float* in, float* out, uint64_t n, int exp_bits, i
     FormatPlan f;
     const int status = make_format_plan(&fmt, &f);
     if (status != QSIM_OK) return status;
-    const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    const RngKey key = make_key(seed, stream_id, index0);
     hipStream_t stream = as_stream(hip_stream);
     if (!aligned16(in) || !aligned16(out)) return launch_elementwise_rt(in, out, n, f, key, stream);
     if (f.float_form == kFloatGeneral) return launch_elementwise(in, out, n, rounding, FloatGeneralOp{f.flt}, key, stream);
@@ -306,9 +342,15 @@ int qsim_float_quantize(const float* in, float* out, uint64_t n, int exp_bits, i
 int qsim_fixed_quantize(const float* in, float* out, uint64_t n, int wl, int fl, int rounding, uint32_t flags,
                         uint64_t seed, uint32_t stream_id, void* hip_stream)
 {
+    return qsim_fixed_quantize_at(in, out, n, 0, wl, fl, rounding, flags, seed, stream_id, hip_stream);
+}
+
+int qsim_fixed_quantize_at(const float* in, float* out, uint64_t n, uint64_t index0, int wl, int fl, int rounding,
+                           uint32_t flags, uint64_t seed, uint32_t stream_id, void* hip_stream)
+{
     if (!valid_rounding(rounding)) return QSIM_ERR_ROUNDING;
     if (!valid_fixed(wl, fl) || !valid_flags(flags)) return QSIM_ERR_FORMAT;
-    if (n > kMaxElements) return QSIM_ERR_SHAPE;
+    if (n > kMaxElements || !valid_index0(index0)) return QSIM_ERR_SHAPE;
     if (n == 0) return QSIM_OK;
     if (!in || !out) return QSIM_ERR_NULL;
     if (partial_overlap(in, out, n)) return QSIM_ERR_OVERLAP;
@@ -316,7 +358,7 @@ int qsim_fixed_quantize(const float* in, float* out, uint64_t n, int wl, int fl,
     FormatPlan f;
     const int status = make_format_plan(&fmt, &f);
     if (status != QSIM_OK) return status;
-    const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    const RngKey key = make_key(seed, stream_id, index0);
     hipStream_t stream = as_stream(hip_stream);
     if (!aligned16(in) || !aligned16(out)) return launch_elementwise_rt(in, out, n, f, key, stream);
     return launch_elementwise(in, out, n, rounding, FixedOp{f.grid}, key, stream);
@@ -332,9 +374,17 @@ int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer,
                         int wl, int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id, void* workspace,
                         size_t workspace_bytes, void* hip_stream)
 {
+    return qsim_block_quantize_at(in, out, n, outer, nblocks, inner, 0, wl, rounding, flags, seed, stream_id, workspace,
+                                  workspace_bytes, hip_stream);
+}
+
+int qsim_block_quantize_at(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner,
+                           uint64_t index0, int wl, int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id,
+                           void* workspace, size_t workspace_bytes, void* hip_stream)
+{
     if (!valid_rounding(rounding)) return QSIM_ERR_ROUNDING;
     if (!valid_block_wl(wl) || !valid_flags(flags)) return QSIM_ERR_FORMAT;
-    if (n > kMaxElements) return QSIM_ERR_SHAPE;
+    if (n > kMaxElements || !valid_index0(index0)) return QSIM_ERR_SHAPE;
     if (n == 0) return QSIM_OK;
     if (!valid_block_shape(n, outer, nblocks, inner)) return QSIM_ERR_SHAPE;
     if (!in || !out) return QSIM_ERR_NULL;
@@ -346,7 +396,7 @@ int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer,
         if (ranges_overlap(workspace, s.workspace, in, n * 4) || ranges_overlap(workspace, s.workspace, out, n * 4))
             return QSIM_ERR_OVERLAP;
     }
-    const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    const RngKey key = make_key(seed, stream_id, index0);
     const int symmetric = (flags & QSIM_SYMMETRIC) ? 1 : 0;
     hipStream_t stream = as_stream(hip_stream);
     switch (rounding) {
@@ -354,6 +404,62 @@ int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer,
     case QSIM_RN_AWAY: return launch_block_mode<QSIM_RN_AWAY>(in, out, s, wl, symmetric, key, workspace, stream);
     case QSIM_RN_ZERO: return launch_block_mode<QSIM_RN_ZERO>(in, out, s, wl, symmetric, key, workspace, stream);
     default:           return launch_block_mode<QSIM_STOCHASTIC>(in, out, s, wl, symmetric, key, workspace, stream);
+    }
+}
+
+int qsim_block_max(const float* in, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner, uint32_t* block_max,
+                   void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (n == 0 || n > kMaxElements || !valid_block_shape(n, outer, nblocks, inner)) return QSIM_ERR_SHAPE;
+    if (!in || !block_max) return QSIM_ERR_NULL;
+    if (nblocks > 0x7fffffffull) return QSIM_ERR_UNSUPPORTED;
+    if (ranges_overlap(block_max, nblocks * sizeof(uint32_t), in, n * 4)) return QSIM_ERR_OVERLAP;
+    const BlockSchedule s = block_schedule(n, outer, nblocks, inner);
+    const SliceGeom sg = two_pass_geometry(s);
+    uint32_t* partial = block_max;                       // one slice per block: pass 1 writes the result itself
+    if (sg.slices > 1) {
+        const size_t need = (size_t)nblocks * sg.slices * sizeof(uint32_t);
+        if (!workspace || !aligned16(workspace) || workspace_bytes < need) return QSIM_ERR_WORKSPACE;
+        if (ranges_overlap(workspace, need, in, n * 4) || ranges_overlap(workspace, need, block_max, nblocks * sizeof(uint32_t)))
+            return QSIM_ERR_OVERLAP;
+        partial = static_cast<uint32_t*>(workspace);
+    }
+    hipStream_t stream = as_stream(hip_stream);
+    const dim3 grid = folded_xz(nblocks, sg.slices);
+    if (aligned16(in) && inner % 4 == 0)
+        hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, u32(in), partial, sg);
+    else
+        hipLaunchKernelGGL((block_partial_max_kernel<false>), grid, dim3(kThreads), 0, stream, u32(in), partial, sg);
+    if (sg.slices > 1)
+        hipLaunchKernelGGL(block_fold_partials_kernel, folded((nblocks + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
+                           partial, block_max, nblocks, sg.slices);
+    return launch_status();
+}
+
+int qsim_block_quantize_with_max(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks,
+                                 uint64_t inner, uint64_t index0, int wl, int rounding, uint32_t flags, uint64_t seed,
+                                 uint32_t stream_id, const uint32_t* block_max, void* hip_stream)
+{
+    if (!valid_rounding(rounding)) return QSIM_ERR_ROUNDING;
+    if (!valid_block_wl(wl) || !valid_flags(flags)) return QSIM_ERR_FORMAT;
+    if (n > kMaxElements || !valid_index0(index0)) return QSIM_ERR_SHAPE;
+    if (n == 0) return QSIM_OK;
+    if (!valid_block_shape(n, outer, nblocks, inner)) return QSIM_ERR_SHAPE;
+    if (!in || !out || !block_max) return QSIM_ERR_NULL;
+    if (partial_overlap(in, out, n)) return QSIM_ERR_OVERLAP;
+    if (nblocks > 0x7fffffffull) return QSIM_ERR_UNSUPPORTED;
+    if (ranges_overlap(block_max, nblocks * sizeof(uint32_t), in, n * 4) ||
+        ranges_overlap(block_max, nblocks * sizeof(uint32_t), out, n * 4))
+        return QSIM_ERR_OVERLAP;
+    const SliceGeom sg = two_pass_geometry(block_schedule(n, outer, nblocks, inner));
+    const RngKey key = make_key(seed, stream_id, index0);
+    const int symmetric = (flags & QSIM_SYMMETRIC) ? 1 : 0;
+    hipStream_t stream = as_stream(hip_stream);
+    switch (rounding) {
+    case QSIM_RN_EVEN: return launch_block_given_max<QSIM_RN_EVEN>(in, out, sg, wl, symmetric, key, block_max, stream);
+    case QSIM_RN_AWAY: return launch_block_given_max<QSIM_RN_AWAY>(in, out, sg, wl, symmetric, key, block_max, stream);
+    case QSIM_RN_ZERO: return launch_block_given_max<QSIM_RN_ZERO>(in, out, sg, wl, symmetric, key, block_max, stream);
+    default:           return launch_block_given_max<QSIM_STOCHASTIC>(in, out, sg, wl, symmetric, key, block_max, stream);
     }
 }
 
@@ -405,14 +511,26 @@ int qsim_quant_sgd_step_ex(float* w_master, float* w_q, const float* grad, float
                            const qsim_format* fmt_mom, const qsim_format* fmt_weight, uint64_t seed,
                            uint32_t stream_id, void* hip_stream)
 {
+    return qsim_quant_sgd_step_at(w_master, w_q, grad, mom, n, 0, lr, momentum, options, fmt_grad, fmt_mom, fmt_weight, seed,
+                                  stream_id, hip_stream);
+}
+
+int qsim_quant_sgd_step_at(float* w_master, float* w_q, const float* grad, float* mom, uint64_t n, uint64_t index0,
+                           float lr, float momentum, const qsim_sgd_options* options, const qsim_format* fmt_grad,
+                           const qsim_format* fmt_mom, const qsim_format* fmt_weight, uint64_t seed,
+                           uint32_t stream_id, void* hip_stream)
+{
     FormatPlan fg, fm, fw;
     int status;
     if ((status = make_format_plan(fmt_grad, &fg)) != QSIM_OK) return status;
     if ((status = make_format_plan(fmt_mom, &fm)) != QSIM_OK) return status;
     if ((status = make_format_plan(fmt_weight, &fw)) != QSIM_OK) return status;
+    if (!valid_index0(index0)) return QSIM_ERR_SHAPE;
+    for (const FormatPlan* f : {&fg, &fm, &fw})       // a shard holds whole chunks
+        if (f->kind == 3 && index0 % (4ull * (uint64_t)f->lanes) != 0) return QSIM_ERR_SHAPE;
     if ((status = check_sgd_tensor(w_master, w_q, grad, mom, n)) != QSIM_OK) return status;
     if (n == 0) return QSIM_OK;
-    const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    const RngKey key = make_key(seed, stream_id, index0);
     const uint64_t groups = (n + 3) / 4;
     const uint64_t tiles = (groups + kThreads - 1) / kThreads;
     const unsigned blocks = (unsigned)(tiles < kGridX ? tiles : kGridX);       // the kernel strides over the tiles
@@ -483,7 +601,7 @@ int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* co
             ++t;
             continue;
         }
-        const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id + (uint32_t)first};
+        const RngKey key = make_key(seed, stream_id + (uint32_t)first, 0);
         if (vec)
             hipLaunchKernelGGL((sgd_multi_kernel<true>), folded(tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
                                fg, fm, fw, key);
@@ -591,7 +709,7 @@ int qsim_quant_sgd_step_table(const qsim_sgd_table* table, float lr, float momen
         table->bytes < table_owner_offset(table->count) + (size_t)table->tiles * sizeof(uint32_t))
         return QSIM_ERR_WORKSPACE;
     const SgdHyper h = make_hyper(lr, momentum, options);
-    const RngKey key{(uint32_t)seed, (uint32_t)(seed >> 32), stream_id};
+    const RngKey key = make_key(seed, stream_id, 0);
     const SgdTableEntry* entries = static_cast<const SgdTableEntry*>(table->device);
     const uint32_t* owner =
         reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(table->device) + table_owner_offset(table->count));

@@ -38,14 +38,19 @@ __device__ __forceinline__ Words4 philox4x32_10(uint32_t c0, uint32_t c1, uint32
     return Words4{{c0, c1, c2, c3}};
 }
 
+// group0: group number, in the whole tensor, of the first group of the array a call is given
+// (0 unless the array is a shard of a larger tensor); wave-uniform.
 struct RngKey {
     uint32_t seed_lo, seed_hi, stream_id;
+    uint64_t group0;
 };
 
-// Random words of the four elements 4*j .. 4*j+3 (Sec. 3.1 "Rounding mode": stochastic rounding).
+// Random words of the four elements 4*j .. 4*j+3 of the array (Sec. 3.1 "Rounding mode":
+// stochastic rounding), which are elements 4*(group0+j) .. of the tensor the counter is keyed by.
 __device__ __forceinline__ Words4 random_words(uint64_t j, const RngKey& key, uint32_t role)
 {
-    return philox4x32_10((uint32_t)j, (uint32_t)(j >> 32), key.stream_id, role, key.seed_lo, key.seed_hi);
+    const uint64_t c = j + key.group0;
+    return philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), key.stream_id, role, key.seed_lo, key.seed_hi);
 }
 
 // ---------------------------------------------------------------------------------------------

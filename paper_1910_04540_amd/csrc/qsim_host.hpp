@@ -13,6 +13,8 @@ namespace qsim {
 
 constexpr uint64_t kMaxElements = 1ull << 38;   // keeps every grid below 2^31 workgroups
 
+// Position of a shard's first element in the whole tensor: whole groups, and far from wrapping.
+inline bool valid_index0(uint64_t index0) { return index0 % 4 == 0 && index0 <= (1ull << 62); }
 inline bool valid_rounding(int r) { return r >= QSIM_RN_EVEN && r <= QSIM_STOCHASTIC; }
 inline bool valid_flags(uint32_t f) { return (f & ~(QSIM_SATURATE | QSIM_SUBNORMAL | QSIM_SYMMETRIC)) == 0; }
 inline bool valid_fixed(int wl, int fl) { return wl >= 1 && wl <= 24 && fl >= wl - 128 && fl <= 149; }

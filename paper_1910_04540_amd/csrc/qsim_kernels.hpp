@@ -303,16 +303,33 @@ __global__ __launch_bounds__(kThreads) void block_partial_max_kernel(const uint3
     if (threadIdx.x == 0) partial[b * sg.slices + blockIdx.y] = m;
 }
 
+// Block maxima from the partial maxima of pass 1: block_max[b] = max over s of partial[b * slices + s].
+__global__ __launch_bounds__(kThreads) void block_fold_partials_kernel(const uint32_t* partial, uint32_t* block_max,
+                                                                       uint64_t nblocks, uint32_t slices)
+{
+    const uint64_t b = linear_block() * kThreads + threadIdx.x;
+    if (b >= nblocks) return;
+    uint32_t m = 0;
+    for (uint32_t s = 0; s < slices; ++s) {
+        const uint32_t a = partial[b * slices + s];
+        m = m > a ? m : a;
+    }
+    block_max[b] = m;
+}
+
+// `npartial` maxima per block are folded: the slices of pass 1, or 1 when the caller supplies
+// finished block maxima.
 template <int MODE, bool VEC>
 __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* in, uint32_t* out, const uint32_t* partial,
-                                                               SliceGeom sg, int wl, int symmetric, RngKey key)
+                                                               uint32_t npartial, SliceGeom sg, int wl, int symmetric,
+                                                               RngKey key)
 {
     __shared__ uint32_t lds[kThreads / 64];
     const uint64_t b = linear_block_xz();
     if (b >= sg.g.nblocks) return;                    // the whole workgroup leaves together
     uint32_t m = 0;
-    for (uint32_t s = threadIdx.x; s < sg.slices; s += kThreads) {
-        const uint32_t a = partial[b * sg.slices + s];
+    for (uint32_t s = threadIdx.x; s < npartial; s += kThreads) {
+        const uint32_t a = partial[b * npartial + s];
         m = m > a ? m : a;
     }
     const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);

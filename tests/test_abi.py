@@ -174,3 +174,34 @@ def test_sgd_table_validation_without_gpu():
     assert step(B.SgdTable(None, 0, 1, 1, 1)) == 1
     assert step(B.SgdTable(FAKE, 48, 1, 1, 1)) == 6                         # too small for one entry and one tile
     assert step(B.SgdTable(FAKE + 8, 64, 1, 1, 1)) == 6
+
+
+def test_shard_validation_without_gpu():
+    L = B.lib()
+    ident = B.Format(0, 0, 0, 0, 0)
+    assert L.qsim_fixed_quantize_at(FAKE, FAKE, 16, 6, 8, 6, 0, 1, 0, 0, None) == 4          # index0 not a multiple of 4
+    assert L.qsim_float_quantize_at(FAKE, FAKE, 16, (1 << 62) + 4, 5, 2, 0, 1, 0, 0, None) == 4
+    assert L.qsim_float_quantize_at(FAKE, FAKE, 0, 8, 5, 2, 0, 1, 0, 0, None) == 0
+    assert L.qsim_fixed_quantize_at(FAKE, FAKE, 16, 8, 25, 6, 0, 1, 0, 0, None) == 2          # the format is checked first
+    assert L.qsim_block_quantize_at(FAKE, FAKE, 64, 1, 4, 16, 2, 8, 0, 0, 0, 0, None, 0, None) == 4
+    blk = B.Format(3, 8, 256, 0, 0)
+
+    def sgd(index0, fw=blk):
+        return L.qsim_quant_sgd_step_at(FAKE, None, FAKE + (1 << 20), FAKE + (2 << 20), 0, index0, 0.1, 0.9, None,
+                                        ctypes.byref(ident), ctypes.byref(ident), ctypes.byref(fw), 0, 0, None)
+
+    assert sgd(0) == 0 and sgd(512) == 0
+    assert sgd(128) == 4                                       # a shard must hold whole chunks of 256
+    assert sgd(128, fw=ident) == 0 and sgd(130, fw=ident) == 4
+    mx = FAKE + (4 << 20)
+    assert L.qsim_block_max(FAKE, 0, 1, 1, 1, mx, None, 0, None) == 4
+    assert L.qsim_block_max(FAKE, 64, 1, 4, 15, mx, None, 0, None) == 4
+    assert L.qsim_block_max(None, 64, 1, 4, 16, mx, None, 0, None) == 1
+    assert L.qsim_block_max(FAKE, 64, 1, 4, 16, None, None, 0, None) == 1
+    assert L.qsim_block_max(FAKE, 64, 1, 4, 16, FAKE + 64, None, 0, None) == 5              # maxima inside the input
+    assert L.qsim_block_max(FAKE, 1 << 20, 1, 1, 1 << 20, mx, None, 0, None) == 6           # several slices need scratch
+    assert L.qsim_block_quantize_with_max(FAKE, FAKE, 64, 1, 4, 16, 0, 8, 0, 0, 0, 0, None, None) == 1
+    assert L.qsim_block_quantize_with_max(FAKE, FAKE, 64, 1, 4, 16, 2, 8, 0, 0, 0, 0, mx, None) == 4
+    assert L.qsim_block_quantize_with_max(FAKE, FAKE, 64, 1, 4, 16, 0, 1, 0, 0, 0, 0, mx, None) == 2
+    assert L.qsim_block_quantize_with_max(FAKE, FAKE, 64, 1, 4, 16, 0, 8, 0, 0, 0, 0, FAKE + 16, None) == 5
+    assert L.qsim_block_quantize_with_max(FAKE, FAKE, 0, 1, 4, 16, 0, 8, 0, 0, 0, 0, None, None) == 0
