@@ -88,6 +88,8 @@ struct BlockSchedule {
 };
 
 constexpr uint64_t kCachedMaxInner = 16384;      // 256 threads x 16 groups x 4 elements
+constexpr int kWideThreads = 1024;
+constexpr uint64_t kWideCachedMaxInner = 65536;  // 1024 threads x 16 groups x 4 elements
 constexpr uint32_t kMaxSlices = 1024;
 constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
@@ -218,6 +220,23 @@ static void launch_block_cached(const uint32_t* in, uint32_t* out, const BlockGe
                        team_log2, wl, symmetric, key);
 }
 
+template <int MODE, int GPT>
+static void launch_block_ragged(const uint32_t* in, uint32_t* out, const BlockGeom& g, bool wide, int wl, int symmetric,
+                                const RngKey& key, hipStream_t stream)
+{
+    // whole blocks per workgroup: their elements plus the strangers in the first and last group fit the registers
+    uint64_t rows = (4ull * kThreads * GPT - 6) / g.inner;
+    if (rows > (uint64_t)kRaggedMaxRows) rows = kRaggedMaxRows;
+    const uint32_t magic = g.inner > 1 ? (uint32_t)((1ull << 32) / g.inner) + 1u : 0u;
+    const uint64_t blocks = (g.nblocks + rows - 1) / rows;
+    if (wide)
+        hipLaunchKernelGGL((block_ragged_kernel<MODE, GPT, true>), folded(blocks), dim3(kThreads), 0, stream, in, out, g,
+                           (uint32_t)rows, magic, wl, symmetric, key);
+    else
+        hipLaunchKernelGGL((block_ragged_kernel<MODE, GPT, false>), folded(blocks), dim3(kThreads), 0, stream, in, out, g,
+                           (uint32_t)rows, magic, wl, symmetric, key);
+}
+
 template <int MODE>
 static int launch_block_mode(const float* in, float* out, const BlockSchedule& s, int wl, int symmetric,
                              const RngKey& key, void* workspace, hipStream_t stream)
@@ -242,6 +261,12 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
             else if (per_lane <= 4) launch_block_cached<MODE, 4, true>(pin, pout, g, 8, wl, symmetric, key, stream);
             else if (per_lane <= 8) launch_block_cached<MODE, 8, true>(pin, pout, g, 8, wl, symmetric, key, stream);
             else launch_block_cached<MODE, 16, true>(pin, pout, g, 8, wl, symmetric, key, stream);
+        } else if (g.inner + 6 <= 4ull * kThreads * 16) {
+            // any block length, aligned arrays or not: whole blocks per workgroup, the tensor's own groups
+            const bool wide = aligned16(in) && aligned16(out);
+            if (g.inner + 6 <= 4ull * kThreads * 4) launch_block_ragged<MODE, 4>(pin, pout, g, wide, wl, symmetric, key, stream);
+            else if (g.inner + 6 <= 4ull * kThreads * 8) launch_block_ragged<MODE, 8>(pin, pout, g, wide, wl, symmetric, key, stream);
+            else launch_block_ragged<MODE, 16>(pin, pout, g, wide, wl, symmetric, key, stream);
         } else {
             hipLaunchKernelGGL((block_rows_kernel<MODE>), folded(g.nblocks), dim3(kThreads), 0, stream, pin,
                                pout, g, wl, symmetric, key);
@@ -254,6 +279,17 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         // single pass when the blocks fit in the chip's registers, else the streaming two-pass form:
         // blocks on grid.y (folded when there are more than 65535), slices on grid.x
         if (try_resident_any<MODE>(pin, pout, g, wl, symmetric, key, partial, stream)) return launch_status();
+        if (g.inner <= kWideCachedMaxInner) {
+            // too many blocks to hold at once, but each fits the registers of a 1024-thread workgroup
+            const uint64_t per_lane = ((g.inner + 3) / 4 + kWideThreads - 1) / kWideThreads;
+            if (per_lane <= 8)
+                hipLaunchKernelGGL((block_cached_kernel<MODE, 8, true, kWideThreads>), folded(g.nblocks), dim3(kWideThreads), 0,
+                                   stream, pin, pout, g, 10, wl, symmetric, key);
+            else
+                hipLaunchKernelGGL((block_cached_kernel<MODE, 16, true, kWideThreads>), folded(g.nblocks), dim3(kWideThreads), 0,
+                                   stream, pin, pout, g, 10, wl, symmetric, key);
+            return launch_status();
+        }
         const unsigned by = (unsigned)(g.nblocks < 65535 ? g.nblocks : 65535);
         hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,

@@ -137,7 +137,8 @@ __global__ __launch_bounds__(kThreads) void elementwise_rt_kernel(const uint32_t
 // ---------------------------------------------------------------------------------------------
 
 // Workgroup-wide maximum: wave reduction, then one LDS slot per wave.
-__device__ __forceinline__ uint32_t workgroup_max(uint32_t v, uint32_t* lds /* kThreads / 64 slots */)
+template <int THREADS = kThreads>
+__device__ __forceinline__ uint32_t workgroup_max(uint32_t v, uint32_t* lds /* THREADS / 64 slots */)
 {
     const uint32_t w = wave_max(v);
     const int wave = threadIdx.x >> 6;
@@ -146,7 +147,7 @@ __device__ __forceinline__ uint32_t workgroup_max(uint32_t v, uint32_t* lds /* k
     __syncthreads();
     uint32_t m = lds[0];
 #pragma unroll
-    for (int k = 1; k < kThreads / 64; ++k) m = m > lds[k] ? m : lds[k];
+    for (int k = 1; k < THREADS / 64; ++k) m = m > lds[k] ? m : lds[k];
     return m;
 }
 
@@ -168,16 +169,17 @@ struct BlockGeom {
 };
 
 // Contiguous blocks (outer == 1, inner % 4 == 0, aligned arrays) held in registers: a team of
-// `team` lanes (a power of two, 1..64, or the whole workgroup when team == 256) owns one block and
+// `team` lanes (a power of two, 1..64) or the whole workgroup of THREADS threads owns one block and
 // every lane keeps GPT groups of it, so the block is read from memory exactly once.
-// Requires ceil(inner / 4) <= team * GPT.
-template <int MODE, int GPT, bool WHOLE_WORKGROUP>
-__global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* in, uint32_t* out, BlockGeom g,
-                                                                int team_log2, int wl, int symmetric, RngKey key)
+// Requires ceil(inner / 4) <= team * GPT (THREADS * GPT for the whole workgroup).  THREADS = 1024
+// with 16 groups per thread holds a block of 65,536 elements: half of a compute unit's registers.
+template <int MODE, int GPT, bool WHOLE_WORKGROUP, int THREADS = kThreads>
+__global__ __launch_bounds__(THREADS) void block_cached_kernel(const uint32_t* in, uint32_t* out, BlockGeom g,
+                                                               int team_log2, int wl, int symmetric, RngKey key)
 {
-    __shared__ uint32_t lds[kThreads / 64];
+    __shared__ uint32_t lds[THREADS / 64];
     const int team = 1 << team_log2;
-    const int teams_per_wg = WHOLE_WORKGROUP ? 1 : (kThreads >> team_log2);
+    const int teams_per_wg = WHOLE_WORKGROUP ? 1 : (THREADS >> team_log2);
     const int lane = WHOLE_WORKGROUP ? (int)threadIdx.x : ((int)threadIdx.x & (team - 1));
     const uint64_t b = linear_block() * teams_per_wg + (WHOLE_WORKGROUP ? 0 : ((int)threadIdx.x >> team_log2));
     // a team past the last block keeps all its lanes running with nothing to load or store, so the
@@ -187,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* 
     const uint64_t end = start + len;
     const uint64_t j0 = start / 4;
     const int groups = (int)((len + 3) / 4);
-    const int stride = WHOLE_WORKGROUP ? kThreads : team;
+    const int stride = WHOLE_WORKGROUP ? THREADS : team;
 
     uint4 v[GPT];
 #pragma unroll
@@ -208,7 +210,7 @@ __global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* 
         const uint32_t gm = max4_mag(v[k]);
         m = m > gm ? m : gm;
     }
-    m = WHOLE_WORKGROUP ? workgroup_max(m, lds) : group_max(m, team);
+    m = WHOLE_WORKGROUP ? workgroup_max<THREADS>(m, lds) : group_max(m, team);
     const GridPlan p = block_plan(m, wl, symmetric);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
@@ -218,6 +220,102 @@ __global__ __launch_bounds__(kThreads) void block_cached_kernel(const uint32_t* 
             if (k < PRE) r = early[k];
             else if (MODE == QSIM_STOCHASTIC) r = random_words(j0 + t, key, 0u);
             store_group<true>(out, j0 + t, end, quantize_group_to_grid<MODE>(v[k], p, r));
+        }
+    }
+}
+
+// Contiguous blocks (outer == 1) of ANY length up to 4 * kThreads * GPT - 6, aligned arrays or not:
+// the form for block lengths that are not a multiple of four (a 3x3 kernel's 27 weights, a row of
+// 1001).  A workgroup owns `rows_per_wg` whole consecutive blocks, i.e. one contiguous range of
+// elements, and walks it in the tensor's own groups of four (which is what the random words are
+// keyed by, and what a dwordx4 access needs); a group may straddle blocks, and the first and last
+// group of the range may be shared with the neighbouring workgroups, which each store only their
+// own elements of it.  Block maxima meet in LDS (one ds_max per run of same-block elements of a
+// group); every element then takes the plan of its own block.  The data is read once.
+// `magic` = floor(2^32 / inner) + 1 (any value when inner == 1): element offset / inner by one
+// multiply-high, exact for offsets below 2^16.
+constexpr int kRaggedMaxRows = 4096;
+
+template <int MODE, int GPT, bool VEC>
+__global__ __launch_bounds__(kThreads) void block_ragged_kernel(const uint32_t* in, uint32_t* out, BlockGeom g,
+                                                                uint32_t rows_per_wg, uint32_t magic, int wl, int symmetric,
+                                                                RngKey key)
+{
+    __shared__ uint32_t rowmax[kRaggedMaxRows];
+    const uint64_t r0 = linear_block() * rows_per_wg;
+    if (r0 >= g.nblocks) return;                      // the whole workgroup leaves together
+    const uint64_t r1 = (g.nblocks - r0 < rows_per_wg) ? g.nblocks : r0 + rows_per_wg;
+    const uint32_t nrows = (uint32_t)(r1 - r0);
+    const uint64_t e0 = r0 * g.inner;
+    const uint64_t e1 = (r1 * g.inner < g.n) ? r1 * g.inner : g.n;      // the last block may be short
+    const uint64_t j0 = e0 / 4;
+    const uint32_t ngroups = (uint32_t)((e1 + 3) / 4 - j0);             // <= kThreads * GPT by the host's choice
+    const uint32_t lead = (uint32_t)(e0 - j0 * 4);                      // elements of the first group before the range
+    const uint32_t span = (uint32_t)(e1 - e0);
+    const uint32_t inner = (uint32_t)g.inner;
+
+    for (uint32_t t = threadIdx.x; t < nrows; t += kThreads) rowmax[t] = 0u;
+    __syncthreads();
+
+    uint4 v[GPT];
+    uint32_t rows01[GPT], rows23[GPT];       // block of each element relative to r0, 16 bits each (clamped outside the range)
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (t < ngroups) v[k] = load_group<VEC>(in, j0 + t, g.n);
+    }
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        if (t < ngroups) {
+            const uint32_t bits[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+            uint32_t mag[4], row[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t at = t * 4u + (uint32_t)e;                  // offset from the first group's start
+                const bool mine = at >= lead && at - lead < span;
+                const uint32_t off = mine ? at - lead : 0u;
+                const uint32_t r = inner == 1u ? off : __umulhi(off, magic);
+                row[e] = r < nrows ? r : nrows - 1u;
+                mag[e] = mine ? (bits[e] & 0x7fffffffu) : 0u;
+            }
+            rows01[k] = row[0] | (row[1] << 16);
+            rows23[k] = row[2] | (row[3] << 16);
+            uint32_t m = mag[0];
+#pragma unroll
+            for (int e = 1; e < 4; ++e) {
+                if (row[e] != row[e - 1]) {
+                    atomicMax(&rowmax[row[e - 1]], m);
+                    m = 0u;
+                }
+                m = m > mag[e] ? m : mag[e];
+            }
+            atomicMax(&rowmax[row[3]], m);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        if (t < ngroups) {
+            const uint64_t j = j0 + t;
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+            const uint32_t bits[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+            const uint32_t row[4] = {rows01[k] & 0xffffu, rows01[k] >> 16, rows23[k] & 0xffffu, rows23[k] >> 16};
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                o[e] = quantize_to_grid<MODE>(bits[e], block_plan(rowmax[row[e]], wl, symmetric), r.w[e]);
+            const uint32_t at = t * 4u;
+            if (at >= lead && at + 3u - lead < span) {
+                store_group<VEC>(out, j, g.n, make_uint4(o[0], o[1], o[2], o[3]));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (at + (uint32_t)e >= lead && at + (uint32_t)e - lead < span) out[j * 4 + (uint64_t)e] = o[e];
+            }
         }
     }
 }

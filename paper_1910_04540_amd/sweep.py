@@ -10,6 +10,11 @@ reduction ops; floating point has no such comparator (it needs bit operations), 
 
 Prints one row per (format, rounding, size): microseconds per call for both approaches and their
 ratio.  Nearest rounding of the comparator is checked against the fused result on every size.
+
+    python -m paper_1910_04540_amd.sweep --block-shapes
+
+times block floating point with one block per row over row lengths from 1 to the whole tensor
+(64 Mi elements in all, three rotating buffer sets), to show which kernel form serves which shape.
 """
 from __future__ import annotations
 
@@ -56,16 +61,50 @@ def _time(fn, reps):
     return a.elapsed_time(b) * 1e3 / reps
 
 
+BLOCK_ROW_LENGTHS = [1, 3, 4, 10, 16, 27, 64, 100, 256, 1000, 1001, 1024, 4096, 4098, 16384, 16388, 25088, 65536,
+                     1 << 20, 1 << 24, 1 << 26]
+
+
+def block_shapes() -> int:
+    """Per-row block quantize of 64 Mi elements for a range of row lengths."""
+    total = 1 << 26
+    xs = [torch.randn(total, device="cuda") for _ in range(3)]
+    outs = [torch.empty(total, device="cuda") for _ in range(3)]
+    print(f"{'rows':>10} {'row length':>10} | {'nearest us':>10} {'% of 8 TB/s':>11} | {'stochastic us':>13} {'% of 8 TB/s':>11}")
+    for cols in BLOCK_ROW_LENGTHS:
+        rows = total // cols
+        n = rows * cols
+        ws = torch.empty(max(Q.block_workspace_bytes(n, 1, rows, cols), 16), dtype=torch.uint8, device="cuda")
+        cells = []
+        for mode in (Q.RN_EVEN, Q.STOCHASTIC):
+            turn = [0]
+
+            def call():
+                k = turn[0] % 3
+                turn[0] += 1
+                Q.block_quantize(xs[k][:n], 1, rows, cols, 8, mode, 0, 1, 0, out=outs[k][:n], workspace=ws)
+
+            for _ in range(100):
+                call()
+            us = _time(call, 100)
+            cells.append((us, n * 8 / us / 1e3 / 80.0))
+        print(f"{rows:>10} {cols:>10} | {cells[0][0]:10.1f} {cells[0][1]:11.1f} | {cells[1][0]:13.1f} {cells[1][1]:11.1f}", flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--min-log2", type=int, default=10)
     ap.add_argument("--max-log2", type=int, default=28)
     ap.add_argument("--json", action="store_true")
+    ap.add_argument("--block-shapes", action="store_true")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         print("the sweep needs a GPU", file=sys.stderr)
         return 2
     Q.lib()
+    if args.block_shapes:
+        return block_shapes()
     rows = []
     base = torch.from_numpy(W.normal_tensor(1 << 20, seed=21)).cuda()
     for lg in range(args.min_log2, args.max_log2 + 1, 2):

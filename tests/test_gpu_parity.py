@@ -229,6 +229,41 @@ def test_block_row_shapes(rows, cols, rounding):
     _block_case(x, 1, rows, cols, 8, rounding)
 
 
+@pytest.mark.parametrize("rounding", [RN_AWAY, STOCHASTIC])
+@pytest.mark.parametrize("rows,cols,short", [(70000, 1, 0), (50001, 2, 1), (40000, 3, 2), (30000, 5, 0), (20000, 10, 3),
+                                             (9000, 27, 0), (700, 1001, 500), (50, 4098, 0), (9, 8190, 1), (5, 16377, 0),
+                                             (5, 16378, 7), (3, 16379, 0), (2, 16383, 16000), (3000, 4095, 0)])
+def test_block_lengths_that_are_not_whole_groups(rows, cols, short, rounding):
+    """Contiguous blocks whose length is not a multiple of four, so that the tensor's groups of four
+    straddle blocks and workgroups share their first and last group; a short last block; the same
+    from a misaligned address and in place."""
+    n = rows * cols - short
+    x = W.row_scaled_matrix(rows, cols, seed=rows + cols).reshape(-1)[:n].copy()
+    x[n // 2] = np.float32(-1.0e30)
+    want = R.block_quantize(x, 1, rows, cols, 8, rounding, 0, 21, 5)
+    assert_bit_equal(host(Q.block_quantize(dev(x), 1, rows, cols, 8, rounding, 0, 21, 5)), want, f"{rows} blocks of {cols}")
+    pad = dev(np.concatenate([np.zeros(3, np.float32), x, np.zeros(2, np.float32)]))
+    view = pad[3:3 + n]
+    assert_bit_equal(host(Q.block_quantize(view, 1, rows, cols, 8, rounding, 0, 21, 5)), want, "from a misaligned address")
+    Q.block_quantize(view, 1, rows, cols, 8, rounding, 0, 21, 5, out=view)
+    full = host(pad)
+    assert_bit_equal(full[3:3 + n], want, "in place")
+    assert not full[:3].any() and not full[3 + n:].any()
+
+
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("rows,cols,short", [(600, 20000, 0), (1100, 16388, 100), (270, 65536, 0), (530, 32772, 5000)])
+def test_block_many_long_rows(rows, cols, short, rounding):
+    """More rows of 16 Ki to 64 Ki elements than the chip holds at once: one 1024-thread workgroup per row."""
+    n = rows * cols - short
+    x = W.row_scaled_matrix(rows, cols, seed=rows).reshape(-1)[:n].copy()
+    want = R.block_quantize(x, 1, rows, cols, 8, rounding, 0, 8, 1)
+    d = dev(x)
+    assert_bit_equal(host(Q.block_quantize(d, 1, rows, cols, 8, rounding, 0, 8, 1)), want, f"{rows} rows of {cols}")
+    Q.block_quantize(d, 1, rows, cols, 8, rounding, 0, 8, 1, out=d)
+    assert_bit_equal(host(d), want, "in place")
+
+
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
 @pytest.mark.parametrize("n", [1, 3, 1000, 8192, 8193, 100003, (1 << 20) + 4, 3 * (1 << 20) + 1])
 def test_block_whole_tensor(n, rounding):
