@@ -23,19 +23,26 @@ __device__ __forceinline__ uint64_t linear_block() { return (uint64_t)blockIdx.y
 __device__ __forceinline__ uint64_t linear_block_xz() { return (uint64_t)blockIdx.z * gridDim.x + blockIdx.x; }
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_at_dword __attribute__((aligned(4)));     // a group at an address that is only dword aligned
 
-__device__ __forceinline__ uint4 to_uint4(const u32x4& v) { return make_uint4(v.x, v.y, v.z, v.w); }
+__device__ __forceinline__ uint4 to_uint4(u32x4 v) { return make_uint4(v.x, v.y, v.z, v.w); }
 __device__ __forceinline__ u32x4 to_u32x4(const uint4& v) { return u32x4{v.x, v.y, v.z, v.w}; }
 
 // ---------------------------------------------------------------------------------------------
 // Group access: elements [4*j, 4*j+4) of an array whose valid elements end at `end`.
-// VEC: the array is 16-byte aligned, so a whole group is one dwordx4 access.
+// VEC: the array is 16-byte aligned.  A whole group is one dwordx4 access either way (global
+// memory takes multi-dword accesses at any dword-aligned address; a misaligned one merely touches
+// one more cache line per wavefront); only a group cut off by `end` goes element by element.
 // ---------------------------------------------------------------------------------------------
 template <bool VEC>
 __device__ __forceinline__ uint4 load_group(const uint32_t* p, uint64_t j, uint64_t end)
 {
     const uint64_t i = j * 4;
-    if (VEC && i + 4 <= end) return to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + i)));
+    if (i + 4 <= end) {
+        if (VEC) return to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p + i)));
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_at_dword*>(p + i));
+        return to_uint4(v);
+    }
     uint4 v = {0u, 0u, 0u, 0u};
     if (i + 0 < end) v.x = p[i + 0];
     if (i + 1 < end) v.y = p[i + 1];
@@ -48,8 +55,9 @@ template <bool VEC>
 __device__ __forceinline__ void store_group(uint32_t* p, uint64_t j, uint64_t end, const uint4& v)
 {
     const uint64_t i = j * 4;
-    if (VEC && i + 4 <= end) {
-        __builtin_nontemporal_store(to_u32x4(v), reinterpret_cast<u32x4*>(p + i));
+    if (i + 4 <= end) {
+        if (VEC) __builtin_nontemporal_store(to_u32x4(v), reinterpret_cast<u32x4*>(p + i));
+        else __builtin_nontemporal_store(to_u32x4(v), reinterpret_cast<u32x4_at_dword*>(p + i));
         return;
     }
     if (i + 0 < end) p[i + 0] = v.x;
