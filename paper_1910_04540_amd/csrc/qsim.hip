@@ -81,6 +81,8 @@ static int launch_elementwise_rt(const float* in, float* out, uint64_t n, const 
 struct BlockSchedule {
     bool one_launch;       // contiguous blocks small enough for one team or workgroup each
     SliceGeom sg;          // otherwise: two launches over slices
+    bool flat;             // outer > 1 and short rows: the flat form (any alignment)
+    FlatGeom fg;
     bool column;           // outer > 1 and rows made of whole groups: the column form (aligned arrays)
     ColumnGeom cg;
     size_t column_bytes;   // scratch of the column form: column maxima, then block maxima
@@ -95,6 +97,8 @@ constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
 constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
 constexpr uint64_t kColumnThreads = 1ull << 19;  // threads the column form aims for
+constexpr uint64_t kFlatWorkgroups = 1024;       // workgroups of the flat form (four per CU)
+constexpr uint32_t kFlatParts = 32;              // parts of its first fold
 constexpr uint64_t kMultiTiles = 1ull << 30;     // tiles of one multi-tensor launch (running counts are 32-bit)
 
 static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner)
@@ -116,6 +120,27 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
     // the single-pass form keeps its counter and one slot per workgroup in the same scratch
     const size_t resident = (size_t)(kSyncSlots0 + kMaxResidentWgs) * sizeof(uint32_t);
     if (outer == 1 && s.workspace < resident) s.workspace = resident;
+    // the flat form: short rows, few enough blocks for a table in LDS
+    const unsigned __int128 row128 = (unsigned __int128)nblocks * inner;
+    if (outer > 1 && row128 <= kFlatMaxRow && nblocks <= (uint64_t)kFlatMaxBlocks) {
+        s.flat = true;
+        FlatGeom& fg = s.fg;
+        fg.n = n;
+        fg.groups = (n + 3) / 4;
+        fg.row = (uint32_t)row128;
+        fg.inner = (uint32_t)inner;
+        fg.nblocks = (uint32_t)nblocks;
+        fg.magic_row = fg.row > 1 ? (uint32_t)((1ull << 32) / fg.row) + 1u : 0u;
+        fg.magic_inner = fg.inner > 1 ? (uint32_t)((1ull << 32) / fg.inner) + 1u : 0u;
+        const uint64_t steps = (fg.groups + kFlatStepGroups - 1) / kFlatStepGroups;
+        const uint64_t wgs = steps < kFlatWorkgroups ? steps : kFlatWorkgroups;
+        fg.groups_per_wg = (steps + wgs - 1) / wgs * kFlatStepGroups;
+        fg.wgs = (uint32_t)((fg.groups + fg.groups_per_wg - 1) / fg.groups_per_wg);
+        fg.copies = 1;
+        while (fg.copies < 64 && 2 * fg.copies * fg.nblocks <= (uint32_t)kFlatMaxBlocks) fg.copies *= 2;
+        const size_t flat_bytes = (size_t)(kFlatWorkgroups + kFlatParts + 1) * nblocks * sizeof(uint32_t);
+        if (s.workspace < flat_bytes) s.workspace = flat_bytes;
+    }
     // the column form: rows of whole groups, short enough for 32-bit column arithmetic.  It is for
     // short blocks (a thread walking down a column jumps a whole row per step, which only pays when
     // the alternative cannot use whole groups or would do a division per group of a short segment);
@@ -294,6 +319,27 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
                            partial, s.sg, wl, symmetric, key);
+    } else if (s.flat && !(vec && g.inner >= 64) &&
+               (!(s.column && aligned16(in) && aligned16(out)) || g.nblocks < 64 || s.fg.row < 2048)) {
+        // short rows, unless long aligned segments stream well through the slice kernels: always when
+        // the column form cannot run; otherwise where that form is weak (few blocks make its fold
+        // serial, short rows give it few threads per row)
+        const FlatGeom& fg = s.fg;
+        uint32_t* folded_once = partial + (size_t)kFlatWorkgroups * fg.nblocks;
+        uint32_t* blockmax = folded_once + (size_t)kFlatParts * fg.nblocks;
+        const unsigned bx = (fg.nblocks + kThreads - 1) / kThreads;
+        hipLaunchKernelGGL(block_flat_max_kernel, dim3(fg.wgs), dim3(kThreads), 0, stream, pin, partial, fg);
+        if (fg.wgs > kFlatParts) {
+            hipLaunchKernelGGL(block_fold_rows_kernel, dim3(bx, kFlatParts), dim3(kThreads), 0, stream, partial, folded_once,
+                               fg.nblocks, fg.wgs, kFlatParts);
+            hipLaunchKernelGGL(block_fold_rows_kernel, dim3(bx, 1), dim3(kThreads), 0, stream, folded_once, blockmax, fg.nblocks,
+                               kFlatParts, 1u);
+        } else {
+            hipLaunchKernelGGL(block_fold_rows_kernel, dim3(bx, 1), dim3(kThreads), 0, stream, partial, blockmax, fg.nblocks,
+                               fg.wgs, 1u);
+        }
+        hipLaunchKernelGGL((block_flat_apply_kernel<MODE>), dim3(fg.wgs), dim3(kThreads), 0, stream, pin, pout, blockmax, fg, wl,
+                           symmetric, key);
     } else if (s.column && aligned16(in) && aligned16(out)) {
         const ColumnGeom& cg = s.cg;
         uint4* colmax = reinterpret_cast<uint4*>(workspace);

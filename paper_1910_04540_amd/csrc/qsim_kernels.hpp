@@ -563,6 +563,166 @@ __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint
     }
 }
 
+// Blocks along an inner dimension (outer > 1) with SHORT rows (nblocks * inner <= 61,440 elements,
+// nblocks <= 4096), any inner, any alignment: the "flat" form.  The tensor is walked in its own
+// groups of four, front to back, by a fixed number of workgroups that each own one contiguous
+// range; the block of an element follows from its position in the row,
+//     b = ((first position of the step + offset) mod row) div inner,
+// both by one multiply-high with a host-made reciprocal (exact below 2^16).  Block maxima are
+// collected in an LDS table per workgroup (ds_max), written out as partial[workgroup][block]
+// (no atomics in memory, nothing to initialise), folded by block_fold_rows_kernel in two steps,
+// and pass 2 walks the same ranges with the finished maxima in LDS.
+constexpr int kFlatMaxBlocks = 4096;
+constexpr uint32_t kFlatMaxRow = 61440;                   // row + one step of 4096 elements stays below 2^16
+constexpr int kFlatGpt = 4;                               // groups per thread and step
+constexpr uint32_t kFlatStepGroups = kThreads * kFlatGpt;   // 4096 elements per step
+
+struct FlatGeom {
+    uint64_t n, groups;          // elements, groups of four
+    uint64_t groups_per_wg;      // a multiple of kFlatStepGroups
+    uint32_t row, inner, nblocks;
+    uint32_t magic_row, magic_inner;   // floor(2^32 / d) + 1 (unused when d == 1)
+    uint32_t wgs;
+    uint32_t copies;             // copies of the LDS table in pass 1: a power of two, 1..64, copies * nblocks <= 4096
+};
+
+__device__ __forceinline__ uint32_t flat_block(const FlatGeom& fg, uint32_t pos /* < 2^16 */)
+{
+    const uint32_t in_row = fg.row == 1u ? 0u : pos - __umulhi(pos, fg.magic_row) * fg.row;
+    return fg.inner == 1u ? in_row : __umulhi(in_row, fg.magic_inner);
+}
+
+// The groups of one step.  A step that lies wholly inside the array (all but the last) issues its
+// loads back to back with nothing in between, so that all of them are in flight together.
+__device__ __forceinline__ void flat_load_step(const uint32_t* in, uint64_t base, const FlatGeom& fg, uint4 (&v)[kFlatGpt])
+{
+    if ((base + kFlatStepGroups) * 4 <= fg.n) {                              // wave-uniform
+        const u32x4_at_dword* p = reinterpret_cast<const u32x4_at_dword*>(in + base * 4) + threadIdx.x;
+#pragma unroll
+        for (int k = 0; k < kFlatGpt; ++k) {
+            const u32x4 w = __builtin_nontemporal_load(p + k * kThreads);
+            v[k] = to_uint4(w);
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < kFlatGpt; ++k) {
+            const uint64_t j = base + threadIdx.x + (uint64_t)k * kThreads;
+            v[k] = make_uint4(0u, 0u, 0u, 0u);
+            if (j < fg.groups) v[k] = load_group<false>(in, j, fg.n);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void block_flat_max_kernel(const uint32_t* in, uint32_t* partial, FlatGeom fg)
+{
+    // Few blocks mean many lanes per block, and same-address LDS atomics of one instruction are
+    // carried out one after the other: so the table is replicated, lane l works on copy l mod copies
+    // (copies * nblocks <= 4096), and the copies are folded at the end.
+    __shared__ uint32_t table[kFlatMaxBlocks];
+    const uint32_t copies = fg.copies;
+    for (uint32_t t = threadIdx.x; t < fg.nblocks * copies; t += kThreads) table[t] = 0u;
+    __syncthreads();
+    uint32_t* mine = table + (threadIdx.x & (copies - 1u)) * fg.nblocks;
+    // steps are dealt out round-robin, so that at any moment the workgroups together read one
+    // contiguous front of the tensor
+    const uint64_t g1 = fg.groups;
+    for (uint64_t base = (uint64_t)blockIdx.x * kFlatStepGroups; base < g1; base += (uint64_t)fg.wgs * kFlatStepGroups) {
+        const uint32_t pos0 = (uint32_t)((base * 4) % fg.row);            // wave-uniform
+        uint4 v[kFlatGpt];
+        flat_load_step(in, base, fg, v);
+#pragma unroll
+        for (int k = 0; k < kFlatGpt; ++k) {
+            const uint64_t j = base + threadIdx.x + (uint64_t)k * kThreads;
+            if (j < g1) {
+                const uint32_t off = (threadIdx.x + (uint32_t)k * kThreads) * 4u;
+                if (fg.inner % 4u == 0u) {                                    // a group never straddles blocks
+                    atomicMax(&mine[flat_block(fg, pos0 + off)], max4_mag(v[k]));
+                } else {
+                    const uint32_t mag[4] = {v[k].x & 0x7fffffffu, v[k].y & 0x7fffffffu, v[k].z & 0x7fffffffu,
+                                             v[k].w & 0x7fffffffu};
+                    uint32_t prev = flat_block(fg, pos0 + off), m = mag[0];
+#pragma unroll
+                    for (uint32_t e = 1; e < 4; ++e) {
+                        // elements past the end read as zero; their block number is still a valid one
+                        const uint32_t b = flat_block(fg, pos0 + off + e);
+                        if (b != prev) {
+                            atomicMax(&mine[prev], m);
+                            m = 0u;
+                            prev = b;
+                        }
+                        m = m > mag[e] ? m : mag[e];
+                    }
+                    atomicMax(&mine[prev], m);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (uint32_t t = threadIdx.x; t < fg.nblocks; t += kThreads) {
+        uint32_t m = table[t];
+        for (uint32_t c = 1; c < copies; ++c) {
+            const uint32_t a = table[c * fg.nblocks + t];
+            m = m > a ? m : a;
+        }
+        partial[(uint64_t)blockIdx.x * fg.nblocks + t] = m;
+    }
+}
+
+// dst[p * nblocks + b] = max over the rows k of part p of src[k * nblocks + b]; `rows` rows are cut
+// into `parts` parts.  One thread per (p, b): neighbouring threads read neighbouring blocks.
+__global__ __launch_bounds__(kThreads) void block_fold_rows_kernel(const uint32_t* src, uint32_t* dst, uint32_t nblocks,
+                                                                   uint32_t rows, uint32_t parts)
+{
+    const uint32_t b = blockIdx.x * kThreads + threadIdx.x;
+    const uint32_t p = blockIdx.y;
+    if (b >= nblocks) return;
+    const uint32_t per = (rows + parts - 1) / parts;
+    const uint32_t k0 = p * per;
+    const uint32_t k1 = (k0 + per < rows) ? k0 + per : rows;
+    uint32_t m = 0;
+    for (uint32_t k = k0; k < k1; ++k) {
+        const uint32_t a = src[(uint64_t)k * nblocks + b];
+        m = m > a ? m : a;
+    }
+    dst[(uint64_t)p * nblocks + b] = m;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void block_flat_apply_kernel(const uint32_t* in, uint32_t* out, const uint32_t* blockmax,
+                                                                    FlatGeom fg, int wl, int symmetric, RngKey key)
+{
+    __shared__ uint32_t table[kFlatMaxBlocks];
+    for (uint32_t t = threadIdx.x; t < fg.nblocks; t += kThreads) table[t] = blockmax[t];
+    __syncthreads();
+    // steps are dealt out round-robin, so that at any moment the workgroups together read one
+    // contiguous front of the tensor
+    const uint64_t g1 = fg.groups;
+    for (uint64_t base = (uint64_t)blockIdx.x * kFlatStepGroups; base < g1; base += (uint64_t)fg.wgs * kFlatStepGroups) {
+        const uint32_t pos0 = (uint32_t)((base * 4) % fg.row);            // wave-uniform
+        uint4 v[kFlatGpt];
+        flat_load_step(in, base, fg, v);
+#pragma unroll
+        for (int k = 0; k < kFlatGpt; ++k) {
+            const uint64_t j = base + threadIdx.x + (uint64_t)k * kThreads;
+            if (j < g1) {
+                const uint32_t off = (threadIdx.x + (uint32_t)k * kThreads) * 4u;
+                Words4 r = {{0u, 0u, 0u, 0u}};
+                if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+                uint4 o;
+                if (fg.inner % 4u == 0u) {
+                    o = quantize_group_to_grid<MODE>(v[k], block_plan(table[flat_block(fg, pos0 + off)], wl, symmetric), r);
+                } else {
+                    o.x = quantize_to_grid<MODE>(v[k].x, block_plan(table[flat_block(fg, pos0 + off)], wl, symmetric), r.w[0]);
+                    o.y = quantize_to_grid<MODE>(v[k].y, block_plan(table[flat_block(fg, pos0 + off + 1u)], wl, symmetric), r.w[1]);
+                    o.z = quantize_to_grid<MODE>(v[k].z, block_plan(table[flat_block(fg, pos0 + off + 2u)], wl, symmetric), r.w[2]);
+                    o.w = quantize_to_grid<MODE>(v[k].w, block_plan(table[flat_block(fg, pos0 + off + 3u)], wl, symmetric), r.w[3]);
+                }
+                store_group<false>(out, j, fg.n, o);
+            }
+        }
+    }
+}
+
 // Contiguous blocks spread over several workgroups (outer == 1, inner % 4 == 0, aligned arrays):
 // the streaming forms of the two passes.  Workgroup (s, b) owns slice s of block b in both passes
 // and walks it in steps of 4096 elements with four loads in flight per thread.  Pass 1 writes the

@@ -291,6 +291,30 @@ def test_block_over_an_inner_dimension(shape, dim, rounding):
     _block_case(x, outer, shape[dim], inner, 8, rounding)
 
 
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("outer,nblocks,inner", [(5000, 3, 300), (1048577, 5, 1), (9000, 4096, 1), (300000, 3, 7),
+                                                 (3, 32768, 1), (600, 128, 256), (70001, 1, 3), (2, 1, 1), (100001, 255, 1), (200, 2, 16385),
+                                                 (90, 61440, 1), (70, 4, 15360), (50, 3, 20479)])
+def test_block_short_rows_many_of_them(outer, nblocks, inner, rounding):
+    """Blocks along an inner dimension with rows of at most 60 Ki elements: the flat walk with the
+    block table in LDS, several steps per workgroup, ragged tails, also from a misaligned address
+    and in place."""
+    g = np.random.Generator(np.random.PCG64(outer + nblocks + inner))
+    n = outer * nblocks * inner
+    scale = np.exp2(g.integers(-10, 10, size=nblocks)).astype(np.float32)
+    x = (g.standard_normal((outer, nblocks, inner), dtype=np.float32) * scale[None, :, None]).astype(np.float32)
+    x.reshape(-1)[g.integers(0, n)] = np.float32(3.0e33)
+    want = R.block_quantize(x, outer, nblocks, inner, 8, rounding, 0, 17, 3).reshape(-1)
+    assert_bit_equal(host(Q.block_quantize(dev(x.reshape(-1)), outer, nblocks, inner, 8, rounding, 0, 17, 3)), want,
+                     f"[{outer},{nblocks},{inner}]")
+    pad = dev(np.concatenate([np.zeros(1, np.float32), x.reshape(-1), np.zeros(3, np.float32)]))
+    view = pad[1:1 + n]
+    Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 17, 3, out=view)
+    full = host(pad)
+    assert_bit_equal(full[1:1 + n], want, "in place from a misaligned address")
+    assert not full[:1].any() and not full[1 + n:].any()
+
+
 def test_block_misaligned_and_inplace():
     x = W.row_scaled_matrix(1, 50000 + 8, seed=11).reshape(-1)
     for off, n, nb, inner in [(1, 50000, 50, 1000), (3, 49999, 1, 49999), (0, 50000, 50, 1000), (2, 50002, 1, 50002)]:
