@@ -81,6 +81,9 @@ static int launch_elementwise_rt(const float* in, float* out, uint64_t n, const 
 struct BlockSchedule {
     bool one_launch;       // contiguous blocks small enough for one team or workgroup each
     SliceGeom sg;          // otherwise: two launches over slices
+    bool cluster;          // many contiguous blocks of up to 64 register-resident slices each: single pass per block
+    bool strided_cluster;  // outer > 1, aligned segments of >= 64 elements, blocks of up to 256 slices: the same
+    StridedClusterGeom scg;
     bool flat;             // outer > 1 and short rows: the flat form (any alignment)
     FlatGeom fg;
     bool column;           // outer > 1 and rows made of whole groups: the column form (aligned arrays)
@@ -92,6 +95,9 @@ struct BlockSchedule {
 constexpr uint64_t kCachedMaxInner = 16384;      // 256 threads x 16 groups x 4 elements
 constexpr int kWideThreads = 1024;
 constexpr uint64_t kWideCachedMaxInner = 65536;  // 1024 threads x 16 groups x 4 elements
+constexpr uint64_t kClusterSliceLen = 4ull * kThreads * 16;     // 16 groups per thread
+constexpr uint64_t kClusterMaxSlices = 64;       // one lane of a wavefront watches each slot
+constexpr uint64_t kClusterMaxWgs = 1ull << 22;
 constexpr uint32_t kMaxSlices = 1024;
 constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
@@ -120,6 +126,29 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
     // the single-pass form keeps its counter and one slot per workgroup in the same scratch
     const size_t resident = (size_t)(kSyncSlots0 + kMaxResidentWgs) * sizeof(uint32_t);
     if (outer == 1 && s.workspace < resident) s.workspace = resident;
+    // the same kernel meeting block by block: one slot per workgroup of 16,384 elements
+    const uint64_t cluster_slices = (inner + kClusterSliceLen - 1) / kClusterSliceLen;
+    if (outer == 1 && inner > kWideCachedMaxInner && cluster_slices <= kClusterMaxSlices &&
+        nblocks * cluster_slices <= kClusterMaxWgs) {
+        s.cluster = true;
+        const size_t bytes = (size_t)(kSyncSlots0 + nblocks * cluster_slices) * sizeof(uint32_t);
+        if (s.workspace < bytes) s.workspace = bytes;
+    }
+    if (outer > 1 && inner % 4 == 0 && inner >= 64 && inner <= (1ull << 22) &&
+        s.sg.block_len <= (uint64_t)kStridedMaxSlices * kStridedSliceLen) {
+        const uint64_t slices_each = (s.sg.block_len + kStridedSliceLen - 1) / kStridedSliceLen;
+        if (nblocks * slices_each <= kClusterMaxWgs) {
+            s.strided_cluster = true;
+            s.scg.nblocks = nblocks;
+            s.scg.block_len = (uint32_t)s.sg.block_len;
+            s.scg.slices = (uint32_t)slices_each;
+            s.scg.inner = (uint32_t)inner;
+            s.scg.magic_inner = (uint32_t)((1ull << 32) / inner) + 1u;
+            s.scg.total_wgs = (uint32_t)(nblocks * slices_each);
+            const size_t bytes = (size_t)s.scg.total_wgs * sizeof(uint32_t);
+            if (s.workspace < bytes) s.workspace = bytes;
+        }
+    }
     // the flat form: short rows, few enough blocks for a table in LDS
     const unsigned __int128 row128 = (unsigned __int128)nblocks * inner;
     if (outer > 1 && row128 <= kFlatMaxRow && nblocks <= (uint64_t)kFlatMaxBlocks) {
@@ -223,6 +252,28 @@ static bool try_resident(const uint32_t* in, uint32_t* out, const BlockGeom& g, 
     return true;
 }
 
+// The single-pass form block by block, for more blocks than the chip holds at once (see the kernel).
+template <int MODE>
+static bool try_cluster(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
+                        uint32_t* sync, hipStream_t stream)
+{
+    const uint64_t slices = (g.inner + kClusterSliceLen - 1) / kClusterSliceLen;
+    if (resident_capacity<MODE, 16>() < kClusterMaxSlices) return false;     // a block's workgroups must fit together
+    ResidentGeom rg;
+    rg.sg.g = g;
+    rg.sg.block_len = g.inner;
+    rg.sg.slice_len = kClusterSliceLen;
+    rg.sg.slices = (uint32_t)slices;
+    rg.total_wgs = (uint32_t)(slices * g.nblocks);
+    rg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
+    uint32_t* slots = sync + kSyncSlots0;
+    hipLaunchKernelGGL(block_sync_clear_kernel, folded((rg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
+                       slots, rg.total_wgs);
+    hipLaunchKernelGGL((block_resident_kernel<MODE, 16, true>), folded(rg.total_wgs), dim3(kThreads), 0, stream, in, out, sync,
+                       rg, wl, symmetric, key);
+    return true;
+}
+
 template <int MODE>
 static bool try_resident_any(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
                              uint32_t* sync, hipStream_t stream)
@@ -315,10 +366,19 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                                    stream, pin, pout, g, 10, wl, symmetric, key);
             return launch_status();
         }
+        if (s.cluster && try_cluster<MODE>(pin, pout, g, wl, symmetric, key, partial, stream)) return launch_status();
         const unsigned by = (unsigned)(g.nblocks < 65535 ? g.nblocks : 65535);
         hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
                            partial, s.sg, wl, symmetric, key);
+    } else if (vec && s.strided_cluster && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
+        // single pass, block by block (see the kernel): the workgroups of a block must fit together
+        StridedClusterGeom cg = s.scg;
+        cg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
+        hipLaunchKernelGGL(block_sync_clear_kernel, folded((cg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
+                           partial, cg.total_wgs);
+        hipLaunchKernelGGL((block_cluster_strided_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
+                           partial, cg, wl, symmetric, key);
     } else if (s.flat && !(vec && g.inner >= 64) &&
                (!(s.column && aligned16(in) && aligned16(out)) || g.nblocks < 64 || s.fg.row < 2048)) {
         // short rows, unless long aligned segments stream well through the slice kernels: always when

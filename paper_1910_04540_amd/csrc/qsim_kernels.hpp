@@ -859,7 +859,15 @@ struct ResidentGeom {
 
 // With 16 groups per thread the kernel must keep to 128 VGPRs (four waves per SIMD, four workgroups
 // per CU): that is what lets 1024 workgroups hold a 16 Mi-element tensor.
-template <int MODE, int GPT>
+//
+// CLUSTER: the tensor as a whole does not fit, but each block does (at most 64 slices), and the
+// grid may be far larger than the chip.  Only the workgroups of one block meet: each publishes its
+// slot and polls the slots of its block (one lane per slot) instead of the counters and flags.
+// Workgroups are numbered block by block and dispatched in that order, so the workgroups of the
+// lowest unfinished block are always among the resident ones and the grid drains block after
+// block; should the dispatcher ever do otherwise, the bounded wait and the exact fallback below
+// still end every workgroup with the right result.
+template <int MODE, int GPT, bool CLUSTER = false>
 __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_kernel(const uint32_t* in, uint32_t* out, uint32_t* sync,
                                                                   ResidentGeom rg, int wl, int symmetric, RngKey key)
 {
@@ -870,7 +878,8 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
     __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
     __shared__ uint32_t lds[kThreads / 64];
     __shared__ uint32_t shared_word;
-    const uint32_t wg = blockIdx.x;
+    const uint32_t wg = CLUSTER ? (uint32_t)linear_block() : blockIdx.x;
+    if (CLUSTER && wg >= rg.total_wgs) return;                   // the whole workgroup leaves together
     const uint32_t b = wg / rg.sg.slices, s = wg - b * rg.sg.slices;
     const SliceView sv = slice_view(rg.sg, b, s);
     uint32_t* slots = sync + kSyncSlots0;
@@ -915,7 +924,24 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
     // nothing else has to become visible between workgroups, so no release or acquire fence (each
     // of which writes back or invalidates a whole L2 on this multi-die part) is needed.  Order is
     // kept by waiting for the returned value of one atomic before the next one is issued.
-    if (threadIdx.x == 0) {
+    if (CLUSTER) {
+        if (threadIdx.x == 0) {
+            uint32_t old = __hip_atomic_exchange(&slots[wg], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
+        }
+        if (threadIdx.x < 64) {
+            // the first wavefront polls: lane i watches slot i of the block (slices <= 64)
+            const uint32_t* watched = slots + (uint64_t)b * rg.sg.slices + (threadIdx.x < rg.sg.slices ? threadIdx.x : 0u);
+            const uint64_t t0 = __builtin_amdgcn_s_memrealtime();        // 100 MHz
+            const uint64_t budget = (uint64_t)rg.wait_us * 100u;
+            bool all = __all((__hip_atomic_load(watched, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kPublished) != 0u);
+            while (!all && __builtin_amdgcn_s_memrealtime() - t0 < budget) {
+                __builtin_amdgcn_s_sleep(2);
+                all = __all((__hip_atomic_load(watched, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kPublished) != 0u);
+            }
+            if (threadIdx.x == 0) shared_word = all ? 1u : 0u;
+        }
+    } else if (threadIdx.x == 0) {
         uint32_t old = __hip_atomic_exchange(&slots[wg], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");       // the slot is published before we count
         const uint32_t group = wg / kSyncGroup;
@@ -985,6 +1011,158 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
             const uint4 o = quantize_group_to_grid<MODE>(v[k], p, r);
             if (full) __builtin_nontemporal_store(to_u32x4(o), reinterpret_cast<u32x4*>(sout) + t);
             else store_group<true>(sout, (uint64_t)t, slice_end, o);
+        }
+    }
+}
+
+// The same block-by-block single pass for blocks along an inner dimension (outer > 1) made of
+// aligned segments of at least 64 elements (inner % 4 == 0): per-channel blocks of an
+// [N, C, H, W] tensor.  Slice s of block b is elements [s * 16384, ...) of the block's own
+// numbering t = o * inner + i; a group's place in the array follows from one division by `inner`
+// (multiply-high with a reciprocal rounded up, corrected by at most one).  Up to 256 slices per
+// block; every lane of the polling wavefront watches up to four slots.  `slots`: one word per
+// workgroup, zeroed before the launch.
+constexpr uint32_t kStridedSliceLen = 4u * kThreads * 16u;
+constexpr uint32_t kStridedMaxSlices = 256;
+
+struct StridedClusterGeom {
+    uint64_t nblocks;
+    uint32_t block_len;      // outer * inner, at most kStridedMaxSlices * kStridedSliceLen
+    uint32_t slices;
+    uint32_t inner;          // a multiple of 4, at least 64
+    uint32_t magic_inner;    // floor(2^32 / inner) + 1
+    uint32_t total_wgs;
+    uint32_t wait_us;
+};
+
+// Group number, in the array, of the group at element tt (a multiple of 4) of block b.
+__device__ __forceinline__ uint64_t strided_group(const StridedClusterGeom& cg, uint32_t b, uint32_t tt)
+{
+    uint32_t o = __umulhi(tt, cg.magic_inner);           // tt / inner or one more (tt < 2^22)
+    uint32_t i = tt - o * cg.inner;
+    if ((int32_t)i < 0) {
+        o -= 1u;
+        i += cg.inner;
+    }
+    return (((uint64_t)o * cg.nblocks + b) * cg.inner + i) >> 2;
+}
+
+__device__ __forceinline__ uint32_t strided_slice_groups(const StridedClusterGeom& cg, uint32_t s)
+{
+    const uint32_t t0 = s * kStridedSliceLen;
+    const uint32_t t1 = (cg.block_len - t0 < kStridedSliceLen) ? cg.block_len : t0 + kStridedSliceLen;
+    return (t1 - t0) / 4u;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(const uint32_t* in, uint32_t* out, uint32_t* slots,
+                                                                            StridedClusterGeom cg, int wl, int symmetric,
+                                                                            RngKey key)
+{
+    constexpr int GPT = 16;
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? 9 : 0;          // random words parked in LDS, as in the kernel above
+    __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
+    __shared__ uint32_t lds[kThreads / 64];
+    __shared__ uint32_t shared_word;
+    const uint32_t wg = (uint32_t)linear_block();
+    if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
+    const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
+    const uint32_t t0 = s * kStridedSliceLen;
+    const uint32_t ngroups = strided_slice_groups(cg, s);
+
+    uint4 v[GPT];
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (t < ngroups) {
+            const uint64_t j = strided_group(cg, b, t0 + 4u * t);
+            v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in) + j));
+            if (k < PRE) {
+                const Words4 r = random_words(j, key, 0u);
+                parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+            }
+        }
+    }
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t gm = max4_mag(v[k]);
+        m = m > gm ? m : gm;
+    }
+    m = workgroup_max(m, lds);
+
+    // relaxed device-scope atomics on words only atomics touch; order by waiting for returned values
+    uint32_t* mine = slots + (uint64_t)b * cg.slices;
+    if (threadIdx.x == 0) {
+        uint32_t old = __hip_atomic_exchange(&mine[s], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
+    }
+    if (threadIdx.x < 64) {
+        const uint64_t start = __builtin_amdgcn_s_memrealtime();     // 100 MHz
+        const uint64_t budget = (uint64_t)cg.wait_us * 100u;
+        bool all;
+        for (;;) {
+            bool ok = true;
+            for (uint32_t i = threadIdx.x; i < cg.slices; i += 64u)
+                ok = ok && (__hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kPublished) != 0u;
+            all = __all(ok);
+            if (all || __builtin_amdgcn_s_memrealtime() - start >= budget) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (threadIdx.x == 0) shared_word = all ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool all_arrived = shared_word != 0u;
+
+    uint32_t bm = 0;
+    if (all_arrived) {
+        for (uint32_t i = threadIdx.x; i < cg.slices; i += kThreads) {
+            const uint32_t a = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ~kPublished;
+            bm = bm > a ? bm : a;
+        }
+        bm = workgroup_max(bm, lds);
+    } else {
+        for (uint32_t i = 0; i < cg.slices; ++i) {
+            __syncthreads();
+            if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            uint32_t a = shared_word;
+            if (!(a & kPublished)) {
+                // the owner of slice i has not published, so it has not written any output yet:
+                // read its input; if the slot is still unpublished afterwards, the read was clean
+                uint32_t own = 0;
+                const uint32_t count = strided_slice_groups(cg, i);
+                for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
+                    const uint4 w = *(reinterpret_cast<const uint4*>(in) + strided_group(cg, b, i * kStridedSliceLen + 4u * t));
+                    const uint32_t gm = max4_mag(w);
+                    own = own > gm ? own : gm;
+                }
+                own = workgroup_max(own, lds);
+                __syncthreads();
+                if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __syncthreads();
+                a = (shared_word & kPublished) ? shared_word : own;
+            }
+            a &= ~kPublished;
+            bm = bm > a ? bm : a;
+        }
+    }
+
+    const GridPlan p = block_plan(bm, wl, symmetric);
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        if (t < ngroups) {
+            const uint64_t j = strided_group(cg, b, t0 + 4u * t);
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (k < PRE) {
+                const uint4 w = parked[k * kThreads + threadIdx.x];
+                r = Words4{{w.x, w.y, w.z, w.w}};
+            } else if (MODE == QSIM_STOCHASTIC) {
+                r = random_words(j, key, 0u);
+            }
+            __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + j);
         }
     }
 }

@@ -348,6 +348,68 @@ def test_block_single_pass_when_the_wait_runs_out(rounding):
         Q.set_barrier_wait_us(2000)
 
 
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("rows,cols,short", [(300, 70000, 0), (600, 65540, 30000), (40, 1048576, 0), (130, 262148, 100000)])
+def test_block_many_rows_that_each_fit_the_registers(rows, cols, short, rounding):
+    """More long rows than the chip holds at once, each of at most 64 register-resident slices: the
+    workgroups of a row meet among themselves, row after row."""
+    n = rows * cols - short
+    x = W.row_scaled_matrix(rows, cols, seed=rows + 1).reshape(-1)[:n].copy()
+    x[(rows // 2) * cols + cols - 5] = np.float32(9.0e20)        # a maximum that sits in one row's last slice only
+    want = R.block_quantize(x, 1, rows, cols, 8, rounding, 0, 4, 2)
+    d = dev(x)
+    assert_bit_equal(host(Q.block_quantize(d, 1, rows, cols, 8, rounding, 0, 4, 2)), want, f"{rows} rows of {cols}")
+    Q.block_quantize(d, 1, rows, cols, 8, rounding, 0, 4, 2, out=d)
+    assert_bit_equal(host(d), want, "in place")
+
+
+def test_block_row_by_row_single_pass_when_the_wait_runs_out():
+    """The same with the wait forced to zero: every workgroup derives the maxima of the slices that
+    have not been published from memory itself; exact, also in place."""
+    Q.set_barrier_wait_us(0)
+    try:
+        rows, cols = 300, 70000
+        x = W.row_scaled_matrix(rows, cols, seed=5).reshape(-1)
+        want = R.block_quantize(x, 1, rows, cols, 8, STOCHASTIC, 0, 4, 2)
+        d = dev(x)
+        assert_bit_equal(host(Q.block_quantize(d, 1, rows, cols, 8, STOCHASTIC, 0, 4, 2)), want, "out of place")
+        Q.block_quantize(d, 1, rows, cols, 8, STOCHASTIC, 0, 4, 2, out=d)
+        assert_bit_equal(host(d), want, "in place")
+    finally:
+        Q.set_barrier_wait_us(2000)
+
+
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("shape", [(32, 64, 3136), (64, 256, 3136), (64, 3, 65536), (1000, 40, 64), (7, 5, 16388), (3, 1100, 16384)])
+def test_block_per_channel_single_pass(shape, rounding):
+    """Blocks along an inner dimension made of aligned segments (per-channel blocks of an activation
+    tensor): the workgroups of a block meet among themselves, block after block; in place too."""
+    outer, nblocks, inner = shape
+    g = np.random.Generator(np.random.PCG64(sum(shape)))
+    scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
+    x = (g.standard_normal(shape, dtype=np.float32) * scale[None, :, None]).astype(np.float32)
+    x[outer - 1, nblocks // 2, inner - 1] = np.float32(-2.0e25)      # a maximum in a block's very last element
+    want = R.block_quantize(x, outer, nblocks, inner, 8, rounding, 0, 6, 1).reshape(-1)
+    d = dev(x.reshape(-1))
+    assert_bit_equal(host(Q.block_quantize(d, outer, nblocks, inner, 8, rounding, 0, 6, 1)), want, f"{shape}")
+    Q.block_quantize(d, outer, nblocks, inner, 8, rounding, 0, 6, 1, out=d)
+    assert_bit_equal(host(d), want, f"{shape} in place")
+
+
+def test_block_per_channel_single_pass_when_the_wait_runs_out():
+    Q.set_barrier_wait_us(0)
+    try:
+        shape = (32, 64, 3136)
+        x = W.lognormal_gradients(shape, seed=9)
+        want = R.block_quantize(x, *shape, 8, STOCHASTIC, 0, 6, 1).reshape(-1)
+        d = dev(x.reshape(-1))
+        assert_bit_equal(host(Q.block_quantize(d, *shape, 8, STOCHASTIC, 0, 6, 1)), want, "out of place")
+        Q.block_quantize(d, *shape, 8, STOCHASTIC, 0, 6, 1, out=d)
+        assert_bit_equal(host(d), want, "in place")
+    finally:
+        Q.set_barrier_wait_us(2000)
+
+
 @pytest.mark.parametrize("log2n", [20, 22, 23, 24])
 def test_block_single_pass_meets_without_waiting_out(log2n):
     """On an otherwise idle GPU every workgroup of the single-pass kernel gets a slot, so the
