@@ -176,7 +176,14 @@ def main() -> int:
             a_in[k].copy_(torch.roll(torch.from_numpy(g_host).cuda(), 7654321 * k))
         run("float_e5m10_nearest_even_gradients", lambda k: Q.float_quantize(
             a_in[k % NSETS], 5, 10, Q.RN_EVEN, Q.SATURATE | Q.SUBNORMAL, out=a_out[k % NSETS]), na)
-        del a_in, a_out
+        # the same [128, 256, 56, 56] tensor with one shared exponent per channel (dimension 1)
+        cn, cc, chw = 128, 256, 56 * 56
+        cws = torch.empty(max(Q.block_workspace_bytes(na, cn, cc, chw), 16), dtype=torch.uint8, device="cuda")
+        for mode, tag in ((Q.RN_EVEN, "nearest_even"), (Q.STOCHASTIC, "stochastic")):
+            run(f"block8_per_channel_128x256x56x56_{tag}", lambda k, mode=mode: Q.block_quantize(
+                a_in[k % NSETS], cn, cc, chw, 8, mode, 0, 1234, k, out=a_out[k % NSETS], workspace=cws), na,
+                extra={"note": "blocks along dimension 1; single pass, the workgroups of a channel meet among themselves"})
+        del a_in, a_out, cws
         torch.cuda.empty_cache()
 
         m_host = W.row_scaled_matrix()
@@ -191,7 +198,7 @@ def main() -> int:
                 m_in[k % NSETS], 1, rows, cols, 8, mode, 0, 1234, k, out=m_out[k % NSETS]), nm)
             run(f"block8_whole_tensor_{tag}", lambda k, mode=mode: Q.block_quantize(
                 m_in[k % NSETS], 1, 1, nm, 8, mode, 0, 1234, k, out=m_out[k % NSETS], workspace=ws), nm,
-                extra={"note": "fraction is against 8 B/element; the input is read twice"})
+                extra={"note": "single pass: 1024 resident workgroups hold the tensor in registers and meet once"})
         del m_in, m_out
         torch.cuda.empty_cache()
 
@@ -237,12 +244,17 @@ def main() -> int:
 
         threads = min(16, os.cpu_count() or 1)
         R.lib()
+        # whole passes over the headline tensor until about 15 s of CPU work have gone by
+        passes, dt = 0, 0.0
         t0 = time.perf_counter()
-        R.fixed_quantize(x_host, 8, 6, R.STOCHASTIC, R.SATURATE, seed=1234, threads=threads)
-        dt = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": n / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
-                                  "sample": f"the whole {n}-element tensor of the headline workload, one pass, "
-                                            f"split over {threads} threads ({dt:.2f} s wall)"}
+        while passes < 50 and dt * threads < 15.0:
+            R.fixed_quantize(x_host, 8, 6, R.STOCHASTIC, R.SATURATE, seed=1234, stream_id=passes, threads=threads)
+            passes += 1
+            dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": n * passes / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"{passes} passes over the whole {n}-element tensor of the headline workload, "
+                                            f"each split over {threads} threads ({dt:.2f} s wall, "
+                                            f"{dt * threads:.0f} s of CPU work)"}
     print(json.dumps(result))
     return 0
 
