@@ -75,9 +75,10 @@ static int launch_elementwise_rt(const float* in, float* out, uint64_t n, const 
 }
 
 // ---- block floating point ------------------------------------------------------------------
-// How a block-quantize call is carried out; decided on the host from the shape alone, so that
-// qsim_block_workspace_bytes and qsim_block_quantize always agree.  (Alignment can only move a
-// call from the register-cached form to the two-read form, neither of which needs scratch.)
+// How a block-quantize call may be carried out: every form the shape admits, decided on the host
+// from the shape alone, so that qsim_block_workspace_bytes and qsim_block_quantize always agree.
+// Which of them runs also depends on the alignment of the arrays and on the device; the scratch is
+// sized for the largest.
 struct BlockSchedule {
     bool one_launch;       // contiguous blocks small enough for one team or workgroup each
     SliceGeom sg;          // otherwise: two launches over slices
