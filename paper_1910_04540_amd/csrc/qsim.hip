@@ -104,6 +104,7 @@ constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
 constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
 constexpr uint64_t kColumnThreads = 1ull << 19;  // threads the column form aims for
+constexpr uint32_t kColumnParts = 8;             // slices left after the first, coalesced fold of its column maxima
 constexpr uint64_t kFlatWorkgroups = 1024;       // workgroups of the flat form (four per CU)
 constexpr uint32_t kFlatParts = 32;              // parts of its first fold
 constexpr uint64_t kMultiTiles = 1ull << 30;     // tiles of one multi-tensor launch (running counts are 32-bit)
@@ -190,7 +191,8 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         if (slices > 65535) slices = 65535;
         cg.rows_per_slice = (uint32_t)((outer + slices - 1) / slices);
         cg.slices = (uint32_t)((outer + cg.rows_per_slice - 1) / cg.rows_per_slice);
-        s.column_bytes = (size_t)cg.slices * (size_t)row * sizeof(uint32_t) + (size_t)nblocks * sizeof(uint32_t);
+        // column maxima of every slice, the same folded to kColumnParts slices, block maxima
+        s.column_bytes = ((size_t)cg.slices + kColumnParts) * (size_t)row * sizeof(uint32_t) + (size_t)nblocks * sizeof(uint32_t);
         if (s.workspace < s.column_bytes) s.workspace = s.column_bytes;
     }
     return s;
@@ -404,11 +406,22 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
     } else if (s.column && aligned16(in) && aligned16(out)) {
         const ColumnGeom& cg = s.cg;
         uint4* colmax = reinterpret_cast<uint4*>(workspace);
-        uint32_t* blockmax = partial + (size_t)cg.slices * cg.row_groups * 4;
+        const size_t row_words = (size_t)cg.row_groups * 4;
+        uint32_t* fewer = partial + (size_t)cg.slices * row_words;
+        uint32_t* blockmax = fewer + (size_t)kColumnParts * row_words;
         const dim3 cgrid((cg.row_groups + kThreads - 1) / kThreads, cg.slices);
         hipLaunchKernelGGL(block_column_max_kernel, cgrid, dim3(kThreads), 0, stream, pin, colmax, cg);
-        hipLaunchKernelGGL(block_column_fold_kernel, folded((cg.nblocks + kThreads / 64 - 1) / (kThreads / 64)), dim3(kThreads), 0,
-                           stream, partial, blockmax, cg);
+        const dim3 fold_grid = folded((cg.nblocks + kThreads / 64 - 1) / (kThreads / 64));
+        if (cg.slices > 2 * kColumnParts) {
+            // many slices: first a fold over slices with neighbouring threads on neighbouring columns
+            ColumnGeom few = cg;
+            few.slices = kColumnParts;
+            hipLaunchKernelGGL(block_fold_rows_kernel, dim3((unsigned)((row_words + kThreads - 1) / kThreads), kColumnParts),
+                               dim3(kThreads), 0, stream, partial, fewer, (uint32_t)row_words, cg.slices, kColumnParts);
+            hipLaunchKernelGGL(block_column_fold_kernel, fold_grid, dim3(kThreads), 0, stream, fewer, blockmax, few);
+        } else {
+            hipLaunchKernelGGL(block_column_fold_kernel, fold_grid, dim3(kThreads), 0, stream, partial, blockmax, cg);
+        }
         hipLaunchKernelGGL((block_column_apply_kernel<MODE>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax, cg, wl,
                            symmetric, key);
     } else if (vec) {

@@ -680,6 +680,7 @@ __global__ __launch_bounds__(kThreads) void block_fold_rows_kernel(const uint32_
     const uint32_t k0 = p * per;
     const uint32_t k1 = (k0 + per < rows) ? k0 + per : rows;
     uint32_t m = 0;
+#pragma unroll 8
     for (uint32_t k = k0; k < k1; ++k) {
         const uint32_t a = src[(uint64_t)k * nblocks + b];
         m = m > a ? m : a;
