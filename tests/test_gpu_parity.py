@@ -637,6 +637,15 @@ def test_full_workload_4_activations_and_gradients():
     assert 0.2 < float(sub.mean()) < 0.6 and float((np.abs(g) > 65504).mean()) > 0
 
 
+def test_full_workload_4_block_per_channel():
+    """The [128, 256, 56, 56] activation tensor with one shared exponent per channel, as bench.py times it."""
+    a = W.relu_activations()
+    n, c, hw = a.shape[0], a.shape[1], a.shape[2] * a.shape[3]
+    want = R.block_quantize(a, n, c, hw, 8, STOCHASTIC, 0, 1234, 0).reshape(-1)
+    got = host(Q.block_quantize(dev(a.reshape(-1)), n, c, hw, 8, STOCHASTIC, 0, 1234, 0))
+    assert_bit_equal(got, want, "block8 per channel, stochastic, 102,760,448 elements")
+
+
 @pytest.mark.parametrize("n", [W.N_PARAMS, W.N_PARAMS_RAGGED])
 def test_full_workload_5_sgd(n):
     w, g, m = W.sgd_state(n)
