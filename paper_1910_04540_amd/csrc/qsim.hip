@@ -296,12 +296,14 @@ static void launch_block_cached(const uint32_t* in, uint32_t* out, const BlockGe
     // Teams live inside a wavefront and share nothing beyond it.  One wavefront per workgroup streams
     // best when every lane of every team has work (block lengths 4, 8, ..., 1024: 80 % -> 84 % of
     // peak); with idle lanes the 256-thread workgroup measured faster (rows of 100 or 1000 elements).
-    const uint64_t groups = (g.inner + 3) / 4;
-    if (!WHOLE && (groups & (groups - 1)) == 0) {
-        const uint64_t per_wg = (uint64_t)(kStreamThreads >> team_log2);
-        hipLaunchKernelGGL((block_cached_kernel<MODE, GPT, WHOLE, kStreamThreads>), folded((g.nblocks + per_wg - 1) / per_wg),
-                           dim3(kStreamThreads), 0, stream, in, out, g, team_log2, wl, symmetric, key);
-        return;
+    if constexpr (!WHOLE) {
+        const uint64_t groups = (g.inner + 3) / 4;
+        if ((groups & (groups - 1)) == 0) {
+            const uint64_t per_wg = (uint64_t)(kStreamThreads >> team_log2);
+            hipLaunchKernelGGL((block_cached_kernel<MODE, GPT, false, kStreamThreads>), folded((g.nblocks + per_wg - 1) / per_wg),
+                               dim3(kStreamThreads), 0, stream, in, out, g, team_log2, wl, symmetric, key);
+            return;
+        }
     }
     const uint64_t teams_per_wg = WHOLE ? 1 : (uint64_t)(kThreads >> team_log2);
     const uint64_t blocks = (g.nblocks + teams_per_wg - 1) / teams_per_wg;
@@ -369,11 +371,11 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         // blocks on grid.y (folded when there are more than 65535), slices on grid.x
         if (try_resident_any<MODE>(pin, pout, g, wl, symmetric, key, partial, stream)) return launch_status();
         if (g.inner <= kWideCachedMaxInner) {
-            // too many blocks to hold at once, but each fits the registers of a 1024-thread workgroup
-            const uint64_t per_lane = ((g.inner + 3) / 4 + kWideThreads - 1) / kWideThreads;
-            if (per_lane <= 8)
-                hipLaunchKernelGGL((block_cached_kernel<MODE, 8, true, kWideThreads>), folded(g.nblocks), dim3(kWideThreads), 0,
-                                   stream, pin, pout, g, 10, wl, symmetric, key);
+            // too many blocks to hold at once, but each fits the registers of one large workgroup, 16
+            // groups per lane: two workgroups of 512 threads per CU, or one of 1024
+            if (g.inner <= kWideCachedMaxInner / 2)
+                hipLaunchKernelGGL((block_cached_kernel<MODE, 16, true, kWideThreads / 2>), folded(g.nblocks),
+                                   dim3(kWideThreads / 2), 0, stream, pin, pout, g, 9, wl, symmetric, key);
             else
                 hipLaunchKernelGGL((block_cached_kernel<MODE, 16, true, kWideThreads>), folded(g.nblocks), dim3(kWideThreads), 0,
                                    stream, pin, pout, g, 10, wl, symmetric, key);

@@ -179,39 +179,57 @@ struct BlockGeom {
 // Contiguous blocks (outer == 1, inner % 4 == 0, aligned arrays) held in registers: a team of
 // `team` lanes (a power of two, 1..64) or the whole workgroup of THREADS threads owns one block and
 // every lane keeps GPT groups of it, so the block is read from memory exactly once.
-// Requires ceil(inner / 4) <= team * GPT (THREADS * GPT for the whole workgroup).  THREADS = 1024
-// with 16 groups per thread holds a block of 65,536 elements: half of a compute unit's registers.
+// Requires ceil(inner / 4) <= team * GPT (THREADS * GPT for the whole workgroup).  With 16 groups
+// per thread (128 registers per lane) 512 threads hold a block of 32,768 elements and 1024 threads
+// one of 65,536: a quarter and a half of a compute unit's registers.
 template <int MODE, int GPT, bool WHOLE_WORKGROUP, int THREADS = kThreads>
 __global__ __launch_bounds__(THREADS) void block_cached_kernel(const uint32_t* in, uint32_t* out, BlockGeom g,
                                                                int team_log2, int wl, int symmetric, RngKey key)
 {
     __shared__ uint32_t lds[THREADS / 64];
     const int team = 1 << team_log2;
-    const int teams_per_wg = WHOLE_WORKGROUP ? 1 : (THREADS >> team_log2);
-    const int lane = WHOLE_WORKGROUP ? (int)threadIdx.x : ((int)threadIdx.x & (team - 1));
-    const uint64_t b = linear_block() * teams_per_wg + (WHOLE_WORKGROUP ? 0 : ((int)threadIdx.x >> team_log2));
+    const uint32_t teams_per_wg = WHOLE_WORKGROUP ? 1u : (uint32_t)(THREADS >> team_log2);
+    // Everything a lane needs is a 32-bit offset from the workgroup's first element, which is
+    // wave-uniform: the 64-bit arithmetic stays in scalar registers.
+    const uint64_t b0 = linear_block() * teams_per_wg;              // first block of the workgroup
+    if (b0 >= g.nblocks) return;                                    // the whole workgroup leaves together
+    const uint64_t e0 = b0 * g.inner;                               // its first element (a multiple of four)
+    const uint32_t* win = in + e0;
+    uint32_t* wout = out + e0;
+    const uint64_t left = g.n - e0;
+    const uint32_t avail = left < 0x40000000ull ? (uint32_t)left : 0x40000000u;     // elements up to the array's end
+    const uint32_t inner = (uint32_t)g.inner;                       // at most 65,536 here
+    const uint32_t lane = WHOLE_WORKGROUP ? threadIdx.x : (threadIdx.x & (uint32_t)(team - 1));
+    const uint32_t first = WHOLE_WORKGROUP ? 0u : (threadIdx.x >> team_log2) * inner;   // the team's block, relative
     // a team past the last block keeps all its lanes running with nothing to load or store, so the
-    // cross-lane operations below always see a full wavefront
-    const uint64_t start = b < g.nblocks ? b * g.inner : g.n;
-    const uint64_t len = (g.n - start < g.inner) ? g.n - start : g.inner;
-    const uint64_t end = start + len;
-    const uint64_t j0 = start / 4;
-    const int groups = (int)((len + 3) / 4);
-    const int stride = WHOLE_WORKGROUP ? THREADS : team;
+    // cross-lane operations below always see a full wavefront; the last block may be short
+    const uint32_t len = first >= avail ? 0u : (avail - first < inner ? avail - first : inner);
+    const uint32_t end = first + len;
+    const uint32_t g0 = first / 4u;
+    const uint32_t groups = (len + 3u) / 4u;
+    const uint32_t stride = WHOLE_WORKGROUP ? (uint32_t)THREADS : (uint32_t)team;
+    const uint64_t j0 = e0 / 4;                                     // uniform: the workgroup's first group
 
     uint4 v[GPT];
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        const int t = lane + k * stride;
+        const uint32_t t = lane + (uint32_t)k * stride;
         v[k] = make_uint4(0u, 0u, 0u, 0u);
-        if (t < groups) v[k] = load_group<true>(in, j0 + t, end);
+        if (t < groups) v[k] = load_group<true>(win, (uint64_t)(g0 + t), (uint64_t)end);
     }
     // stochastic rounding: the random words of the first groups are drawn while the loads are in
     // flight (they do not depend on the data), the rest after the reduction
-    constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 4 ? GPT : 4) : 0;
+    // (the large workgroups have 128 registers per lane, half of them data: fewer words drawn early, not pinned)
+    constexpr int kEarly = THREADS > kThreads ? 4 : 8;
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < kEarly ? GPT : kEarly) : 0;
     Words4 early[PRE > 0 ? PRE : 1];
 #pragma unroll
-    for (int k = 0; k < PRE; ++k) early[k] = random_words(j0 + (uint64_t)(lane + k * stride), key, 0u);
+    for (int k = 0; k < PRE; ++k) {
+        early[k] = random_words(j0 + (g0 + lane + (uint32_t)k * stride), key, 0u);
+        // keep the compiler from sinking this below the reduction, where it would no longer overlap the loads
+        if (THREADS <= kThreads)
+            asm volatile("" : "+v"(early[k].w[0]), "+v"(early[k].w[1]), "+v"(early[k].w[2]), "+v"(early[k].w[3]));
+    }
     uint32_t m = 0;
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
@@ -222,12 +240,12 @@ __global__ __launch_bounds__(THREADS) void block_cached_kernel(const uint32_t* i
     const GridPlan p = block_plan(m, wl, symmetric);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        const int t = lane + k * stride;
+        const uint32_t t = lane + (uint32_t)k * stride;
         if (t < groups) {
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) r = early[k];
-            else if (MODE == QSIM_STOCHASTIC) r = random_words(j0 + t, key, 0u);
-            store_group<true>(out, j0 + t, end, quantize_group_to_grid<MODE>(v[k], p, r));
+            else if (MODE == QSIM_STOCHASTIC) r = random_words(j0 + (g0 + t), key, 0u);
+            store_group<true>(wout, (uint64_t)(g0 + t), (uint64_t)end, quantize_group_to_grid<MODE>(v[k], p, r));
         }
     }
 }
