@@ -291,6 +291,14 @@ __global__ __launch_bounds__(kThreads) void block_ragged_kernel(const uint32_t* 
         v[k] = make_uint4(0u, 0u, 0u, 0u);
         if (t < ngroups) v[k] = load_group<VEC>(in, j0 + t, g.n);
     }
+    // stochastic rounding: the random words of the first groups are drawn while the loads are in flight
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 4 ? GPT : 4) : 0;
+    Words4 early[PRE > 0 ? PRE : 1];
+#pragma unroll
+    for (int k = 0; k < PRE; ++k) {
+        early[k] = random_words(j0 + (threadIdx.x + (uint32_t)k * kThreads), key, 0u);
+        asm volatile("" : "+v"(early[k].w[0]), "+v"(early[k].w[1]), "+v"(early[k].w[2]), "+v"(early[k].w[3]));
+    }
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
@@ -327,7 +335,8 @@ __global__ __launch_bounds__(kThreads) void block_ragged_kernel(const uint32_t* 
         if (t < ngroups) {
             const uint64_t j = j0 + t;
             Words4 r = {{0u, 0u, 0u, 0u}};
-            if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+            if (k < PRE) r = early[k];
+            else if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
             const uint32_t bits[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
             const uint32_t row[4] = {rows01[k] & 0xffffu, rows01[k] >> 16, rows23[k] & 0xffffu, rows23[k] >> 16};
             uint32_t o[4];
