@@ -111,13 +111,14 @@ int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer,
 size_t qsim_block_workspace_bytes(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner);
 
 /*
- * Tuning and test knob of qsim_block_quantize.  A contiguous block that is too long for one
- * workgroup but fits in the register files of the whole chip is quantized in a single pass by
- * workgroups that wait for each other once.  That wait is bounded: after `microseconds` (default
- * 2000) a workgroup stops waiting and derives the missing maxima from memory itself, so the result
- * is the same, only slower; this happens when the device is shared with other work and not every
- * workgroup got a slot.  0 makes every workgroup take that path at once.  Process-wide; affects
- * calls made after it returns.
+ * Tuning and test knob of qsim_block_quantize.  A block that is too long for one workgroup but
+ * fits in the register files of the chip (a whole tensor of up to 16 Mi elements; in larger
+ * tensors every block of up to 1 Mi contiguous or 4 Mi strided elements) is quantized in a single
+ * pass by workgroups that wait for each other once.  That wait is bounded: after `microseconds`
+ * (default 2000) a workgroup stops waiting and derives the missing maxima from memory itself, so
+ * the result is the same, only slower; this happens when the device is shared with other work and
+ * not every workgroup got a slot.  0 makes every workgroup take that path at once.  Process-wide;
+ * affects calls made after it returns.
  */
 void qsim_set_barrier_wait_us(uint32_t microseconds);
 
