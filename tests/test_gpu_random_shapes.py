@@ -94,3 +94,45 @@ def test_random_elementwise_and_sgd(seed):
         assert_bit_equal(Q.fixed_quantize(d, wl, fl, rounding, fx_flags, seed64, stream).cpu().numpy(),
                          R.fixed_quantize(x, wl, fl, rounding, fx_flags, seed64, stream),
                          f"seed {seed} case {case}: fixed({wl},{fl}) n={n} mode={rounding} flags={fx_flags} offset={offset}")
+
+
+def _random_format(g):
+    kind = int(g.integers(0, 4))
+    rounding = int(g.integers(0, 4))
+    if kind == 0:
+        return (0, 0, 0, 0, 0)
+    if kind == 1:
+        return (1, int(g.integers(2, 9)), int(g.integers(1, 24)), rounding, int(g.integers(0, 4)))
+    if kind == 2:
+        wl = int(g.integers(1, 25))
+        return (2, wl, int(g.integers(wl - 20, 40)), rounding, int(g.choice([0, 1, 5, 4])))
+    return (3, int(g.integers(2, 25)), int(2 ** g.integers(2, 11)), rounding, int(g.choice([0, 4])))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_sgd_steps(seed):
+    g = np.random.Generator(np.random.PCG64(9000 + seed))
+    for case in range(15):
+        n = _log_uniform(g, 1, 1_000_000)
+        offset = int(g.choice([0, 0, 1, 3]))
+        fmts = [_random_format(g) for _ in range(3)]
+        opts = (float(g.choice([0.0, 5e-4])), float(g.choice([0.0, 0.25])), int(g.integers(0, 2)))
+        mode = str(g.choice(["copy", "in_place", "none"]))
+        lr, mu = float(g.choice([0.1, 0.01])), float(g.choice([0.0, 0.9]))
+        w = (g.standard_normal(n, dtype=np.float32) * np.float32(0.05)).astype(np.float32)
+        gr = (g.standard_normal(n, dtype=np.float32) * np.exp2(g.integers(-20, 2, size=n))).astype(np.float32)
+        mo = (g.standard_normal(n, dtype=np.float32) * np.float32(1e-3)).astype(np.float32)
+        seed64, stream = int(g.integers(0, 2 ** 62)), int(g.integers(0, 2 ** 31))
+        wr, wqr, mr = R.quant_sgd_step(w, gr, mo, lr, mu, *[R.Format(*f) for f in fmts], seed64, stream,
+                                       want_wq=mode == "copy", in_place_weights=mode == "in_place", options=R.SgdOptions(*opts))
+        what = f"seed {seed} case {case}: n={n} formats={fmts} options={opts} weights={mode} offset={offset}"
+        put = lambda a: torch.from_numpy(np.concatenate([np.zeros(offset, np.float32), a])).cuda()[offset:]
+        dw, dg, dm = put(w), put(gr), put(mo)
+        dq = torch.empty(n, device="cuda") if mode == "copy" else (dw if mode == "in_place" else None)
+        Q.quant_sgd_step(dw, dg, dm, lr, mu, *[Q.Format(*f) for f in fmts], seed64, stream, w_q=dq, options=Q.SgdOptions(*opts))
+        torch.cuda.synchronize()
+        ok = np.isfinite(wr.astype(np.float64)) & np.isfinite(mr.astype(np.float64))      # NaN payloads made by arithmetic are unspecified
+        assert_bit_equal(dm.cpu().numpy()[ok], mr[ok], what + ": momentum")
+        assert_bit_equal(dw.cpu().numpy()[ok], wr[ok], what + ": weights")
+        if mode == "copy":
+            assert_bit_equal(dq.cpu().numpy()[ok], wqr[ok], what + ": quantized weights")
