@@ -680,3 +680,28 @@ def test_full_workload_5_sgd_over_a_resnet50_parameter_list():
         assert_bit_equal(gw[lo:lo + n], wr, f"weights of tensor {t} (n={n})")
         assert_bit_equal(gq[lo:lo + n], wqr, f"quantized weights of tensor {t} (n={n})")
         lo += n
+
+
+def test_block_single_pass_forms_on_two_streams_at_once():
+    """Two calls whose workgroups wait for their block-mates run side by side on two streams, each
+    with its own scratch: both must finish with exact results."""
+    rows, cols = 300, 70000
+    shape = (32, 64, 3136)
+    x1 = W.row_scaled_matrix(rows, cols, seed=31).reshape(-1)
+    x2 = W.lognormal_gradients(shape, seed=32).reshape(-1)
+    want1 = R.block_quantize(x1, 1, rows, cols, 8, STOCHASTIC, 0, 9, 1)
+    want2 = R.block_quantize(x2, *shape, 8, STOCHASTIC, 0, 9, 2)
+    d1, d2 = dev(x1), dev(x2)
+    o1, o2 = torch.empty_like(d1), torch.empty_like(d2)
+    ws1 = torch.empty(Q.block_workspace_bytes(d1.numel(), 1, rows, cols), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(Q.block_workspace_bytes(d2.numel(), *shape), dtype=torch.uint8, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(5):
+        with torch.cuda.stream(s1):
+            Q.block_quantize(d1, 1, rows, cols, 8, STOCHASTIC, 0, 9, 1, out=o1, workspace=ws1)
+        with torch.cuda.stream(s2):
+            Q.block_quantize(d2, *shape, 8, STOCHASTIC, 0, 9, 2, out=o2, workspace=ws2)
+    torch.cuda.synchronize()
+    assert_bit_equal(host(o1), want1, "rows, stream 1")
+    assert_bit_equal(host(o2), want2, "channels, stream 2")
