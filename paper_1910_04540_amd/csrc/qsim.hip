@@ -83,6 +83,8 @@ struct BlockSchedule {
     bool one_launch;       // contiguous blocks small enough for one team or workgroup each
     SliceGeom sg;          // otherwise: two launches over slices
     bool cluster;          // many contiguous blocks of up to 64 register-resident slices each: single pass per block
+    bool strided_packed;   // outer > 1, whole-group segments, blocks of at most 2048 elements: several per workgroup
+    StridedPackedGeom spg;
     bool strided_cluster;  // outer > 1, aligned segments of >= 64 elements, blocks of up to 256 slices: the same
     StridedClusterGeom scg;
     bool flat;             // outer > 1 and short rows: the flat form (any alignment)
@@ -135,6 +137,16 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         s.cluster = true;
         const size_t bytes = (size_t)(kSyncSlots0 + nblocks * cluster_slices) * sizeof(uint32_t);
         if (s.workspace < bytes) s.workspace = bytes;
+    }
+    if (outer > 1 && inner % 4 == 0 && s.sg.block_len <= 2048) {
+        s.strided_packed = true;
+        s.spg.nblocks = nblocks;
+        s.spg.outer_inner = (uint32_t)s.sg.block_len;
+        s.spg.groups_per_block = s.spg.outer_inner / 4;
+        s.spg.magic_groups = s.spg.groups_per_block > 1 ? (uint32_t)((1ull << 32) / s.spg.groups_per_block) + 1u : 0u;
+        s.spg.inner = (uint32_t)inner;
+        s.spg.magic_inner = (uint32_t)((1ull << 32) / inner) + 1u;
+        s.spg.blocks_per_wg = 1024u / s.spg.groups_per_block;
     }
     if (outer > 1 && inner % 4 == 0 && inner >= 64 && inner <= (1ull << 22) &&
         s.sg.block_len <= (uint64_t)kStridedMaxSlices * kStridedSliceLen) {
@@ -386,6 +398,10 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
                            partial, s.sg, wl, symmetric, key);
+    } else if (vec && s.strided_packed) {
+        const uint64_t wgs = (g.nblocks + s.spg.blocks_per_wg - 1) / s.spg.blocks_per_wg;
+        hipLaunchKernelGGL((block_strided_packed_kernel<MODE>), folded(wgs), dim3(kThreads), 0, stream, pin, pout, s.spg, wl,
+                           symmetric, key);
     } else if (vec && s.strided_cluster && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // single pass, block by block (see the kernel): the workgroups of a block must fit together
         StridedClusterGeom cg = s.scg;

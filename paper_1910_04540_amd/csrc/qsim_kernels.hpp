@@ -1195,6 +1195,81 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     }
 }
 
+// Blocks along an inner dimension that are SHORT (outer * inner <= 2048 elements, inner % 4 == 0,
+// aligned arrays): a [2, 300000, 64] tensor with one block per index of the middle dimension.  One
+// workgroup takes as many consecutive blocks as fit 4096 elements and holds them in registers, four
+// groups per thread; block maxima meet in LDS; single pass, nothing to wait for.  For a fixed outer
+// index the segments of consecutive blocks are neighbours in memory, so the accesses of a workgroup
+// fall into `outer` contiguous runs.
+struct StridedPackedGeom {
+    uint64_t nblocks;
+    uint32_t outer_inner;      // elements per block, a multiple of 4, at most 2048
+    uint32_t groups_per_block; // outer_inner / 4
+    uint32_t magic_groups;     // floor(2^32 / groups_per_block) + 1 (unused when groups_per_block == 1)
+    uint32_t inner;
+    uint32_t magic_inner;      // floor(2^32 / inner) + 1
+    uint32_t blocks_per_wg;    // floor(1024 / groups_per_block), at least 2
+};
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void block_strided_packed_kernel(const uint32_t* in, uint32_t* out, StridedPackedGeom pg,
+                                                                        int wl, int symmetric, RngKey key)
+{
+    constexpr int GPT = 4;
+    __shared__ uint32_t blockmax[kThreads * GPT];                 // at most 1024 blocks of one group each
+    const uint64_t b0 = linear_block() * pg.blocks_per_wg;
+    if (b0 >= pg.nblocks) return;                                 // the whole workgroup leaves together
+    const uint32_t mine = pg.nblocks - b0 < pg.blocks_per_wg ? (uint32_t)(pg.nblocks - b0) : pg.blocks_per_wg;
+    const uint32_t ngroups = mine * pg.groups_per_block;          // at most 1024
+    for (uint32_t t = threadIdx.x; t < mine; t += kThreads) blockmax[t] = 0u;
+    __syncthreads();
+
+    uint4 v[GPT];
+    uint32_t owner[GPT];
+    uint64_t where[GPT];
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);
+        owner[k] = 0u;
+        where[k] = 0u;
+        if (t < ngroups) {
+            const uint32_t bl = pg.groups_per_block == 1u ? t : __umulhi(t, pg.magic_groups);     // exact: t < 2^16
+            const uint32_t tt = (t - bl * pg.groups_per_block) * 4u;                              // element within the block
+            const uint32_t o = __umulhi(tt, pg.magic_inner);                                       // exact: tt < 2^16
+            const uint32_t i = tt - o * pg.inner;
+            owner[k] = bl;
+            where[k] = (((uint64_t)o * pg.nblocks + (b0 + bl)) * pg.inner + i) >> 2;
+            v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in) + where[k]));
+        }
+    }
+    // stochastic rounding: the random words are drawn while the loads are in flight
+    Words4 words[MODE == QSIM_STOCHASTIC ? GPT : 1];
+    if (MODE == QSIM_STOCHASTIC) {
+#pragma unroll
+        for (int k = 0; k < GPT; ++k) {
+            words[k] = random_words(where[k], key, 0u);
+            asm volatile("" : "+v"(words[k].w[0]), "+v"(words[k].w[1]), "+v"(words[k].w[2]), "+v"(words[k].w[3]));
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        if (t < ngroups) atomicMax(&blockmax[owner[k]], max4_mag(v[k]));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        if (t < ngroups) {
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (MODE == QSIM_STOCHASTIC) r = words[k];
+            const GridPlan p = block_plan(blockmax[owner[k]], wl, symmetric);
+            __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + where[k]);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Fused quantized SGD step.  A workgroup walks tiles of 1024 elements (one group per thread), so a
 // chunk of L <= 1024 elements never leaves the workgroup: its maximum is a reduction over L/4

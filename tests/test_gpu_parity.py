@@ -396,6 +396,22 @@ def test_block_per_channel_single_pass(shape, rounding):
     assert_bit_equal(host(d), want, f"{shape} in place")
 
 
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("shape", [(2, 300000, 64), (4, 1000, 4), (2, 5, 1024), (8, 50000, 128), (3, 100001, 100), (2, 1, 4),
+                                   (512, 70000, 4), (2, 1000003, 16), (32, 33, 64)])
+def test_block_short_blocks_along_an_inner_dimension(shape, rounding):
+    """Blocks of at most 2048 elements made of whole-group segments: several blocks per workgroup, single pass."""
+    outer, nblocks, inner = shape
+    g = np.random.Generator(np.random.PCG64(sum(shape)))
+    scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
+    x = (g.standard_normal(shape, dtype=np.float32) * scale[None, :, None]).astype(np.float32)
+    want = R.block_quantize(x, outer, nblocks, inner, 8, rounding, 0, 6, 1).reshape(-1)
+    d = dev(x.reshape(-1))
+    assert_bit_equal(host(Q.block_quantize(d, outer, nblocks, inner, 8, rounding, 0, 6, 1)), want, f"{shape}")
+    Q.block_quantize(d, outer, nblocks, inner, 8, rounding, 0, 6, 1, out=d)
+    assert_bit_equal(host(d), want, f"{shape} in place")
+
+
 def test_block_per_channel_single_pass_when_the_wait_runs_out():
     Q.set_barrier_wait_us(0)
     try:
