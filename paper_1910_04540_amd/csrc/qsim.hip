@@ -89,9 +89,8 @@ struct BlockSchedule {
     StridedClusterGeom scg;
     bool flat;             // outer > 1 and short rows: the flat form (any alignment)
     FlatGeom fg;
-    bool column;           // outer > 1 and rows made of whole groups: the column form (aligned arrays)
+    bool column;           // outer > 1 and short blocks: the column form (any row length, any alignment)
     ColumnGeom cg;
-    size_t column_bytes;   // scratch of the column form: column maxima, then block maxima
     size_t workspace;      // bytes of scratch needed (the largest of the forms the shape may take)
 };
 
@@ -106,15 +105,49 @@ constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
 constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
 constexpr uint64_t kColumnThreads = 1ull << 19;  // threads the column form aims for
+constexpr uint64_t kColumnShortInner = 64;       // below: always; up to kColumnMaxInner: when there are enough blocks
+constexpr uint64_t kColumnMaxInner = 4096;       // to keep the one-wavefront-per-block fold parallel
+constexpr uint64_t kColumnManyBlocks = 1024;
 constexpr uint32_t kColumnParts = 8;             // slices left after the first, coalesced fold of its column maxima
 constexpr uint64_t kFlatWorkgroups = 1024;       // workgroups of the flat form (four per CU)
 constexpr uint32_t kFlatParts = 32;              // parts of its first fold
 constexpr uint64_t kMultiTiles = 1ull << 30;     // tiles of one multi-tensor launch (running counts are 32-bit)
 
+// Row slices of the column form: a thread owns a run of four columns.
+static ColumnGeom column_geometry(uint64_t outer, uint64_t nblocks, uint64_t inner)
+{
+    ColumnGeom cg;
+    cg.outer = outer;
+    cg.row = (uint32_t)(nblocks * inner);
+    cg.row_groups = (uint32_t)(((uint64_t)cg.row + 3) / 4);
+    const uint64_t columns = cg.row_groups;
+    cg.inner = (uint32_t)inner;
+    cg.nblocks = (uint32_t)nblocks;
+    // enough threads to fill the chip, at least 16 rows per thread when there are that many
+    uint64_t slices = (kColumnThreads + columns - 1) / columns;
+    const uint64_t most = (outer + 15) / 16;
+    if (slices > most) slices = most;
+    if (slices > 65535) slices = 65535;
+    cg.rows_per_slice = (uint32_t)((outer + slices - 1) / slices);
+    cg.slices = (uint32_t)((outer + cg.rows_per_slice - 1) / cg.rows_per_slice);
+    return cg;
+}
+
+// Scratch of a column form: column maxima of every slice, the same folded to kColumnParts slices, block maxima.
+static size_t column_bytes(const ColumnGeom& cg)
+{
+    const size_t fewer = cg.slices > 2 * kColumnParts ? kColumnParts : 0;      // only many slices are folded twice
+    return ((size_t)cg.slices + fewer) * (size_t)cg.row_groups * 4 * sizeof(uint32_t) + (size_t)cg.nblocks * sizeof(uint32_t);
+}
+
 static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner)
 {
     BlockSchedule s;
     memset(&s, 0, sizeof(s));
+    if (nblocks == 1 && outer > 1) {      // one block is one block, however the view splits it
+        inner = n;
+        outer = 1;
+    }
     s.sg.g = BlockGeom{n, outer, nblocks, inner};
     s.sg.block_len = outer * inner;
     s.one_launch = outer == 1 && inner <= kCachedMaxInner;
@@ -138,7 +171,8 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         const size_t bytes = (size_t)(kSyncSlots0 + nblocks * cluster_slices) * sizeof(uint32_t);
         if (s.workspace < bytes) s.workspace = bytes;
     }
-    if (outer > 1 && inner % 4 == 0 && s.sg.block_len <= 2048) {
+    // (the runs a workgroup reads are 16 KiB / outer long: only for few outer indices)
+    if (outer > 1 && outer <= 16 && inner % 4 == 0 && s.sg.block_len <= 2048) {
         s.strided_packed = true;
         s.spg.nblocks = nblocks;
         s.spg.outer_inner = (uint32_t)s.sg.block_len;
@@ -184,28 +218,19 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         const size_t flat_bytes = (size_t)(kFlatWorkgroups + kFlatParts + 1) * nblocks * sizeof(uint32_t);
         if (s.workspace < flat_bytes) s.workspace = flat_bytes;
     }
-    // the column form: rows of whole groups, short enough for 32-bit column arithmetic.  It is for
-    // short blocks (a thread walking down a column jumps a whole row per step, which only pays when
-    // the alternative cannot use whole groups or would do a division per group of a short segment);
-    // long segments stream better through the slice kernels.
+    // the column form: short segments (a thread walking down a column jumps a whole row per step, which
+    // only pays when the alternative would do a division per run of a short segment), and segments of
+    // up to 4096 elements when there are many blocks (the alternative gives every block a workgroup
+    // of its own, however small the block; the fold here is one wavefront per block over
+    // slices * inner values, so it needs many blocks to be parallel).  Rows short enough for 32-bit
+    // column arithmetic.
     const unsigned __int128 row = (unsigned __int128)nblocks * inner;
-    if (outer > 1 && row % 4 == 0 && row <= (1ull << 31) && outer <= (1ull << 32) && (inner % 4 != 0 || inner < 64)) {
+    if (outer > 1 && row <= (1ull << 31) && outer <= (1ull << 32) &&
+        (inner < kColumnShortInner || (inner <= kColumnMaxInner && nblocks >= kColumnManyBlocks))) {
         s.column = true;
-        ColumnGeom& cg = s.cg;
-        cg.outer = outer;
-        cg.row_groups = (uint32_t)(row / 4);
-        cg.inner = (uint32_t)inner;
-        cg.nblocks = (uint32_t)nblocks;
-        // enough threads to fill the chip, at least 16 rows per thread when there are that many
-        uint64_t slices = (kColumnThreads + cg.row_groups - 1) / cg.row_groups;
-        const uint64_t most = (outer + 15) / 16;
-        if (slices > most) slices = most;
-        if (slices > 65535) slices = 65535;
-        cg.rows_per_slice = (uint32_t)((outer + slices - 1) / slices);
-        cg.slices = (uint32_t)((outer + cg.rows_per_slice - 1) / cg.rows_per_slice);
-        // column maxima of every slice, the same folded to kColumnParts slices, block maxima
-        s.column_bytes = ((size_t)cg.slices + kColumnParts) * (size_t)row * sizeof(uint32_t) + (size_t)nblocks * sizeof(uint32_t);
-        if (s.workspace < s.column_bytes) s.workspace = s.column_bytes;
+        s.cg = column_geometry(outer, nblocks, inner);
+        const size_t bytes = column_bytes(s.cg);
+        if (s.workspace < bytes) s.workspace = bytes;
     }
     return s;
 }
@@ -347,7 +372,8 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
     const uint32_t* pin = u32(in);
     uint32_t* pout = u32(out);
     const BlockGeom& g = s.sg.g;
-    const bool vec = aligned16(in) && aligned16(out) && (g.inner % 4 == 0);
+    // whole groups per block: every block starts on a group boundary (a single block always does)
+    const bool vec = aligned16(in) && aligned16(out) && (g.inner % 4 == 0 || g.nblocks == 1);
     if (s.one_launch) {
         const uint64_t groups = (g.inner + 3) / 4;
         if (vec && groups <= 256) {
@@ -410,8 +436,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                            partial, cg.total_wgs);
         hipLaunchKernelGGL((block_cluster_strided_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
                            partial, cg, wl, symmetric, key);
-    } else if (s.flat && !(vec && g.inner >= 64) &&
-               (!(s.column && aligned16(in) && aligned16(out)) || g.nblocks < 64 || s.fg.row < 2048)) {
+    } else if (s.flat && !(vec && g.inner >= 64) && (!s.column || g.nblocks < 64 || s.fg.row < 2048)) {
         // short rows, unless long aligned segments stream well through the slice kernels: always when
         // the column form cannot run; otherwise where that form is weak (few blocks make its fold
         // serial, short rows give it few threads per row)
@@ -431,27 +456,39 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         }
         hipLaunchKernelGGL((block_flat_apply_kernel<MODE>), dim3(fg.wgs), dim3(kThreads), 0, stream, pin, pout, blockmax, fg, wl,
                            symmetric, key);
-    } else if (s.column && aligned16(in) && aligned16(out)) {
+    } else if (s.column) {
+        // dwordx4 accesses at group boundaries when rows are whole groups and the arrays aligned, at any dword otherwise
         const ColumnGeom& cg = s.cg;
-        uint4* colmax = reinterpret_cast<uint4*>(workspace);
+        const bool wide = cg.row % 4 == 0 && aligned16(in) && aligned16(out);
         const size_t row_words = (size_t)cg.row_groups * 4;
         uint32_t* fewer = partial + (size_t)cg.slices * row_words;
-        uint32_t* blockmax = fewer + (size_t)kColumnParts * row_words;
+        uint32_t* blockmax = fewer + (cg.slices > 2 * kColumnParts ? (size_t)kColumnParts * row_words : 0);
         const dim3 cgrid((cg.row_groups + kThreads - 1) / kThreads, cg.slices);
-        hipLaunchKernelGGL(block_column_max_kernel, cgrid, dim3(kThreads), 0, stream, pin, colmax, cg);
-        const dim3 fold_grid = folded((cg.nblocks + kThreads / 64 - 1) / (kThreads / 64));
+        uint4* colmax = reinterpret_cast<uint4*>(workspace);
+        if (wide) hipLaunchKernelGGL(block_column_max_kernel<true>, cgrid, dim3(kThreads), 0, stream, pin, colmax, cg);
+        else hipLaunchKernelGGL(block_column_max_kernel<false>, cgrid, dim3(kThreads), 0, stream, pin, colmax, cg);
+        // fold: over slices first when there are many (neighbouring threads on neighbouring columns),
+        // then one wavefront per block, or one thread per block when a block has few values left
+        ColumnGeom rest = cg;
+        const uint32_t* folded_from = partial;
         if (cg.slices > 2 * kColumnParts) {
-            // many slices: first a fold over slices with neighbouring threads on neighbouring columns
-            ColumnGeom few = cg;
-            few.slices = kColumnParts;
+            rest.slices = kColumnParts;
+            folded_from = fewer;
             hipLaunchKernelGGL(block_fold_rows_kernel, dim3((unsigned)((row_words + kThreads - 1) / kThreads), kColumnParts),
                                dim3(kThreads), 0, stream, partial, fewer, (uint32_t)row_words, cg.slices, kColumnParts);
-            hipLaunchKernelGGL(block_column_fold_kernel, fold_grid, dim3(kThreads), 0, stream, fewer, blockmax, few);
-        } else {
-            hipLaunchKernelGGL(block_column_fold_kernel, fold_grid, dim3(kThreads), 0, stream, partial, blockmax, cg);
         }
-        hipLaunchKernelGGL((block_column_apply_kernel<MODE>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax, cg, wl,
-                           symmetric, key);
+        if ((uint64_t)rest.slices * rest.inner <= 64)
+            hipLaunchKernelGGL(block_column_fold_small_kernel, folded((cg.nblocks + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                               stream, folded_from, blockmax, rest);
+        else
+            hipLaunchKernelGGL(block_column_fold_kernel, folded((cg.nblocks + kThreads / 64 - 1) / (kThreads / 64)),
+                               dim3(kThreads), 0, stream, folded_from, blockmax, rest);
+        if (wide)
+            hipLaunchKernelGGL((block_column_apply_kernel<MODE, true>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax, cg,
+                               wl, symmetric, key);
+        else
+            hipLaunchKernelGGL((block_column_apply_kernel<MODE, false>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax, cg,
+                               wl, symmetric, key);
     } else if (vec) {
         hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg.slices,
@@ -610,7 +647,7 @@ int qsim_block_max(const float* in, uint64_t n, uint64_t outer, uint64_t nblocks
     }
     hipStream_t stream = as_stream(hip_stream);
     const dim3 grid = folded_xz(nblocks, sg.slices);
-    if (aligned16(in) && inner % 4 == 0)
+    if (aligned16(in) && sg.g.inner % 4 == 0)
         hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, u32(in), partial, sg);
     else
         hipLaunchKernelGGL((block_partial_max_kernel<false>), grid, dim3(kThreads), 0, stream, u32(in), partial, sg);

@@ -53,6 +53,22 @@ __device__ __forceinline__ Words4 random_words(uint64_t j, const RngKey& key, ui
     return philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), key.stream_id, role, key.seed_lo, key.seed_hi);
 }
 
+// Random words of the four elements i0 .. i0+3 for ANY i0: they straddle two counter values unless
+// i0 is a multiple of four, so a run that is not group-aligned pays for two Philox blocks.
+__device__ __forceinline__ Words4 random_words_at(uint64_t i0, const RngKey& key, uint32_t role)
+{
+    const uint32_t s = (uint32_t)i0 & 3u;
+    const Words4 a = random_words(i0 >> 2, key, role);
+    if (s == 0u) return a;
+    const Words4 b = random_words((i0 >> 2) + 1u, key, role);
+    Words4 r;
+    r.w[0] = s == 1u ? a.w[1] : (s == 2u ? a.w[2] : a.w[3]);
+    r.w[1] = s == 1u ? a.w[2] : (s == 2u ? a.w[3] : b.w[0]);
+    r.w[2] = s == 1u ? a.w[3] : (s == 2u ? b.w[0] : b.w[1]);
+    r.w[3] = s == 1u ? b.w[0] : (s == 2u ? b.w[1] : b.w[2]);
+    return r;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Rounding a non-negative scaled value y = |x| / 2^q (y < 2^24, exact in fp32) to an integer
 // (Sec. 3.1 "Rounding mode").  fract/trunc/convert are exact on such y; the stochastic threshold

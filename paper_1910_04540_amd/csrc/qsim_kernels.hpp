@@ -393,10 +393,18 @@ struct SliceGeom {
     uint32_t slices;       // workgroups per block
 };
 
+// Segment number of element t of a block: a 32-bit division whenever the operands allow it (a
+// 64-bit one is several times the instructions, and this sits in the inner loops of the general form).
+__device__ __forceinline__ uint64_t segment_of(const BlockGeom& g, uint64_t t)
+{
+    if ((t | g.inner) <= 0xffffffffull) return (uint32_t)t / (uint32_t)g.inner;
+    return t / g.inner;
+}
+
 __device__ __forceinline__ uint64_t flat_index(const BlockGeom& g, uint64_t b, uint64_t t)
 {
     if (g.outer == 1) return b * g.inner + t;
-    const uint64_t o = t / g.inner, i = t - o * g.inner;
+    const uint64_t o = segment_of(g, t), i = t - o * g.inner;
     return (o * g.nblocks + b) * g.inner + i;
 }
 
@@ -427,9 +435,21 @@ __global__ __launch_bounds__(kThreads) void block_partial_max_kernel(const uint3
             m = m > gm ? m : gm;
         }
     } else {
-        for (uint64_t t = t0 + threadIdx.x; t < t1; t += kThreads) {
-            const uint32_t a = in[flat_index(sg.g, b, t)] & 0x7fffffffu;
-            m = m > a ? m : a;
+        // any layout, any alignment: runs of four elements of the block's own numbering; a run that
+        // stays inside one segment is one (dword-aligned) dwordx4 access
+        for (uint64_t t = t0 + 4ull * threadIdx.x; t < t1; t += 4ull * kThreads) {
+            const uint64_t o = sg.g.outer == 1 ? 0 : segment_of(sg.g, t), i = t - o * sg.g.inner;
+            if (t + 4 <= t1 && (sg.g.outer == 1 || i + 4 <= sg.g.inner)) {
+                const uint64_t at = sg.g.outer == 1 ? b * sg.g.inner + t : (o * sg.g.nblocks + b) * sg.g.inner + i;
+                const u32x4 w = *reinterpret_cast<const u32x4_at_dword*>(in + at);       // cached: read again in pass 2
+                const uint32_t gm = max4_mag(to_uint4(w));
+                m = m > gm ? m : gm;
+            } else {
+                for (uint64_t e = t; e < t + 4 && e < t1; ++e) {
+                    const uint32_t a = in[flat_index(sg.g, b, e)] & 0x7fffffffu;
+                    m = m > a ? m : a;
+                }
+            }
         }
     }
     m = workgroup_max(m, lds);
@@ -478,11 +498,23 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
             store_group<true>(out, j, sg.g.n, quantize_group_to_grid<MODE>(v, p, r));
         }
     } else {
-        for (uint64_t t = t0 + threadIdx.x; t < t1; t += kThreads) {
-            const uint64_t i = flat_index(sg.g, b, t);
-            uint32_t r = 0;
-            if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
-            out[i] = quantize_to_grid<MODE>(in[i], p, r);
+        for (uint64_t t = t0 + 4ull * threadIdx.x; t < t1; t += 4ull * kThreads) {
+            const uint64_t o = sg.g.outer == 1 ? 0 : segment_of(sg.g, t), i = t - o * sg.g.inner;
+            if (t + 4 <= t1 && (sg.g.outer == 1 || i + 4 <= sg.g.inner)) {
+                const uint64_t at = sg.g.outer == 1 ? b * sg.g.inner + t : (o * sg.g.nblocks + b) * sg.g.inner + i;
+                const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4_at_dword*>(in + at));
+                Words4 r = {{0u, 0u, 0u, 0u}};
+                if (MODE == QSIM_STOCHASTIC) r = random_words_at(at, key, 0u);
+                __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(to_uint4(w), p, r)),
+                                            reinterpret_cast<u32x4_at_dword*>(out + at));
+            } else {
+                for (uint64_t e = t; e < t + 4 && e < t1; ++e) {
+                    const uint64_t at = flat_index(sg.g, b, e);
+                    uint32_t r = 0;
+                    if (MODE == QSIM_STOCHASTIC) r = random_words(at >> 2, key, 0u).w[at & 3];
+                    out[at] = quantize_to_grid<MODE>(in[at], p, r);
+                }
+            }
         }
     }
 }
@@ -497,27 +529,51 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
 //   pass 2   the same walk again: quantize with the plans of the four columns' blocks
 struct ColumnGeom {
     uint64_t outer;            // rows
-    uint32_t row_groups;       // groups per row = nblocks * inner / 4
+    uint32_t row;              // elements per row = nblocks * inner
+    uint32_t row_groups;       // runs of four columns per row = ceil(row / 4); colmax rows are 4 * row_groups wide
     uint32_t inner;
     uint32_t nblocks;
     uint32_t slices;           // row slices
     uint32_t rows_per_slice;
 };
 
+// A thread's run of four columns in row o starts at element o * row + 4 * c: a group boundary when
+// rows are whole groups and the array is aligned (ALIGNED), any dword otherwise.  The last run of a
+// row that is not a multiple of four is short and goes element by element.
+template <bool ALIGNED>
+__device__ __forceinline__ uint4 column_load(const uint32_t* in, uint64_t at, uint32_t have, bool stream)
+{
+    if (have >= 4u) {
+        if (ALIGNED) {
+            const u32x4* p = reinterpret_cast<const u32x4*>(in + at);
+            return to_uint4(stream ? __builtin_nontemporal_load(p) : *p);
+        }
+        const u32x4_at_dword* p = reinterpret_cast<const u32x4_at_dword*>(in + at);
+        const u32x4 w = stream ? __builtin_nontemporal_load(p) : *p;
+        return to_uint4(w);
+    }
+    uint4 v = {0u, 0u, 0u, 0u};
+    if (have > 0u) v.x = in[at];
+    if (have > 1u) v.y = in[at + 1];
+    if (have > 2u) v.z = in[at + 2];
+    return v;
+}
+
+template <bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void block_column_max_kernel(const uint32_t* in, uint4* colmax, ColumnGeom cg)
 {
     const uint32_t c = blockIdx.x * kThreads + threadIdx.x;
     if (c >= cg.row_groups) return;
     const uint64_t o0 = (uint64_t)blockIdx.y * cg.rows_per_slice;
     const uint64_t o1 = (o0 + cg.rows_per_slice < cg.outer) ? o0 + cg.rows_per_slice : cg.outer;
-    const uint4* col = reinterpret_cast<const uint4*>(in) + c;
+    const uint32_t have = cg.row - 4u * c;                  // columns of this run that exist (4 or more: a whole run)
     uint4 m = {0u, 0u, 0u, 0u};
     for (uint64_t o = o0; o < o1; o += 4) {
         uint4 v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             v[k] = make_uint4(0u, 0u, 0u, 0u);
-            if (o + k < o1) v[k] = col[(o + k) * cg.row_groups];
+            if (o + k < o1) v[k] = column_load<ALIGNED>(in, (o + k) * cg.row + 4ull * c, have, false);   // cached: read again in pass 2
         }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -551,7 +607,21 @@ __global__ __launch_bounds__(kThreads) void block_column_fold_kernel(const uint3
     if (lane == 0 && b < cg.nblocks) blockmax[b] = m;
 }
 
-template <int MODE>
+// The same fold with one THREAD per block, for blocks of few columns and few slices (a wavefront
+// per block would leave most of its lanes idle and need millions of workgroups).
+__global__ __launch_bounds__(kThreads) void block_column_fold_small_kernel(const uint32_t* colmax, uint32_t* blockmax, ColumnGeom cg)
+{
+    const uint64_t b = linear_block() * kThreads + threadIdx.x;
+    if (b >= cg.nblocks) return;
+    uint32_t m = 0;
+    for (uint32_t s = 0; s < cg.slices; ++s) {
+        const uint32_t* p = colmax + (uint64_t)s * (4ull * cg.row_groups) + b * cg.inner;
+        for (uint32_t i = 0; i < cg.inner; ++i) m = m > p[i] ? m : p[i];
+    }
+    blockmax[b] = m;
+}
+
+template <int MODE, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint32_t* in, uint32_t* out,
                                                                       const uint32_t* blockmax, ColumnGeom cg, int wl,
                                                                       int symmetric, RngKey key)
@@ -560,31 +630,41 @@ __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint
     if (c >= cg.row_groups) return;
     const uint64_t o0 = (uint64_t)blockIdx.y * cg.rows_per_slice;
     const uint64_t o1 = (o0 + cg.rows_per_slice < cg.outer) ? o0 + cg.rows_per_slice : cg.outer;
-    const uint32_t b0 = (4u * c) / cg.inner;
+    const uint32_t have = cg.row - 4u * c;
     GridPlan p[4];
     if (cg.inner % 4 == 0) {
-        p[0] = p[1] = p[2] = p[3] = block_plan(blockmax[b0], wl, symmetric);
+        p[0] = p[1] = p[2] = p[3] = block_plan(blockmax[(4u * c) / cg.inner], wl, symmetric);
     } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) p[e] = block_plan(blockmax[(4u * c + e) / cg.inner], wl, symmetric);
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t col = 4u * c + (uint32_t)e < cg.row ? 4u * c + (uint32_t)e : cg.row - 1u;
+            p[e] = block_plan(blockmax[col / cg.inner], wl, symmetric);
+        }
     }
     for (uint64_t o = o0; o < o1; o += 4) {
         uint4 v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (o + k < o1) v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in) + (o + k) * cg.row_groups + c));
+            if (o + k < o1) v[k] = column_load<ALIGNED>(in, (o + k) * cg.row + 4ull * c, have, true);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             if (o + k < o1) {
-                const uint64_t j = (o + k) * cg.row_groups + c;
+                const uint64_t at = (o + k) * cg.row + 4ull * c;
                 Words4 r = {{0u, 0u, 0u, 0u}};
-                if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+                if (MODE == QSIM_STOCHASTIC) r = ALIGNED ? random_words(at >> 2, key, 0u) : random_words_at(at, key, 0u);
                 uint4 q;
                 q.x = quantize_to_grid<MODE>(v[k].x, p[0], r.w[0]);
                 q.y = quantize_to_grid<MODE>(v[k].y, p[1], r.w[1]);
                 q.z = quantize_to_grid<MODE>(v[k].z, p[2], r.w[2]);
                 q.w = quantize_to_grid<MODE>(v[k].w, p[3], r.w[3]);
-                __builtin_nontemporal_store(to_u32x4(q), reinterpret_cast<u32x4*>(out) + j);
+                if (have >= 4u) {
+                    if (ALIGNED) __builtin_nontemporal_store(to_u32x4(q), reinterpret_cast<u32x4*>(out + at));
+                    else __builtin_nontemporal_store(to_u32x4(q), reinterpret_cast<u32x4_at_dword*>(out + at));
+                } else {
+                    if (have > 0u) out[at] = q.x;
+                    if (have > 1u) out[at + 1] = q.y;
+                    if (have > 2u) out[at + 2] = q.z;
+                }
             }
         }
     }

@@ -15,6 +15,13 @@ ratio.  Nearest rounding of the comparator is checked against the fused result o
 
 times block floating point with one block per row over row lengths from 1 to the whole tensor
 (64 Mi elements in all, three rotating buffer sets), to show which kernel form serves which shape.
+
+    python -m paper_1910_04540_amd.sweep --shape-scan SEED
+
+times block floating point over some 200 seeded random views [outer, nblocks, inner] of a tensor of
+up to 32 Mi elements (sizes spread over orders of magnitude, half of the inner lengths rounded to
+multiples of four) and prints the slowest shapes and the quartiles: a search for shapes that no
+kernel form serves well.
 """
 from __future__ import annotations
 
@@ -92,12 +99,54 @@ def block_shapes() -> int:
     return 0
 
 
+def shape_scan(seed: int) -> int:
+    import numpy as np
+
+    g = np.random.Generator(np.random.PCG64(seed))
+    total = 1 << 25
+    x = torch.randn(total + 64, device="cuda")
+    out = torch.empty(total + 64, device="cuda")
+    rows = []
+    for _ in range(220):
+        a = g.uniform(0, 25)
+        b = g.uniform(0, 25 - a)
+        if g.integers(0, 3) == 0:
+            a = 0.0
+        outer = max(1, int(round(2 ** a * g.uniform(0.7, 1.3))))
+        nblocks = max(1, int(round(2 ** b * g.uniform(0.7, 1.3))))
+        inner = max(1, total // (outer * nblocks))
+        if g.integers(0, 2) == 0:
+            inner = max(4, inner // 4 * 4)
+        n = outer * nblocks * inner
+        if n > total or n < total // 4:
+            continue
+        need = Q.block_workspace_bytes(n, outer, nblocks, inner)
+        if need > (1 << 31):
+            continue
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+        for mode, name in ((Q.RN_EVEN, "nearest"), (Q.STOCHASTIC, "stochastic")):
+            call = lambda: Q.block_quantize(x[:n], outer, nblocks, inner, 8, mode, 0, 1, 0, out=out[:n], workspace=ws)
+            for _ in range(4):
+                call()
+            us = _time(call, 8)
+            rows.append((n * 8 / us / 1e3 / 80.0, us, outer, nblocks, inner, n, name))
+        del ws
+    rows.sort()
+    print(f"{len(rows)} timings (shape x rounding), % of 8 TB/s at 8 B per element; slowest first")
+    for r in rows[:12]:
+        print(f"{r[0]:5.1f} %  {r[1]:8.1f} us  [{r[2]}, {r[3]}, {r[4]}]  n={r[5]}  {r[6]}")
+    q = [rows[int(len(rows) * f)][0] for f in (0.0, 0.25, 0.5, 0.75)] + [rows[-1][0]]
+    print("minimum, quartiles, maximum: " + ", ".join(f"{v:.1f} %" for v in q))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--min-log2", type=int, default=10)
     ap.add_argument("--max-log2", type=int, default=28)
     ap.add_argument("--json", action="store_true")
     ap.add_argument("--block-shapes", action="store_true")
+    ap.add_argument("--shape-scan", type=int, default=None, metavar="SEED")
     args = ap.parse_args()
     if not torch.cuda.is_available():
         print("the sweep needs a GPU", file=sys.stderr)
@@ -105,6 +154,8 @@ def main() -> int:
     Q.lib()
     if args.block_shapes:
         return block_shapes()
+    if args.shape_scan is not None:
+        return shape_scan(args.shape_scan)
     rows = []
     base = torch.from_numpy(W.normal_tensor(1 << 20, seed=21)).cuda()
     for lg in range(args.min_log2, args.max_log2 + 1, 2):

@@ -412,6 +412,29 @@ def test_block_short_blocks_along_an_inner_dimension(shape, rounding):
     assert_bit_equal(host(d), want, f"{shape} in place")
 
 
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("shape", [(4, 100003, 1), (46, 5743, 1), (71, 6029, 7), (22, 10601, 14), (631, 3035, 1), (9, 6, 20714),
+                                   (5, 3, 4098), (77, 1, 43577), (3, 4, 279622), (40, 72, 1165), (300, 5000, 3)])
+def test_block_rows_that_are_not_whole_groups_along_an_inner_dimension(shape, rounding):
+    """Blocks along an inner dimension when a row is not a multiple of four elements, or the blocks
+    are long and odd: the one-column-per-thread form and the general two-pass form; one block in
+    several outer pieces is the whole tensor."""
+    outer, nblocks, inner = shape
+    g = np.random.Generator(np.random.PCG64(sum(shape)))
+    scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
+    x = (g.standard_normal(shape, dtype=np.float32) * scale[None, :, None]).astype(np.float32)
+    want = R.block_quantize(x, outer, nblocks, inner, 8, rounding, 0, 6, 1).reshape(-1)
+    n = x.size
+    pad = dev(np.concatenate([np.zeros(2, np.float32), x.reshape(-1), np.zeros(2, np.float32)]))
+    for off in (2, 0):
+        view = pad[off:off + n]
+        if off == 0:
+            view.copy_(torch.from_numpy(x.reshape(-1)))
+        assert_bit_equal(host(Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 6, 1)), want, f"{shape} offset {off}")
+    Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 6, 1, out=view)
+    assert_bit_equal(host(view), want, f"{shape} in place")
+
+
 def test_block_per_channel_single_pass_when_the_wait_runs_out():
     Q.set_barrier_wait_us(0)
     try:
@@ -448,9 +471,9 @@ def test_block_single_pass_meets_without_waiting_out(log2n):
 
 def test_block_whole_tensor_beyond_register_capacity():
     """A single block of 20 Mi elements does not fit in the chip's registers: two streaming passes."""
-    n = 5 * (1 << 22)
-    x = W.row_scaled_matrix(1, n, seed=77)
-    _block_case(x, 1, 1, n, 8, STOCHASTIC)
+    for n in (5 * (1 << 22), 5 * (1 << 22) + 3):        # the second ends in a partial group
+        x = W.row_scaled_matrix(1, n, seed=77)
+        _block_case(x, 1, 1, n, 8, STOCHASTIC)
 
 
 def test_block_workspace_next_to_the_arrays():
