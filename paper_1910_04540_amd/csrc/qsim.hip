@@ -107,7 +107,7 @@ constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass for
 constexpr uint64_t kColumnThreads = 1ull << 19;  // threads the column form aims for
 constexpr uint64_t kColumnShortInner = 64;       // below: always; up to kColumnMaxInner: when there are enough blocks
 constexpr uint64_t kColumnMaxInner = 4096;       // to keep the one-wavefront-per-block fold parallel
-constexpr uint64_t kColumnManyBlocks = 1024;
+constexpr uint64_t kColumnManyBlocks = 1024;      // (a quarter of both also qualifies: 256 blocks of up to 1024)
 constexpr uint32_t kColumnParts = 8;             // slices left after the first, coalesced fold of its column maxima
 constexpr uint64_t kFlatWorkgroups = 1024;       // workgroups of the flat form (four per CU)
 constexpr uint32_t kFlatParts = 32;              // parts of its first fold
@@ -226,7 +226,8 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
     // column arithmetic.
     const unsigned __int128 row = (unsigned __int128)nblocks * inner;
     if (outer > 1 && row <= (1ull << 31) && outer <= (1ull << 32) &&
-        (inner < kColumnShortInner || (inner <= kColumnMaxInner && nblocks >= kColumnManyBlocks))) {
+        (inner < kColumnShortInner || (inner <= kColumnMaxInner / 4 && nblocks >= kColumnManyBlocks / 4) ||
+         (inner <= kColumnMaxInner && nblocks >= kColumnManyBlocks))) {
         s.column = true;
         s.cg = column_geometry(outer, nblocks, inner);
         const size_t bytes = column_bytes(s.cg);
