@@ -139,6 +139,28 @@ def test_many_small_blocks_beyond_32_bits():
     torch.cuda.empty_cache()
 
 
+def test_blocks_along_a_dimension_beyond_32_bits():
+    """[16, 4200, 65536] = 2^32 + 1.1e8 elements with one block per middle index (64 slices of 16 Ki
+    each, workgroups of a block meeting among themselves), nearest rounding in place; three blocks
+    gathered from the GPU and checked against the oracle."""
+    outer, nblocks, inner = 16, 4200, 65536
+    n = outer * nblocks * inner
+    free, _ = torch.cuda.mem_get_info()
+    if free < n * 4 + (4 << 30):
+        pytest.skip("not enough free device memory for an 18 GiB tensor")
+    x = torch.randn(n, device="cuda")
+    view = x.view(outer, nblocks, inner)
+    view *= torch.exp2(torch.randint(-12, 12, (nblocks,), device="cuda").float())[None, :, None]
+    picks = [0, 2099, nblocks - 1]
+    before = {b: host(view[:, b, :]).copy() for b in picks}
+    Q.block_quantize(x, outer, nblocks, inner, 8, RN_EVEN, out=x)
+    for b in picks:
+        want = R.block_quantize(before[b], outer, 1, inner, 8, RN_EVEN)
+        assert_bit_equal(host(view[:, b, :]).reshape(-1), want.reshape(-1), f"block {b}")
+    del x, view
+    torch.cuda.empty_cache()
+
+
 def test_seed_and_stream_select_the_words():
     x = dev(W.uniform_with_outliers(1 << 14, seed=3))
     a = host(Q.fixed_quantize(x, 8, 6, STOCHASTIC, SATURATE, seed=1, stream_id=0))
