@@ -35,62 +35,25 @@ def sgd_format(number: Number, rounding: Union[str, int] = "nearest", chunk: int
     raise TypeError("number must be FloatingPoint, FixedPoint, BlockFloatingPoint or None")
 
 
-class QuantSGD:
-    """SGD with momentum whose gradient, momentum buffer and weight pass through a quantizer each.
+class _Group:
+    """The parameters that share one set of hyper-parameters: one device table, one launch per step."""
 
-    Per element, in fp32 (``include/qsim.h``, qsim_sgd_options):
-        gq = Qg(grad);  d = gq + weight_decay * w;  v = Qm(momentum * v + (1 - dampening) * d)
-        w  = w - lr * (nesterov ? d + momentum * v : v);  quantized copy = Qw(w)
-    The momentum buffers start at zero, so the first step gives v = Qm((1 - dampening) * d)
-    (``torch.optim.SGD`` takes v = d on its first step: the two differ when dampening != 0).
-
-    ``weights``:
-        "master"    parameters stay fp32 (the high-precision copy for accumulation, Sec. 1
-                    footnote); ``quantized[i]`` holds Qw of parameter i after each step.
-        "in_place"  the parameters themselves are kept in the weight format.
-        "none"      no quantized copy is produced.
-
-    Stochastic rounding: step s (counted from 0) of parameter t draws from Philox stream
-    ``(s * len(params) + t) mod 2^32`` of ``seed``.
-    """
-
-    def __init__(self, params: Iterable[torch.Tensor], lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
-                 dampening: float = 0.0, nesterov: bool = False, grad_number: Number = None,
-                 momentum_number: Number = None, weight_number: Number = None, grad_rounding="stochastic",
-                 momentum_rounding="stochastic", weight_rounding="nearest", chunk: int = 256, weights: str = "master",
-                 seed: int = 0):
-        self.params = [p for p in params]
+    def __init__(self, params, lr, momentum, weight_decay, dampening, nesterov, weights, first_stream):
+        self.params = list(params)
         if not self.params:
-            raise ValueError("no parameters")
-        if weights not in ("master", "in_place", "none"):
-            raise ValueError('weights must be "master", "in_place" or "none"')
+            raise ValueError("a parameter group is empty")
         for p in self.params:
             Q._device_f32(p.data, "parameter")
         self.lr, self.momentum = float(lr), float(momentum)
         self.options = Q.SgdOptions(float(weight_decay), float(dampening), 1 if nesterov else 0)
-        self.fmt_grad = sgd_format(grad_number, grad_rounding, chunk)
-        self.fmt_mom = sgd_format(momentum_number, momentum_rounding, chunk)
-        self.fmt_weight = sgd_format(weight_number, weight_rounding, chunk)
         self.weights = weights
-        self.seed = int(seed)
-        self.steps = 0
+        self.first_stream = first_stream            # position of the group's first parameter among all parameters
         self.momentum_buffers = [torch.zeros_like(p.data) for p in self.params]
-        self.quantized: Optional[list] = [torch.empty_like(p.data) for p in self.params] if weights == "master" else None
+        self.quantized = [torch.empty_like(p.data) for p in self.params] if weights == "master" else None
         self._list: Optional[Q.SgdTensorList] = None
         self._grad_ptrs: Optional[list] = None
 
-    def zero_grad(self, set_to_none: bool = False) -> None:
-        """Zeroing in place (the default here) keeps the gradient tensors, and with them the device
-        table, from one step to the next."""
-        for p in self.params:
-            if p.grad is not None:
-                if set_to_none:
-                    p.grad = None
-                else:
-                    p.grad.detach_()
-                    p.grad.zero_()
-
-    def _tensor_list(self) -> Q.SgdTensorList:
+    def tensor_list(self) -> Q.SgdTensorList:
         grads = []
         for p in self.params:
             if p.grad is None:
@@ -104,9 +67,81 @@ class QuantSGD:
             self._grad_ptrs = ptrs
         return self._list
 
+
+class QuantSGD:
+    """SGD with momentum whose gradient, momentum buffer and weight pass through a quantizer each.
+
+    Per element, in fp32 (``include/qsim.h``, qsim_sgd_options):
+        gq = Qg(grad);  d = gq + weight_decay * w;  v = Qm(momentum * v + (1 - dampening) * d)
+        w  = w - lr * (nesterov ? d + momentum * v : v);  quantized copy = Qw(w)
+    The momentum buffers start at zero, so the first step gives v = Qm((1 - dampening) * d)
+    (``torch.optim.SGD`` takes v = d on its first step: the two differ when dampening != 0).
+
+    ``params``: an iterable of parameters, or of dicts ``{"params": [...], "lr": ..., "momentum": ...,
+    "weight_decay": ..., "dampening": ..., "nesterov": ...}`` as ``torch.optim`` takes them (weights
+    with decay and biases without, say); a missing key takes the value given to the constructor.
+    Each group is one fused launch per step.
+
+    ``weights``:
+        "master"    parameters stay fp32 (the high-precision copy for accumulation, Sec. 1
+                    footnote); ``quantized[i]`` holds Qw of parameter i after each step.
+        "in_place"  the parameters themselves are kept in the weight format.
+        "none"      no quantized copy is produced.
+
+    Stochastic rounding: step s (counted from 0) of parameter t (counted over all groups in order)
+    draws from Philox stream ``(s * number of parameters + t) mod 2^32`` of ``seed``.
+    """
+
+    def __init__(self, params: Iterable, lr: float, momentum: float = 0.0, weight_decay: float = 0.0,
+                 dampening: float = 0.0, nesterov: bool = False, grad_number: Number = None,
+                 momentum_number: Number = None, weight_number: Number = None, grad_rounding="stochastic",
+                 momentum_rounding="stochastic", weight_rounding="nearest", chunk: int = 256, weights: str = "master",
+                 seed: int = 0):
+        if weights not in ("master", "in_place", "none"):
+            raise ValueError('weights must be "master", "in_place" or "none"')
+        items = list(params)
+        if not items:
+            raise ValueError("no parameters")
+        if not isinstance(items[0], dict):
+            items = [{"params": items}]
+        defaults = {"lr": lr, "momentum": momentum, "weight_decay": weight_decay, "dampening": dampening, "nesterov": nesterov}
+        self.groups = []
+        count = 0
+        for item in items:
+            unknown = set(item) - set(defaults) - {"params"}
+            if unknown:
+                raise ValueError(f"unknown keys in a parameter group: {sorted(unknown)}")
+            cfg = {k: item.get(k, v) for k, v in defaults.items()}
+            group = _Group(item["params"], cfg["lr"], cfg["momentum"], cfg["weight_decay"], cfg["dampening"], cfg["nesterov"],
+                           weights, count)
+            count += len(group.params)
+            self.groups.append(group)
+        self.fmt_grad = sgd_format(grad_number, grad_rounding, chunk)
+        self.fmt_mom = sgd_format(momentum_number, momentum_rounding, chunk)
+        self.fmt_weight = sgd_format(weight_number, weight_rounding, chunk)
+        self.weights = weights
+        self.seed = int(seed)
+        self.steps = 0
+        self.params = [p for g in self.groups for p in g.params]
+        self.momentum_buffers = [m for g in self.groups for m in g.momentum_buffers]
+        self.quantized: Optional[list] = [q for g in self.groups for q in g.quantized] if weights == "master" else None
+
+    def zero_grad(self, set_to_none: bool = False) -> None:
+        """Zeroing in place (the default here) keeps the gradient tensors, and with them the device
+        tables, from one step to the next."""
+        for p in self.params:
+            if p.grad is not None:
+                if set_to_none:
+                    p.grad = None
+                else:
+                    p.grad.detach_()
+                    p.grad.zero_()
+
     @torch.no_grad()
     def step(self) -> None:
-        lst = self._tensor_list()
-        stream = (self.steps * len(self.params)) & 0xFFFFFFFF
-        lst.step(self.lr, self.momentum, self.fmt_grad, self.fmt_mom, self.fmt_weight, self.seed, stream, self.options)
+        lists = [g.tensor_list() for g in self.groups]          # every gradient is checked before anything is updated
+        base = self.steps * len(self.params)
+        for g, lst in zip(self.groups, lists):
+            lst.step(g.lr, g.momentum, self.fmt_grad, self.fmt_mom, self.fmt_weight, self.seed,
+                     (base + g.first_stream) & 0xFFFFFFFF, g.options)
         self.steps += 1

@@ -86,3 +86,35 @@ def test_a_small_model_trains():
         opt.step()
         losses.append(float(loss.detach()))
     assert losses[-1] < 0.1 * losses[0]
+
+
+def test_parameter_groups_with_their_own_hyper_parameters():
+    """Two groups (weights with decay and a larger learning rate, biases without): each is one launch,
+    streams keep counting over all parameters."""
+    state = _state(0)
+    params = [torch.nn.Parameter(torch.from_numpy(w).cuda()) for w, _ in state]
+    decay, plain = [0, 2, 4], [1, 3, 5]
+    opt = QuantSGD([{"params": [params[i] for i in decay], "weight_decay": 1e-3, "lr": 0.1},
+                    {"params": [params[i] for i in plain], "nesterov": True}],
+                   lr=0.02, momentum=0.9, grad_number=FloatingPoint(5, 2, subnormal=True),
+                   momentum_number=FixedPoint(16, 12), weight_number=BlockFloatingPoint(8), chunk=64, seed=5)
+    fg = R.Format(R.KIND_FLOAT, 5, 2, R.STOCHASTIC, R.SATURATE | R.SUBNORMAL)
+    fm = R.Format(R.KIND_FIXED, 16, 12, R.STOCHASTIC, R.SATURATE)
+    fw = R.Format(R.KIND_BLOCK, 8, 64, R.RN_EVEN, 0)
+    order = decay + plain                      # the optimizer's own numbering of the parameters
+    ref_w = {i: state[i][0].reshape(-1).copy() for i in order}
+    ref_m = {i: np.zeros_like(ref_w[i]) for i in order}
+    for step in range(2):
+        grads = [g for _, g in _state(step)]
+        for p, g in zip(params, grads):
+            p.grad = torch.from_numpy(g).cuda()
+        opt.step()
+        for t, i in enumerate(order):
+            lr, options = (0.1, R.SgdOptions(1e-3, 0.0, 0)) if i in decay else (0.02, R.SgdOptions(0.0, 0.0, 1))
+            w, wq, m = R.quant_sgd_step(ref_w[i], grads[i], ref_m[i], lr, 0.9, fg, fm, fw, 5, step * 6 + t, options=options)
+            ref_w[i], ref_m[i] = w, m
+            assert_bit_equal(host(params[i].data), w, f"step {step}, weights of parameter {i}")
+            assert_bit_equal(host(opt.momentum_buffers[t]), m, f"step {step}, momentum of parameter {i}")
+            assert_bit_equal(host(opt.quantized[t]), wq, f"step {step}, quantized copy of parameter {i}")
+    with pytest.raises(ValueError):
+        QuantSGD([{"params": params, "learning_rate": 0.1}], lr=0.1)
