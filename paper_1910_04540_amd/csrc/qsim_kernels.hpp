@@ -519,11 +519,11 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
     }
 }
 
-// Blocks along an inner dimension (outer > 1) when a row of nblocks * inner elements is a whole
-// number of groups and the arrays are aligned: the "column" form.  A thread owns one group of four
-// neighbouring columns and a slice of rows and walks down its rows, so every access is a coalesced
-// dwordx4 along the row, whatever the block length; the block of each of its four columns is
-// fixed, so the index arithmetic (one division per column) is paid once per thread.
+// Blocks along an inner dimension (outer > 1) made of short segments: the "column" form, for any
+// row length and alignment.  A thread owns a run of four neighbouring columns and a slice of rows
+// and walks down its rows, so every access is a coalesced dwordx4 along the row, whatever the
+// block length; the block of each of its four columns is fixed, so the index arithmetic (one
+// division per column) is paid once per thread.
 //   pass 1   per-column maxima of every row slice       -> colmax[slice][column]
 //   fold     block maximum = max over slices and over the block's `inner` columns -> blockmax[b]
 //   pass 2   the same walk again: quantize with the plans of the four columns' blocks
