@@ -182,12 +182,25 @@ def block_workspace_bytes(n, outer, nblocks, inner) -> int:
     return int(lib().qsim_block_workspace_bytes(n, outer, nblocks, inner))
 
 
+_scratch = {}                    # (device index, stream handle) -> uint8 tensor, reused by calls on that stream
+_SCRATCH_KEEP = 64 << 20         # larger scratch is allocated per call and released with it
+
+
 def _workspace(x, outer, nblocks, inner, workspace):
     need = block_workspace_bytes(x.numel(), outer, nblocks, inner)
     if not need:
         return 0, 0, None
     if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        if need > _SCRATCH_KEEP or torch.cuda.is_current_stream_capturing():
+            # (memory allocated during a graph capture belongs to the graph: never shared with eager calls)
+            workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        else:
+            # calls on one stream run one after the other, so they can share a scratch buffer
+            key = (x.device.index, _stream())
+            workspace = _scratch.get(key)
+            if workspace is None or workspace.numel() < need:
+                workspace = torch.empty(max(need, 1 << 20), dtype=torch.uint8, device=x.device)
+                _scratch[key] = workspace
     return workspace.data_ptr(), workspace.numel() * workspace.element_size(), workspace
 
 
