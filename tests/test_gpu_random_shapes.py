@@ -136,3 +136,33 @@ def test_random_sgd_steps(seed):
         assert_bit_equal(dw.cpu().numpy()[ok], wr[ok], what + ": weights")
         if mode == "copy":
             assert_bit_equal(dq.cpu().numpy()[ok], wqr[ok], what + ": quantized weights")
+
+
+def test_random_views_of_a_large_tensor():
+    """Seeded random views [outer, nblocks, inner] of 4 to 32 Mi elements (the sizes at which the
+    single-pass, block-by-block, flat, column and two-pass forms are chosen), against the oracle."""
+    g = np.random.Generator(np.random.PCG64(77))
+    total = 1 << 25
+    done = 0
+    while done < 16:
+        a = g.uniform(0, 25)
+        b = g.uniform(0, 25 - a)
+        if g.integers(0, 3) == 0:
+            a = 0.0
+        outer = max(1, int(round(2 ** a * g.uniform(0.7, 1.3))))
+        nblocks = max(1, int(round(2 ** b * g.uniform(0.7, 1.3))))
+        inner = max(1, total // (outer * nblocks))
+        if g.integers(0, 2) == 0:
+            inner = max(4, inner // 4 * 4)
+        n = outer * nblocks * inner
+        if n > total or n < total // 8:
+            continue
+        rounding, offset = int(g.integers(0, 4)), int(g.choice([0, 0, 1]))
+        scale = np.exp2(g.integers(-10, 10, size=nblocks)).astype(np.float32)
+        x = (g.standard_normal((outer, nblocks, inner), dtype=np.float32) * scale[None, :, None]).astype(np.float32).reshape(-1)
+        want = R.block_quantize(x, outer, nblocks, inner, 8, rounding, 0, 5, done)
+        d = torch.from_numpy(np.concatenate([np.zeros(offset, np.float32), x])).cuda()[offset:]
+        got = Q.block_quantize(d, outer, nblocks, inner, 8, rounding, 0, 5, done)
+        torch.cuda.synchronize()
+        assert_bit_equal(got.cpu().numpy(), want.reshape(-1), f"[{outer},{nblocks},{inner}] n={n} mode={rounding} offset={offset}")
+        done += 1
