@@ -205,3 +205,15 @@ def test_shard_validation_without_gpu():
     assert L.qsim_block_quantize_with_max(FAKE, FAKE, 64, 1, 4, 16, 0, 1, 0, 0, 0, 0, mx, None) == 2
     assert L.qsim_block_quantize_with_max(FAKE, FAKE, 64, 1, 4, 16, 0, 8, 0, 0, 0, 0, FAKE + 16, None) == 5
     assert L.qsim_block_quantize_with_max(FAKE, FAKE, 0, 1, 4, 16, 0, 8, 0, 0, 0, 0, None, None) == 0
+
+
+def test_header_is_plain_c():
+    """The boundary is a C-ABI: the header must compile as C99 (and as C++) on its own."""
+    import shutil
+    import subprocess
+
+    header = os.path.join(ROOT, "include", "qsim.h")
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", header], check=True)
