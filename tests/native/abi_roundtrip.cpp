@@ -61,8 +61,48 @@ static std::vector<float> inputs(size_t n, uint64_t seed)
     return x;
 }
 
-int main()
+// `abi_roundtrip bench`: the headline workload timed by this program itself (HIP events around 300
+// launches on three rotating buffer sets after 300 warm-up launches), as a cross-check of the figure
+// the Python benchmark reports.
+static int bench()
 {
+    const size_t n = 1ull << 26;
+    const int sets = 3, reps = 300;
+    std::vector<float> x = inputs(1 << 20, 4);
+    float *in[sets], *out[sets];
+    hipStream_t stream;
+    HIP_OK(hipStreamCreate(&stream));
+    for (int s = 0; s < sets; ++s) {
+        HIP_OK(hipMalloc(&in[s], n * 4));
+        HIP_OK(hipMalloc(&out[s], n * 4));
+        for (size_t off = 0; off < n; off += x.size()) HIP_OK(hipMemcpy(in[s] + off, x.data(), x.size() * 4, hipMemcpyHostToDevice));
+    }
+    hipEvent_t e0, e1;
+    HIP_OK(hipEventCreate(&e0));
+    HIP_OK(hipEventCreate(&e1));
+    for (int r = 0; r < reps; ++r)
+        if (qsim_fixed_quantize(in[r % sets], out[r % sets], n, 8, 6, QSIM_STOCHASTIC, QSIM_SATURATE, 1234, r, stream) != QSIM_OK) return 3;
+    HIP_OK(hipStreamSynchronize(stream));
+    HIP_OK(hipEventRecord(e0, stream));
+    for (int r = 0; r < reps; ++r)
+        if (qsim_fixed_quantize(in[r % sets], out[r % sets], n, 8, 6, QSIM_STOCHASTIC, QSIM_SATURATE, 1234, r, stream) != QSIM_OK) return 3;
+    HIP_OK(hipEventRecord(e1, stream));
+    HIP_OK(hipEventSynchronize(e1));
+    float ms = 0;
+    HIP_OK(hipEventElapsedTime(&ms, e0, e1));
+    const double us = ms * 1e3 / reps;
+    std::printf("fixed(8,6) stochastic, %zu elements: %.1f us per call, %.1f G elements/s, %.0f GB/s = %.1f %% of 8 TB/s\n", n, us,
+                n / us / 1e3, n * 8.0 / us / 1e3, n * 8.0 / us / 1e3 / 80.0);
+    for (int s = 0; s < sets; ++s) {
+        HIP_OK(hipFree(in[s]));
+        HIP_OK(hipFree(out[s]));
+    }
+    return 0;
+}
+
+int main(int argc, char** argv)
+{
+    if (argc > 1 && std::strcmp(argv[1], "bench") == 0) return bench();
     int devices = 0;
     HIP_OK(hipGetDeviceCount(&devices));
     if (devices == 0) {
