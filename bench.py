@@ -199,6 +199,21 @@ def main() -> int:
             run(f"block8_whole_tensor_{tag}", lambda k, mode=mode: Q.block_quantize(
                 m_in[k % NSETS], 1, 1, nm, 8, mode, 0, 1234, k, out=m_out[k % NSETS], workspace=ws), nm,
                 extra={"note": "single pass: 1024 resident workgroups hold the tensor in registers and meet once"})
+        # one GPU's share of the same tensor split over two: block maxima of the share, the elementwise
+        # maximum that stands in for the max-all-reduce, then quantize with the given maxima
+        half = nm // 2
+        other_max = Q.block_max(m_in[0].reshape(-1)[half:], 1, 1, nm - half, workspace=ws)
+        share_max = torch.empty_like(other_max)
+
+        def shard(k):
+            x = m_in[k % NSETS].reshape(-1)[:half]
+            Q.block_max(x, 1, 1, half, out=share_max, workspace=ws)
+            torch.maximum(share_max, other_max, out=share_max)
+            Q.block_quantize_with_max(x, 1, 1, half, 8, share_max, Q.STOCHASTIC, 0, 1234, k,
+                                      out=m_out[k % NSETS].reshape(-1)[:half])
+
+        run("block8_whole_tensor_one_of_two_shards_stochastic", shard, half,
+            extra={"note": "block_max + maximum + block_quantize_with_max on half of the tensor: two passes, 12 B/element"})
         del m_in, m_out
         torch.cuda.empty_cache()
 

@@ -424,7 +424,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         const unsigned by = (unsigned)(g.nblocks < 65535 ? g.nblocks : 65535);
         hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
-                           partial, s.sg, wl, symmetric, key);
+                           partial, s.sg.slices, s.sg, wl, symmetric, key);
     } else if (vec && s.strided_packed) {
         const uint64_t wgs = (g.nblocks + s.spg.blocks_per_wg - 1) / s.spg.blocks_per_wg;
         hipLaunchKernelGGL((block_strided_packed_kernel<MODE>), folded(wgs), dim3(kThreads), 0, stream, pin, pout, s.spg, wl,
@@ -519,7 +519,13 @@ static int launch_block_given_max(const float* in, float* out, const SliceGeom& 
                                   const uint32_t* block_max, hipStream_t stream)
 {
     const dim3 grid = folded_xz(sg.g.nblocks, sg.slices);
-    if (aligned16(in) && aligned16(out) && sg.g.inner % 4 == 0)
+    const bool vec = aligned16(in) && aligned16(out) && (sg.g.inner % 4 == 0 || sg.g.nblocks == 1);
+    if (vec && sg.g.outer == 1) {
+        // contiguous blocks: the streaming form (blocks on grid.y, folded when there are more than 65535)
+        const unsigned by = (unsigned)(sg.g.nblocks < 65535 ? sg.g.nblocks : 65535);
+        hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(sg.slices, by), dim3(kThreads), 0, stream, u32(in), u32(out),
+                           block_max, 1u, sg, wl, symmetric, key);
+    } else if (vec)
         hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, u32(in), u32(out), block_max, 1u,
                            sg, wl, symmetric, key);
     else
@@ -648,11 +654,18 @@ int qsim_block_max(const float* in, uint64_t n, uint64_t outer, uint64_t nblocks
     }
     hipStream_t stream = as_stream(hip_stream);
     const dim3 grid = folded_xz(nblocks, sg.slices);
-    if (aligned16(in) && sg.g.inner % 4 == 0)
+    const bool vec = aligned16(in) && (sg.g.inner % 4 == 0 || sg.g.nblocks == 1);
+    if (vec && sg.g.outer == 1) {
+        const unsigned by = (unsigned)(sg.g.nblocks < 65535 ? sg.g.nblocks : 65535);
+        hipLaunchKernelGGL(block_slice_max_kernel, dim3(sg.slices, by), dim3(kThreads), 0, stream, u32(in), partial, sg);
+    } else if (vec)
         hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, u32(in), partial, sg);
     else
         hipLaunchKernelGGL((block_partial_max_kernel<false>), grid, dim3(kThreads), 0, stream, u32(in), partial, sg);
-    if (sg.slices > 1)
+    if (sg.slices >= 32)
+        hipLaunchKernelGGL(block_fold_partials_wide_kernel, folded(nblocks), dim3(kThreads), 0, stream, partial, block_max, nblocks,
+                           sg.slices);
+    else if (sg.slices > 1)
         hipLaunchKernelGGL(block_fold_partials_kernel, folded((nblocks + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
                            partial, block_max, nblocks, sg.slices);
     return launch_status();

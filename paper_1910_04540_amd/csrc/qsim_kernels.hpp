@@ -470,6 +470,23 @@ __global__ __launch_bounds__(kThreads) void block_fold_partials_kernel(const uin
     block_max[b] = m;
 }
 
+// The same with one workgroup per block, for blocks of many slices (one thread would walk them one
+// after the other: 512 slices took 33 us).
+__global__ __launch_bounds__(kThreads) void block_fold_partials_wide_kernel(const uint32_t* partial, uint32_t* block_max,
+                                                                            uint64_t nblocks, uint32_t slices)
+{
+    __shared__ uint32_t lds[kThreads / 64];
+    const uint64_t b = linear_block();
+    if (b >= nblocks) return;                          // the whole workgroup leaves together
+    uint32_t m = 0;
+    for (uint32_t s = threadIdx.x; s < slices; s += kThreads) {
+        const uint32_t a = partial[b * slices + s];
+        m = m > a ? m : a;
+    }
+    m = workgroup_max(m, lds);
+    if (threadIdx.x == 0) block_max[b] = m;
+}
+
 // `npartial` maxima per block are folded: the slices of pass 1, or 1 when the caller supplies
 // finished block maxima.
 template <int MODE, bool VEC>
@@ -893,14 +910,15 @@ __global__ __launch_bounds__(kThreads) void block_slice_max_kernel(const uint32_
 
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void block_slice_apply_kernel(const uint32_t* in, uint32_t* out,
-                                                                     const uint32_t* partial, SliceGeom sg, int wl,
-                                                                     int symmetric, RngKey key)
+                                                                     const uint32_t* partial, uint32_t npartial, SliceGeom sg,
+                                                                     int wl, int symmetric, RngKey key)
 {
+    // `npartial` maxima per block are folded: the slices of pass 1, or 1 when the caller supplies finished maxima
     __shared__ uint32_t lds[kThreads / 64];
     for (uint64_t b = blockIdx.y; b < sg.g.nblocks; b += gridDim.y) {
         uint32_t m = 0;
-        for (uint32_t s = threadIdx.x; s < sg.slices; s += kThreads) {
-            const uint32_t a = partial[b * sg.slices + s];
+        for (uint32_t s = threadIdx.x; s < npartial; s += kThreads) {
+            const uint32_t a = partial[b * npartial + s];
             m = m > a ? m : a;
         }
         const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
