@@ -95,3 +95,49 @@ def test_graph_replays_the_table_step():
         torch.cuda.synchronize()
         assert_bit_equal(w.cpu().numpy(), ew.cpu().numpy(), f"weights, replay {replay}")
         assert_bit_equal(m.cpu().numpy(), em.cpu().numpy(), f"momentum, replay {replay}")
+
+
+def test_graph_replays_every_block_form():
+    """Every multi-launch block form (single pass block by block, packed, flat, column, two-pass,
+    the split max / quantize pair) captured once and replayed on new data."""
+    if not torch.cuda.is_available():
+        pytest.fail("needs a GPU")
+    shapes = [(32, 64, 3136), (2, 3000, 64), (5000, 3, 300), (300, 4096, 1), (9, 6, 20714), (1, 300, 70000), (1, 700, 1001),
+              (1, 1, 3 * (1 << 20) + 1)]
+    xs = [torch.empty(o * b * i, device="cuda") for o, b, i in shapes]
+    outs = [torch.empty_like(x) for x in xs]
+    wss = [torch.empty(max(Q.block_workspace_bytes(x.numel(), *s), 16), dtype=torch.uint8, device="cuda") for x, s in zip(xs, shapes)]
+    maxima = torch.empty(shapes[0][1], dtype=torch.int32, device="cuda")
+    split_out = torch.empty_like(xs[0])
+
+    def calls(dst, dst_split):
+        for x, s, o, ws in zip(xs, shapes, dst, wss):
+            Q.block_quantize(x, *s, 8, Q.STOCHASTIC, 0, 3, 1, out=o, workspace=ws)
+        Q.block_max(xs[0], *shapes[0], out=maxima, workspace=wss[0])
+        Q.block_quantize_with_max(xs[0], *shapes[0], 8, maxima, Q.STOCHASTIC, 0, 3, 1, out=dst_split)
+
+    def fill(seed):
+        g = np.random.Generator(np.random.PCG64(seed))
+        for x in xs:
+            x.copy_(torch.from_numpy((g.standard_normal(x.numel(), dtype=np.float32) *
+                                      np.exp2(g.integers(-8, 8, x.numel()))).astype(np.float32)))
+
+    fill(1)
+    calls(outs, split_out)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        calls(outs, split_out)
+    for replay in range(3):
+        fill(100 + replay)
+        eager = [torch.empty_like(x) for x in xs]
+        eager_split = torch.empty_like(xs[0])
+        calls(eager, eager_split)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for s, a, b in zip(shapes, outs, eager):
+            assert_bit_equal(a.cpu().numpy(), b.cpu().numpy(), f"{s}, replay {replay}")
+        assert_bit_equal(split_out.cpu().numpy(), eager_split.cpu().numpy(), f"split pair, replay {replay}")
+        assert_bit_equal(split_out.cpu().numpy(), outs[0].cpu().numpy(), f"split pair equals the fused call, replay {replay}")
