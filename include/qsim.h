@@ -10,7 +10,10 @@
  *   - Every data pointer is a DEVICE pointer owned by the caller.  Format descriptors
  *     (qsim_format) are HOST pointers, read before the call returns.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
- *     enqueued on it and the call returns without synchronising.
+ *     enqueued on it and the call returns without synchronising (qsim_sgd_table_build excepted),
+ *     so calls can be recorded by a stream capture into a HIP graph: every call is kernel launches
+ *     only.  The first qsim_block_quantize of a single-pass shape on a device asks the runtime for
+ *     the kernel's occupancy once; make that first call outside a capture.
  *   - The library allocates and frees no device memory.  Scratch memory and tables, where needed,
  *     are the caller's (`workspace`, `table_device`).
  *   - in == out (exactly the same array) is allowed; any other overlap between arrays of one
