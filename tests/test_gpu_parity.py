@@ -420,7 +420,7 @@ def test_block_per_channel_single_pass(shape, rounding):
 
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
 @pytest.mark.parametrize("shape", [(2, 300000, 64), (4, 1000, 4), (2, 5, 1024), (8, 50000, 128), (3, 100001, 100), (2, 1, 4),
-                                   (512, 70000, 4), (2, 1000003, 16), (32, 33, 64)])
+                                   (512, 20000, 4), (2, 1000003, 16), (32, 33, 64)])
 def test_block_short_blocks_along_an_inner_dimension(shape, rounding):
     """Blocks of at most 2048 elements made of whole-group segments: several blocks per workgroup, single pass."""
     outer, nblocks, inner = shape
