@@ -87,6 +87,8 @@ struct BlockSchedule {
     StridedPackedGeom spg;
     bool strided_cluster;  // outer > 1, aligned segments of >= 64 elements, blocks of up to 256 slices: the same
     StridedClusterGeom scg;
+    bool strided_ragged;   // outer > 1, segments of >= 64 elements of any length and alignment: the same
+    RaggedClusterGeom rcg;
     bool flat;             // outer > 1 and short rows: the flat form (any alignment)
     FlatGeom fg;
     bool column;           // outer > 1 and short blocks: the column form (any row length, any alignment)
@@ -104,6 +106,7 @@ constexpr uint32_t kMaxSlices = 1024;
 constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
 constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
+constexpr uint64_t kRaggedMinGroups = 2048;      // smallest block, in group slots, for the single pass over odd segments
 constexpr uint64_t kColumnThreads = 1ull << 19;  // threads the column form aims for
 constexpr uint64_t kColumnShortInner = 64;       // below: always; up to kColumnMaxInner: when there are enough blocks
 constexpr uint64_t kColumnMaxInner = 4096;       // to keep the one-wavefront-per-block fold parallel
@@ -195,6 +198,29 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
             s.scg.total_wgs = (uint32_t)(nblocks * slices_each);
             const size_t bytes = (size_t)s.scg.total_wgs * sizeof(uint32_t);
             if (s.workspace < bytes) s.workspace = bytes;
+        }
+    }
+    if (outer > 1 && inner >= 64 && inner <= (1ull << 22)) {
+        const uint64_t seg_groups = (inner + 2) / 4 + 1;
+        const unsigned __int128 block_groups = (unsigned __int128)outer * seg_groups;
+        // (a block has workgroups of its own, four of which fit a CU: with fewer than eight loads per
+        // thread in flight they do not keep the memory busy, and the column form measured faster)
+        if (block_groups >= kRaggedMinGroups && block_groups <= (uint64_t)kStridedMaxSlices * kRaggedSliceGroups) {
+            const uint64_t slices_each = ((uint64_t)block_groups + kRaggedSliceGroups - 1) / kRaggedSliceGroups;
+            if (nblocks * slices_each <= kClusterMaxWgs) {
+                s.strided_ragged = true;
+                s.rcg.n = n;
+                s.rcg.nblocks = nblocks;
+                s.rcg.inner = (uint32_t)inner;
+                s.rcg.seg_groups = (uint32_t)seg_groups;
+                s.rcg.magic_groups = (uint32_t)((1ull << 32) / seg_groups) + 1u;
+                s.rcg.block_groups = (uint32_t)block_groups;
+                s.rcg.slices = (uint32_t)slices_each;
+                s.rcg.slice_groups = (uint32_t)(((uint64_t)block_groups + slices_each - 1) / slices_each);
+                s.rcg.total_wgs = (uint32_t)(nblocks * slices_each);
+                const size_t bytes = (size_t)s.rcg.total_wgs * sizeof(uint32_t);
+                if (s.workspace < bytes) s.workspace = bytes;
+            }
         }
     }
     // the flat form: short rows, few enough blocks for a table in LDS
@@ -436,6 +462,15 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         hipLaunchKernelGGL(block_sync_clear_kernel, folded((cg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
                            partial, cg.total_wgs);
         hipLaunchKernelGGL((block_cluster_strided_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
+                           partial, cg, wl, symmetric, key);
+    } else if (s.strided_ragged && !(s.column && g.inner < 128) && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
+        // the same for segments of any length and alignment; very short segments (two shared groups
+        // and an idle slot among fewer than 33) are left to the column form where that one applies
+        RaggedClusterGeom cg = s.rcg;
+        cg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
+        hipLaunchKernelGGL(block_sync_clear_kernel, folded((cg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
+                           partial, cg.total_wgs);
+        hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
                            partial, cg, wl, symmetric, key);
     } else if (s.flat && !(vec && g.inner >= 64) && (!s.column || g.nblocks < 64 || s.fg.row < 2048)) {
         // short rows, unless long aligned segments stream well through the slice kernels: always when

@@ -1141,6 +1141,66 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
     }
 }
 
+// The meeting of the workgroups of one block, as in the kernel above: workgroup s publishes its
+// maximum m in slot s of the block's `slices` slots (zeroed before the launch) and gets the block's
+// maximum back.  The first wavefront polls, every lane up to slices / 64 slots, for at most wait_us;
+// when that runs out, every slot still unpublished is recomputed from memory with
+// slice_max(i), each thread's share of the maximum of slice i (safe for the reason given above).
+// Called by every thread of the workgroup.
+template <class SliceMax>
+__device__ __forceinline__ uint32_t meet_in_block(uint32_t* mine, uint32_t s, uint32_t slices, uint32_t m, uint32_t wait_us,
+                                                  uint32_t* lds, uint32_t& shared_word, SliceMax slice_max)
+{
+    // relaxed device-scope atomics on words only atomics touch; order by waiting for returned values
+    if (threadIdx.x == 0) {
+        uint32_t old = __hip_atomic_exchange(&mine[s], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
+    }
+    if (threadIdx.x < 64) {
+        const uint64_t start = __builtin_amdgcn_s_memrealtime();     // 100 MHz
+        const uint64_t budget = (uint64_t)wait_us * 100u;
+        bool all;
+        for (;;) {
+            bool ok = true;
+            for (uint32_t i = threadIdx.x; i < slices; i += 64u)
+                ok = ok && (__hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kPublished) != 0u;
+            all = __all(ok);
+            if (all || __builtin_amdgcn_s_memrealtime() - start >= budget) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (threadIdx.x == 0) shared_word = all ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool all_arrived = shared_word != 0u;
+
+    uint32_t bm = 0;
+    if (all_arrived) {
+        for (uint32_t i = threadIdx.x; i < slices; i += kThreads) {
+            const uint32_t a = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ~kPublished;
+            bm = bm > a ? bm : a;
+        }
+        return workgroup_max(bm, lds);
+    }
+    for (uint32_t i = 0; i < slices; ++i) {
+        __syncthreads();
+        if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        uint32_t a = shared_word;
+        if (!(a & kPublished)) {
+            // the owner of slice i has not published, so it has not written any output yet:
+            // read its input; if the slot is still unpublished afterwards, the read was clean
+            const uint32_t own = workgroup_max(slice_max(i), lds);
+            __syncthreads();
+            if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            a = (shared_word & kPublished) ? shared_word : own;
+        }
+        a &= ~kPublished;
+        bm = bm > a ? bm : a;
+    }
+    return bm;
+}
+
 // The same block-by-block single pass for blocks along an inner dimension (outer > 1) made of
 // aligned segments of at least 64 elements (inner % 4 == 0): per-channel blocks of an
 // [N, C, H, W] tensor.  Slice s of block b is elements [s * 16384, ...) of the block's own
@@ -1289,6 +1349,179 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
                 r = random_words(j, key, 0u);
             }
             __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + j);
+        }
+    }
+}
+
+// The same for segments of any length from 64 elements at any alignment (inner % 4 != 0, or arrays
+// that are only dword aligned): per-channel blocks of an [N, C, 27, 27] tensor.  The unit is still
+// a group of the ARRAY's numbering (elements 4j .. 4j + 3), so that one Philox block serves it;
+// a segment starting at element S is covered by groups S / 4 ... (S + inner - 1) / 4, of which the
+// first and the last may hold elements of a neighbouring block ("strangers": loaded, because one
+// dwordx4 load at a dword-aligned address is still the cheapest, then masked out of the maximum and
+// never stored).  Every segment is given G = (inner + 2) / 4 + 1 group slots, the most it can
+// cover; slot t of a block is slot u = t % G of segment o = t / G, unused when that segment covers
+// fewer groups.  The slots of a block are dealt out evenly to its slices, at most 4096 each.
+struct RaggedClusterGeom {
+    uint64_t n;
+    uint64_t nblocks;
+    uint32_t inner;          // at least 64
+    uint32_t seg_groups;     // G
+    uint32_t magic_groups;   // floor(2^32 / G) + 1
+    uint32_t block_groups;   // outer * G, at most kStridedMaxSlices * 4096
+    uint32_t slices;         // ceil(block_groups / 4096)
+    uint32_t slice_groups;   // ceil(block_groups / slices): the slots are dealt out evenly
+    uint32_t total_wgs;
+    uint32_t wait_us;
+};
+
+constexpr uint32_t kRaggedSliceGroups = kThreads * 16u;
+
+// Slot t of block b: the group j it stands for and which of its four elements belong to the block
+// (bit e of `mask`; 0 for an unused slot).
+__device__ __forceinline__ void ragged_slot(const RaggedClusterGeom& cg, uint32_t b, uint32_t t, uint64_t& j, uint32_t& mask)
+{
+    uint32_t o = __umulhi(t, cg.magic_groups);            // t / G or one more (t < 2^20)
+    uint32_t u = t - o * cg.seg_groups;
+    if ((int32_t)u < 0) {
+        o -= 1u;
+        u += cg.seg_groups;
+    }
+    const uint64_t start = ((uint64_t)o * cg.nblocks + b) * cg.inner;      // first element of the segment
+    const uint32_t r = (uint32_t)start & 3u;
+    j = (start >> 2) + u;
+    // the segment is elements [lo, hi) of the group's own numbering
+    const int32_t lo = (int32_t)r - 4 * (int32_t)u, hi = (int32_t)(cg.inner + r) - 4 * (int32_t)u;
+    const uint32_t below_hi = hi >= 4 ? 0xFu : hi <= 0 ? 0u : (1u << hi) - 1u;
+    const uint32_t from_lo = lo <= 0 ? 0xFu : (0xFu << lo) & 0xFu;
+    mask = below_hi & from_lo;
+}
+
+__device__ __forceinline__ uint32_t ragged_slice_slots(const RaggedClusterGeom& cg, uint32_t s)
+{
+    const uint32_t t0 = s * cg.slice_groups;
+    if (t0 >= cg.block_groups) return 0u;
+    return cg.block_groups - t0 < cg.slice_groups ? cg.block_groups - t0 : cg.slice_groups;
+}
+
+__device__ __forceinline__ uint4 keep_masked(const uint4& v, uint32_t mask)
+{
+    return make_uint4((mask & 1u) ? v.x : 0u, (mask & 2u) ? v.y : 0u, (mask & 4u) ? v.z : 0u, (mask & 8u) ? v.w : 0u);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const uint32_t* in, uint32_t* out, uint32_t* slots,
+                                                                           RaggedClusterGeom cg, int wl, int symmetric,
+                                                                           RngKey key)
+{
+    constexpr int GPT = 16;
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? 9 : 0;          // random words parked in LDS, as in the kernels above
+    __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
+    __shared__ uint32_t lds[kThreads / 64];
+    __shared__ uint32_t shared_word;
+    const uint32_t wg = (uint32_t)linear_block();
+    if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
+    const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
+    const uint32_t t0 = s * cg.slice_groups;
+    const uint32_t nslots = ragged_slice_slots(cg, s);
+    const bool short_tail = (cg.n & 3u) != 0u;                     // the array's last group is not whole
+
+    // Every load is one unconditional dwordx4 inside the array, so that all sixteen are in flight
+    // together: an unused slot reads the group before it, and the array's short last group reads
+    // the array's last four elements instead (put right below, `shift` elements further on).
+    uint4 v[GPT];
+    uint32_t shifts = 0u;
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (t < nslots) {
+            uint64_t j;
+            uint32_t mask;
+            ragged_slot(cg, b, t0 + t, j, mask);
+            uint64_t at = 4u * j;
+            if (mask == 0u) at -= 4u;
+            if (at + 4u > cg.n) {
+                shifts |= (uint32_t)(at + 4u - cg.n) << (2 * k);
+                at = cg.n - 4u;
+            }
+            v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4_at_dword*>(in + at)));
+            if (k < PRE) {
+                const Words4 r = random_words(j, key, 0u);
+                parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+            }
+        }
+    }
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        // (the slot is worked out again, here and below, rather than kept: sixteen group numbers and
+        // masks do not fit the registers next to sixteen groups; the empty asm keeps the compiler from
+        // finding out that it is the same computation)
+        uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        asm volatile("" : "+v"(t));
+        uint32_t mask = 0u;
+        if (t < nslots) {
+            uint64_t j;
+            ragged_slot(cg, b, t0 + t, j, mask);
+        }
+        if (short_tail) {
+            const uint32_t sh = (shifts >> (2 * k)) & 3u;          // element e of the group was loaded as word e + sh
+            if (sh == 1u) v[k] = make_uint4(v[k].y, v[k].z, v[k].w, 0u);
+            else if (sh == 2u) v[k] = make_uint4(v[k].z, v[k].w, 0u, 0u);
+            else if (sh == 3u) v[k] = make_uint4(v[k].w, 0u, 0u, 0u);
+        }
+        const uint32_t gm = max4_mag(keep_masked(v[k], mask));       // strangers stay in v[k]: quantized below, never stored
+        m = m > gm ? m : gm;
+    }
+    m = workgroup_max(m, lds);
+
+    uint32_t* mine = slots + (uint64_t)b * cg.slices;
+    const uint32_t bm = meet_in_block(mine, s, cg.slices, m, cg.wait_us, lds, shared_word, [&](uint32_t i) {
+        // slice i of this block from memory, element by element where a group is shared
+        uint32_t own = 0;
+        const uint32_t count = ragged_slice_slots(cg, i);
+        for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
+            uint64_t j;
+            uint32_t mask;
+            ragged_slot(cg, b, i * cg.slice_groups + t, j, mask);
+#pragma unroll
+            for (uint32_t e = 0; e < 4u; ++e) {
+                if (mask & (1u << e)) {
+                    const uint32_t a = in[4u * j + e] & 0x7fffffffu;
+                    own = own > a ? own : a;
+                }
+            }
+        }
+        return own;
+    });
+
+    const GridPlan p = block_plan(bm, wl, symmetric);
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        asm volatile("" : "+v"(t));
+        if (t < nslots) {
+            uint64_t j;
+            uint32_t mask;
+            ragged_slot(cg, b, t0 + t, j, mask);
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (k < PRE) {
+                const uint4 w = parked[k * kThreads + threadIdx.x];
+                r = Words4{{w.x, w.y, w.z, w.w}};
+            } else if (MODE == QSIM_STOCHASTIC) {
+                r = random_words(j, key, 0u);
+            }
+            const uint4 q = quantize_group_to_grid<MODE>(v[k], p, r);
+            uint32_t* dst = out + 4u * j;
+            if (mask == 0xFu) {
+                __builtin_nontemporal_store(to_u32x4(q), reinterpret_cast<u32x4_at_dword*>(dst));
+            } else {
+                if (mask & 1u) dst[0] = q.x;
+                if (mask & 2u) dst[1] = q.y;
+                if (mask & 4u) dst[2] = q.z;
+                if (mask & 8u) dst[3] = q.w;
+            }
         }
     }
 }

@@ -436,11 +436,13 @@ def test_block_short_blocks_along_an_inner_dimension(shape, rounding):
 
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
 @pytest.mark.parametrize("shape", [(4, 100003, 1), (46, 5743, 1), (71, 6029, 7), (22, 10601, 14), (631, 3035, 1), (9, 6, 20714),
-                                   (5, 3, 4098), (77, 1, 43577), (3, 4, 279622), (40, 72, 1165), (300, 5000, 3)])
+                                   (5, 3, 4098), (77, 1, 43577), (3, 4, 279622), (40, 72, 1165), (300, 5000, 3),
+                                   (2, 3, (1 << 21) + 1), (2, 2, (1 << 21) + 4)])
 def test_block_rows_that_are_not_whole_groups_along_an_inner_dimension(shape, rounding):
     """Blocks along an inner dimension when a row is not a multiple of four elements, or the blocks
-    are long and odd: the one-column-per-thread form and the general two-pass form; one block in
-    several outer pieces is the whole tensor."""
+    are long and odd: the one-column-per-thread form, the single pass over odd segments and, for
+    blocks of more than four million elements, the general two-pass form; one block in several
+    outer pieces is the whole tensor."""
     outer, nblocks, inner = shape
     g = np.random.Generator(np.random.PCG64(sum(shape)))
     scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
@@ -455,6 +457,49 @@ def test_block_rows_that_are_not_whole_groups_along_an_inner_dimension(shape, ro
         assert_bit_equal(host(Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 6, 1)), want, f"{shape} offset {off}")
     Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 6, 1, out=view)
     assert_bit_equal(host(view), want, f"{shape} in place")
+
+
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("shape", [(130, 5, 65), (125, 7, 64), (121, 3, 66), (124, 2, 67), (128, 6, 729), (7, 11, 4153), (2, 3, 70001),
+                                   (33, 64, 3025), (1000, 2, 4001), (130, 300, 65), (3, 2, 1048577), (9, 5, 3136), (3, 5, 65)])
+def test_block_per_channel_single_pass_with_odd_segments(shape, rounding):
+    """Blocks along an inner dimension made of segments of any length from 64 elements, at every
+    alignment of the arrays: the first and last group of a segment hold a neighbouring block's
+    elements, which must neither count for the maximum nor be written.  Neighbouring blocks differ
+    in scale by up to 2^24 and each block's maximum sits at the edge of one of its segments."""
+    outer, nblocks, inner = shape
+    g = np.random.Generator(np.random.PCG64(sum(shape)))
+    scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
+    x = (g.standard_normal(shape, dtype=np.float32) * scale[None, :, None]).astype(np.float32)
+    for b in range(min(nblocks, 64)):
+        x[g.integers(outer), b, (0, inner - 1)[b % 2]] = np.float32(37.0) * scale[b] * np.float32((-1) ** b)
+    want = R.block_quantize(x, outer, nblocks, inner, 8, rounding, 0, 6, 1).reshape(-1)
+    n = x.size
+    pad = dev(np.zeros(n + 8, np.float32))
+    for off in (0, 1, 2, 3):
+        view = pad[off:off + n]
+        view.copy_(torch.from_numpy(x.reshape(-1)))
+        out = torch.full((n + 8,), 7.0, device="cuda")
+        Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 6, 1, out=out[off:off + n])
+        assert_bit_equal(host(out[off:off + n]), want, f"{shape} offset {off}")
+        assert bool((out[:off] == 7.0).all()) and bool((out[off + n:] == 7.0).all()), f"{shape} offset {off}: wrote outside"
+    Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 6, 1, out=view)
+    assert_bit_equal(host(view), want, f"{shape} in place")
+
+
+def test_block_per_channel_single_pass_with_odd_segments_when_the_wait_runs_out():
+    Q.set_barrier_wait_us(0)
+    try:
+        for shape in [(128, 6, 729), (2, 3, 70001)]:
+            x = W.lognormal_gradients(shape, seed=11)
+            want = R.block_quantize(x, *shape, 8, STOCHASTIC, 0, 6, 1).reshape(-1)
+            pad = dev(np.concatenate([np.zeros(1, np.float32), x.reshape(-1)]))
+            d = pad[1:]
+            assert_bit_equal(host(Q.block_quantize(d, *shape, 8, STOCHASTIC, 0, 6, 1)), want, f"{shape} out of place")
+            Q.block_quantize(d, *shape, 8, STOCHASTIC, 0, 6, 1, out=d)
+            assert_bit_equal(host(d), want, f"{shape} in place")
+    finally:
+        Q.set_barrier_wait_us(2000)
 
 
 def test_block_per_channel_single_pass_when_the_wait_runs_out():
