@@ -1278,62 +1278,17 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     }
     m = workgroup_max(m, lds);
 
-    // relaxed device-scope atomics on words only atomics touch; order by waiting for returned values
     uint32_t* mine = slots + (uint64_t)b * cg.slices;
-    if (threadIdx.x == 0) {
-        uint32_t old = __hip_atomic_exchange(&mine[s], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
-    }
-    if (threadIdx.x < 64) {
-        const uint64_t start = __builtin_amdgcn_s_memrealtime();     // 100 MHz
-        const uint64_t budget = (uint64_t)cg.wait_us * 100u;
-        bool all;
-        for (;;) {
-            bool ok = true;
-            for (uint32_t i = threadIdx.x; i < cg.slices; i += 64u)
-                ok = ok && (__hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kPublished) != 0u;
-            all = __all(ok);
-            if (all || __builtin_amdgcn_s_memrealtime() - start >= budget) break;
-            __builtin_amdgcn_s_sleep(2);
+    const uint32_t bm = meet_in_block(mine, s, cg.slices, m, cg.wait_us, lds, shared_word, [&](uint32_t i) {
+        uint32_t own = 0;
+        const uint32_t count = strided_slice_groups(cg, i);
+        for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
+            const uint4 w = *(reinterpret_cast<const uint4*>(in) + strided_group(cg, b, i * kStridedSliceLen + 4u * t));
+            const uint32_t gm = max4_mag(w);
+            own = own > gm ? own : gm;
         }
-        if (threadIdx.x == 0) shared_word = all ? 1u : 0u;
-    }
-    __syncthreads();
-    const bool all_arrived = shared_word != 0u;
-
-    uint32_t bm = 0;
-    if (all_arrived) {
-        for (uint32_t i = threadIdx.x; i < cg.slices; i += kThreads) {
-            const uint32_t a = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ~kPublished;
-            bm = bm > a ? bm : a;
-        }
-        bm = workgroup_max(bm, lds);
-    } else {
-        for (uint32_t i = 0; i < cg.slices; ++i) {
-            __syncthreads();
-            if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            uint32_t a = shared_word;
-            if (!(a & kPublished)) {
-                // the owner of slice i has not published, so it has not written any output yet:
-                // read its input; if the slot is still unpublished afterwards, the read was clean
-                uint32_t own = 0;
-                const uint32_t count = strided_slice_groups(cg, i);
-                for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
-                    const uint4 w = *(reinterpret_cast<const uint4*>(in) + strided_group(cg, b, i * kStridedSliceLen + 4u * t));
-                    const uint32_t gm = max4_mag(w);
-                    own = own > gm ? own : gm;
-                }
-                own = workgroup_max(own, lds);
-                __syncthreads();
-                if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __syncthreads();
-                a = (shared_word & kPublished) ? shared_word : own;
-            }
-            a &= ~kPublished;
-            bm = bm > a ? bm : a;
-        }
-    }
+        return own;
+    });
 
     const GridPlan p = block_plan(bm, wl, symmetric);
 #pragma unroll
