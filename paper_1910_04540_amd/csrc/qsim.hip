@@ -431,6 +431,11 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
     }
     uint32_t* partial = reinterpret_cast<uint32_t*>(workspace);
     const dim3 grid = folded_xz(g.nblocks, s.sg.slices);
+    // Segments of at most 128 elements that do not start and end on 64-byte lines: a kernel that
+    // works block by block writes their first and last lines in two parts at different times, and
+    // the forms that walk the tensor front to back (flat, column) measured faster, two passes and all
+    // ([7048, 62, 76] 92 us -> 72 us, [8000, 32, 128] one element off 94 us -> 74 us).
+    const bool short_segments = g.inner <= 128 && (s.flat || s.column);
     if (vec && g.outer == 1) {
         // single pass when the blocks fit in the chip's registers, else the streaming two-pass form:
         // blocks on grid.y (folded when there are more than 65535), slices on grid.x
@@ -455,7 +460,8 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         const uint64_t wgs = (g.nblocks + s.spg.blocks_per_wg - 1) / s.spg.blocks_per_wg;
         hipLaunchKernelGGL((block_strided_packed_kernel<MODE>), folded(wgs), dim3(kThreads), 0, stream, pin, pout, s.spg, wl,
                            symmetric, key);
-    } else if (vec && s.strided_cluster && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
+    } else if (vec && s.strided_cluster && !(short_segments && g.inner % 16 != 0) &&
+               resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // single pass, block by block (see the kernel): the workgroups of a block must fit together
         StridedClusterGeom cg = s.scg;
         cg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
@@ -463,16 +469,15 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                            partial, cg.total_wgs);
         hipLaunchKernelGGL((block_cluster_strided_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
                            partial, cg, wl, symmetric, key);
-    } else if (s.strided_ragged && !(s.column && g.inner < 128) && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
-        // the same for segments of any length and alignment; very short segments (two shared groups
-        // and an idle slot among fewer than 33) are left to the column form where that one applies
+    } else if (s.strided_ragged && !short_segments && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
+        // the same for segments of any length and alignment
         RaggedClusterGeom cg = s.rcg;
         cg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
         hipLaunchKernelGGL(block_sync_clear_kernel, folded((cg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
                            partial, cg.total_wgs);
         hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
                            partial, cg, wl, symmetric, key);
-    } else if (s.flat && !(vec && g.inner >= 64) && (!s.column || g.nblocks < 64 || s.fg.row < 2048)) {
+    } else if (s.flat && !(vec && g.inner > 128) && (!s.column || g.nblocks < 64 || s.fg.row < 2048)) {
         // short rows, unless long aligned segments stream well through the slice kernels: always when
         // the column form cannot run; otherwise where that form is weak (few blocks make its fold
         // serial, short rows give it few threads per row)

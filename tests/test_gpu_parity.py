@@ -460,11 +460,11 @@ def test_block_rows_that_are_not_whole_groups_along_an_inner_dimension(shape, ro
 
 
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
-@pytest.mark.parametrize("shape", [(130, 5, 65), (125, 7, 64), (121, 3, 66), (124, 2, 67), (128, 6, 729), (7, 11, 4153), (2, 3, 70001),
+@pytest.mark.parametrize("shape", [(70, 5, 129), (70, 7, 132), (70, 3, 130), (70, 2, 131), (130, 5, 65), (128, 6, 729), (7, 11, 4153), (2, 3, 70001),
                                    (33, 64, 3025), (1000, 2, 4001), (130, 300, 65), (3, 2, 1048577), (9, 5, 3136), (3, 5, 65)])
 def test_block_per_channel_single_pass_with_odd_segments(shape, rounding):
-    """Blocks along an inner dimension made of segments of any length from 64 elements, at every
-    alignment of the arrays: the first and last group of a segment hold a neighbouring block's
+    """Blocks along an inner dimension made of segments of any length, at every alignment of the
+    arrays (single pass above 128 elements per segment, the flat or column form below): the first and last group of a segment hold a neighbouring block's
     elements, which must neither count for the maximum nor be written.  Neighbouring blocks differ
     in scale by up to 2^24 and each block's maximum sits at the edge of one of its segments."""
     outer, nblocks, inner = shape
