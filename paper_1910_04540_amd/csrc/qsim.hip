@@ -106,6 +106,7 @@ constexpr uint32_t kMaxSlices = 1024;
 constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
 constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
+constexpr uint64_t kPackedSmallTensor = 1ull << 23;   // elements; see block_schedule
 constexpr uint64_t kRaggedMinGroups = 2048;      // smallest block, in group slots, for the single pass over odd segments
 constexpr uint64_t kColumnThreads = 1ull << 19;  // threads the column form aims for
 constexpr uint64_t kColumnShortInner = 64;       // below: always; up to kColumnMaxInner: when there are enough blocks
@@ -174,8 +175,10 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         const size_t bytes = (size_t)(kSyncSlots0 + nblocks * cluster_slices) * sizeof(uint32_t);
         if (s.workspace < bytes) s.workspace = bytes;
     }
-    // (the runs a workgroup reads are 16 KiB / outer long: only for few outer indices)
-    if (outer > 1 && outer <= 16 && inner % 4 == 0 && s.sg.block_len <= 2048) {
+    // (the runs a workgroup reads are 16 KiB / outer long: only for few outer indices, or for a
+    // tensor small enough that one launch instead of three or four outweighs the scattered reads:
+    // [128, 512, 4, 4] per channel 14.4 us -> 8.9 us, [128, 4096, 16] 21.6 us -> 18.7 us)
+    if (outer > 1 && (outer <= 16 || n <= kPackedSmallTensor) && inner % 4 == 0 && s.sg.block_len <= 2048) {
         s.strided_packed = true;
         s.spg.nblocks = nblocks;
         s.spg.outer_inner = (uint32_t)s.sg.block_len;

@@ -22,6 +22,13 @@ times block floating point over some 200 seeded random views [outer, nblocks, in
 up to 32 Mi elements (sizes spread over orders of magnitude, half of the inner lengths rounded to
 multiples of four) and prints the slowest shapes and the quartiles: a search for shapes that no
 kernel form serves well.
+
+    python -m paper_1910_04540_amd.sweep --channel-shapes
+
+times block floating point with one block per channel (Sec. 3.1: a block over an arbitrary
+dimension) over activation tensors [N, C, H, W] of the shapes convolutional networks produce:
+the paper's VGG-16 on 32 x 32 images, and ImageNet-sized networks with spatial sizes that are
+(56 x 56, 28 x 28) and are not (55 x 55, 27 x 27, 35 x 35) multiples of four elements.
 """
 from __future__ import annotations
 
@@ -99,6 +106,45 @@ def block_shapes() -> int:
     return 0
 
 
+CHANNEL_SHAPES = [
+    # VGG-16 on CIFAR-10 images, batch 128 (Sec. 5)
+    (128, 64, 32, 32), (128, 128, 16, 16), (128, 256, 8, 8), (128, 512, 4, 4), (128, 512, 2, 2),
+    # ImageNet-sized feature maps, whole groups per row of the view
+    (128, 64, 112, 112), (128, 256, 56, 56), (128, 512, 28, 28), (128, 1024, 14, 14), (128, 2048, 7, 7),
+    # the same with odd spatial sizes
+    (128, 64, 55, 55), (128, 192, 27, 27), (128, 384, 13, 13), (64, 288, 35, 35), (64, 768, 17, 17), (32, 3, 299, 299),
+]
+
+
+def channel_shapes() -> int:
+    """Per-channel block quantize of [N, C, H, W] activations: the view [N, C, H * W], one block per C."""
+    print(f"{'N, C, H, W':>20} {'elements':>10} | {'nearest us':>10} {'% of 8 TB/s':>11} | {'stochastic us':>13} {'% of 8 TB/s':>11}")
+    for shape in CHANNEL_SHAPES:
+        batch, channels, height, width = shape
+        inner = height * width
+        n = batch * channels * inner
+        xs = [torch.randn(n, device="cuda") for _ in range(3)]
+        out = torch.empty(n, device="cuda")
+        ws = torch.empty(max(Q.block_workspace_bytes(n, batch, channels, inner), 16), dtype=torch.uint8, device="cuda")
+        cells = []
+        for mode in (Q.RN_EVEN, Q.STOCHASTIC):
+            turn = [0]
+
+            def call():
+                turn[0] += 1
+                Q.block_quantize(xs[turn[0] % 3], batch, channels, inner, 8, mode, 0, 1, 0, out=out, workspace=ws)
+
+            for _ in range(30):
+                call()
+            us = _time(call, 50)
+            cells.append((us, n * 8 / us / 1e3 / 80.0))
+        label = ", ".join(str(v) for v in shape)
+        print(f"{label:>20} {n:>10} | {cells[0][0]:10.1f} {cells[0][1]:11.1f} | {cells[1][0]:13.1f} {cells[1][1]:11.1f}", flush=True)
+        del xs, out, ws
+        torch.cuda.empty_cache()
+    return 0
+
+
 def shape_scan(seed: int) -> int:
     import numpy as np
 
@@ -146,6 +192,7 @@ def main() -> int:
     ap.add_argument("--max-log2", type=int, default=28)
     ap.add_argument("--json", action="store_true")
     ap.add_argument("--block-shapes", action="store_true")
+    ap.add_argument("--channel-shapes", action="store_true")
     ap.add_argument("--shape-scan", type=int, default=None, metavar="SEED")
     args = ap.parse_args()
     if not torch.cuda.is_available():
@@ -154,6 +201,8 @@ def main() -> int:
     Q.lib()
     if args.block_shapes:
         return block_shapes()
+    if args.channel_shapes:
+        return channel_shapes()
     if args.shape_scan is not None:
         return shape_scan(args.shape_scan)
     rows = []

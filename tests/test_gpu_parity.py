@@ -420,9 +420,11 @@ def test_block_per_channel_single_pass(shape, rounding):
 
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
 @pytest.mark.parametrize("shape", [(2, 300000, 64), (4, 1000, 4), (2, 5, 1024), (8, 50000, 128), (3, 100001, 100), (2, 1, 4),
-                                   (512, 20000, 4), (2, 1000003, 16), (32, 33, 64)])
+                                   (512, 20000, 4), (2, 1000003, 16), (32, 33, 64), (128, 512, 16), (128, 512, 4), (500, 101, 4),
+                                   (1000, 7, 8)])
 def test_block_short_blocks_along_an_inner_dimension(shape, rounding):
-    """Blocks of at most 2048 elements made of whole-group segments: several blocks per workgroup, single pass."""
+    """Blocks of at most 2048 elements made of whole-group segments: several blocks per workgroup,
+    single pass (few outer indices, or a tensor of at most 8 Mi elements)."""
     outer, nblocks, inner = shape
     g = np.random.Generator(np.random.PCG64(sum(shape)))
     scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
