@@ -521,18 +521,21 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
             hipLaunchKernelGGL(block_fold_rows_kernel, dim3((unsigned)((row_words + kThreads - 1) / kThreads), kColumnParts),
                                dim3(kThreads), 0, stream, partial, fewer, (uint32_t)row_words, cg.slices, kColumnParts);
         }
-        if ((uint64_t)rest.slices * rest.inner <= 64)
+        // blocks of one column: the few rows of column maxima that are left are folded by pass 2 itself
+        const uint32_t parts = cg.inner == 1 ? rest.slices : 0u;
+        const uint4* colparts = reinterpret_cast<const uint4*>(folded_from);
+        if (parts == 0u && (uint64_t)rest.slices * rest.inner <= 64)
             hipLaunchKernelGGL(block_column_fold_small_kernel, folded((cg.nblocks + kThreads - 1) / kThreads), dim3(kThreads), 0,
                                stream, folded_from, blockmax, rest);
-        else
+        else if (parts == 0u)
             hipLaunchKernelGGL(block_column_fold_kernel, folded((cg.nblocks + kThreads / 64 - 1) / (kThreads / 64)),
                                dim3(kThreads), 0, stream, folded_from, blockmax, rest);
         if (wide)
-            hipLaunchKernelGGL((block_column_apply_kernel<MODE, true>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax, cg,
-                               wl, symmetric, key);
+            hipLaunchKernelGGL((block_column_apply_kernel<MODE, true>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax,
+                               colparts, parts, cg, wl, symmetric, key);
         else
-            hipLaunchKernelGGL((block_column_apply_kernel<MODE, false>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax, cg,
-                               wl, symmetric, key);
+            hipLaunchKernelGGL((block_column_apply_kernel<MODE, false>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax,
+                               colparts, parts, cg, wl, symmetric, key);
     } else if (vec) {
         hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg.slices,

@@ -264,10 +264,14 @@ __global__ __launch_bounds__(kThreads) void block_column_fold_small_kernel(const
     blockmax[b] = m;
 }
 
+// `parts` > 0 (blocks of one column only): the block maxima are not folded yet; colparts holds
+// `parts` rows of column maxima and the thread folds the entries of its own four columns, which
+// saves the launch of a fold kernel.
 template <int MODE, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint32_t* in, uint32_t* out,
-                                                                      const uint32_t* blockmax, ColumnGeom cg, int wl,
-                                                                      int symmetric, RngKey key)
+                                                                      const uint32_t* blockmax, const uint4* colparts,
+                                                                      uint32_t parts, ColumnGeom cg, int wl, int symmetric,
+                                                                      RngKey key)
 {
     const uint32_t c = blockIdx.x * kThreads + threadIdx.x;
     if (c >= cg.row_groups) return;
@@ -275,7 +279,20 @@ __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint
     const uint64_t o1 = (o0 + cg.rows_per_slice < cg.outer) ? o0 + cg.rows_per_slice : cg.outer;
     const uint32_t have = cg.row - 4u * c;
     GridPlan p[4];
-    if (cg.inner % 4 == 0) {
+    if (parts > 0u) {
+        uint4 m = colparts[c];
+        for (uint32_t s = 1; s < parts; ++s) {
+            const uint4 a = colparts[(uint64_t)s * cg.row_groups + c];
+            m.x = m.x > a.x ? m.x : a.x;
+            m.y = m.y > a.y ? m.y : a.y;
+            m.z = m.z > a.z ? m.z : a.z;
+            m.w = m.w > a.w ? m.w : a.w;
+        }
+        p[0] = block_plan(m.x, wl, symmetric);
+        p[1] = block_plan(m.y, wl, symmetric);
+        p[2] = block_plan(m.z, wl, symmetric);
+        p[3] = block_plan(m.w, wl, symmetric);
+    } else if (cg.inner % 4 == 0) {
         p[0] = p[1] = p[2] = p[3] = block_plan(blockmax[(4u * c) / cg.inner], wl, symmetric);
     } else {
 #pragma unroll
