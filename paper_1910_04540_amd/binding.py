@@ -7,6 +7,7 @@ points raises.
 from __future__ import annotations
 
 import ctypes
+import functools
 import os
 
 import torch
@@ -178,7 +179,10 @@ def set_barrier_wait_us(microseconds: int) -> None:
     lib().qsim_set_barrier_wait_us(microseconds)
 
 
+@functools.lru_cache(maxsize=4096)
 def block_workspace_bytes(n, outer, nblocks, inner) -> int:
+    """qsim_block_workspace_bytes: a function of the shape alone, so the answers are remembered
+    (a training loop asks for the same few shapes every step)."""
     return int(lib().qsim_block_workspace_bytes(n, outer, nblocks, inner))
 
 
