@@ -266,10 +266,16 @@ def main() -> int:
             R.fixed_quantize(x_host, 8, 6, R.STOCHASTIC, R.SATURATE, seed=1234, stream_id=passes, threads=threads)
             passes += 1
             dt = time.perf_counter() - t0
+        # and one thread alone, on the first eighth of the tensor
+        part = x_host[: n // 8]
+        t0 = time.perf_counter()
+        R.fixed_quantize(part, 8, 6, R.STOCHASTIC, R.SATURATE, seed=1234, stream_id=0, threads=1)
+        one = part.size / (time.perf_counter() - t0)
         result["cpu_baseline"] = {"value": n * passes / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
                                   "sample": f"{passes} passes over the whole {n}-element tensor of the headline workload, "
                                             f"each split over {threads} threads ({dt:.2f} s wall, "
-                                            f"{dt * threads:.0f} s of CPU work)"}
+                                            f"{dt * threads:.0f} s of CPU work)",
+                                  "single_thread_value": one}
     print(json.dumps(result))
     return 0
 
