@@ -533,9 +533,16 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         if (wide)
             hipLaunchKernelGGL((block_column_apply_kernel<MODE, true>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax,
                                colparts, parts, cg, wl, symmetric, key);
-        else
+        else if (MODE != QSIM_STOCHASTIC)
             hipLaunchKernelGGL((block_column_apply_kernel<MODE, false>), cgrid, dim3(kThreads), 0, stream, pin, pout, blockmax,
                                colparts, parts, cg, wl, symmetric, key);
+        else {
+            // (63 runs per wavefront: see the kernel)
+            const uint32_t runs_per_wg = kColumnSharedRuns * (kThreads / 64);
+            const dim3 shared_grid((cg.row_groups + runs_per_wg - 1) / runs_per_wg, cg.slices);
+            hipLaunchKernelGGL((block_column_apply_kernel<MODE, false>), shared_grid, dim3(kThreads), 0, stream, pin, pout,
+                               blockmax, colparts, parts, cg, wl, symmetric, key);
+        }
     } else if (vec) {
         hipLaunchKernelGGL((block_partial_max_kernel<true>), grid, dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_apply_kernel<MODE, true>), grid, dim3(kThreads), 0, stream, pin, pout, partial, s.sg.slices,

@@ -267,22 +267,37 @@ __global__ __launch_bounds__(kThreads) void block_column_fold_small_kernel(const
 // `parts` > 0 (blocks of one column only): the block maxima are not folded yet; colparts holds
 // `parts` rows of column maxima and the thread folds the entries of its own four columns, which
 // saves the launch of a fold kernel.
+constexpr uint32_t kColumnSharedRuns = 63;     // runs per wavefront when neighbouring lanes share Philox blocks
+
 template <int MODE, bool ALIGNED>
 __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint32_t* in, uint32_t* out,
                                                                       const uint32_t* blockmax, const uint4* colparts,
                                                                       uint32_t parts, ColumnGeom cg, int wl, int symmetric,
                                                                       RngKey key)
 {
-    const uint32_t c = blockIdx.x * kThreads + threadIdx.x;
-    if (c >= cg.row_groups) return;
+    // Stochastic rounding of runs that are not group-aligned needs two Philox blocks per run, the
+    // second of which is the next run's first: there a wavefront takes 63 runs, its last lane draws
+    // the 64th block only, and every lane gets its second block from its neighbour (SHARE).
+    constexpr bool SHARE = MODE == QSIM_STOCHASTIC && !ALIGNED;
+    uint32_t c = blockIdx.x * kThreads + threadIdx.x;
+    bool live = true;
+    if (SHARE) {
+        const uint32_t lane = threadIdx.x & 63u;
+        c = (blockIdx.x * (kThreads / 64u) + (threadIdx.x >> 6)) * kColumnSharedRuns + lane;
+        if (c - lane >= cg.row_groups) return;                       // the whole wavefront leaves together
+        live = lane < kColumnSharedRuns && c < cg.row_groups;
+    } else if (c >= cg.row_groups) {
+        return;
+    }
     const uint64_t o0 = (uint64_t)blockIdx.y * cg.rows_per_slice;
     const uint64_t o1 = (o0 + cg.rows_per_slice < cg.outer) ? o0 + cg.rows_per_slice : cg.outer;
-    const uint32_t have = cg.row - 4u * c;
+    const uint32_t have = live ? cg.row - 4u * c : 0u;               // 0: no loads, no stores
+    const uint32_t cp = c < cg.row_groups ? c : cg.row_groups - 1u;  // (a lane without elements reads a valid plan)
     GridPlan p[4];
     if (parts > 0u) {
-        uint4 m = colparts[c];
+        uint4 m = colparts[cp];
         for (uint32_t s = 1; s < parts; ++s) {
-            const uint4 a = colparts[(uint64_t)s * cg.row_groups + c];
+            const uint4 a = colparts[(uint64_t)s * cg.row_groups + cp];
             m.x = m.x > a.x ? m.x : a.x;
             m.y = m.y > a.y ? m.y : a.y;
             m.z = m.z > a.z ? m.z : a.z;
@@ -293,11 +308,11 @@ __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint
         p[2] = block_plan(m.z, wl, symmetric);
         p[3] = block_plan(m.w, wl, symmetric);
     } else if (cg.inner % 4 == 0) {
-        p[0] = p[1] = p[2] = p[3] = block_plan(blockmax[(4u * c) / cg.inner], wl, symmetric);
+        p[0] = p[1] = p[2] = p[3] = block_plan(blockmax[(4u * cp) / cg.inner], wl, symmetric);
     } else {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const uint32_t col = 4u * c + (uint32_t)e < cg.row ? 4u * c + (uint32_t)e : cg.row - 1u;
+            const uint32_t col = 4u * cp + (uint32_t)e < cg.row ? 4u * cp + (uint32_t)e : cg.row - 1u;
             p[e] = block_plan(blockmax[col / cg.inner], wl, symmetric);
         }
     }
@@ -311,7 +326,7 @@ __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint
             if (o + k < o1) {
                 const uint64_t at = (o + k) * cg.row + 4ull * c;
                 Words4 r = {{0u, 0u, 0u, 0u}};
-                if (MODE == QSIM_STOCHASTIC) r = ALIGNED ? random_words(at >> 2, key, 0u) : random_words_at(at, key, 0u);
+                if (MODE == QSIM_STOCHASTIC) r = ALIGNED ? random_words(at >> 2, key, 0u) : random_words_at_shared(at, key, 0u);
                 uint4 q;
                 q.x = quantize_to_grid<MODE>(v[k].x, p[0], r.w[0]);
                 q.y = quantize_to_grid<MODE>(v[k].y, p[1], r.w[1]);

@@ -69,6 +69,27 @@ __device__ __forceinline__ Words4 random_words_at(uint64_t i0, const RngKey& key
     return r;
 }
 
+// The same when the lanes of a wavefront hold CONSECUTIVE runs (lane l + 1 starts four elements
+// after lane l, so i0 & 3 is the same in all of them): the second Philox block of a lane's run is the
+// first block of the next lane's, and is taken from there instead of being drawn again.  The last
+// lane has no such neighbour, so its result is only right for a group-aligned run: the caller gives
+// it no elements.  Every lane of the wavefront must make the call.
+__device__ __forceinline__ Words4 random_words_at_shared(uint64_t i0, const RngKey& key, uint32_t role)
+{
+    const uint32_t s = (uint32_t)i0 & 3u;                  // wave-uniform
+    const Words4 a = random_words(i0 >> 2, key, role);
+    if (s == 0u) return a;
+    Words4 b;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) b.w[i] = (uint32_t)__shfl_down((int)a.w[i], 1);
+    Words4 r;
+    r.w[0] = s == 1u ? a.w[1] : (s == 2u ? a.w[2] : a.w[3]);
+    r.w[1] = s == 1u ? a.w[2] : (s == 2u ? a.w[3] : b.w[0]);
+    r.w[2] = s == 1u ? a.w[3] : (s == 2u ? b.w[0] : b.w[1]);
+    r.w[3] = s == 1u ? b.w[0] : (s == 2u ? b.w[1] : b.w[2]);
+    return r;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Rounding a non-negative scaled value y = |x| / 2^q (y < 2^24, exact in fp32) to an integer
 // (Sec. 3.1 "Rounding mode").  fract/trunc/convert are exact on such y; the stochastic threshold
