@@ -178,6 +178,7 @@ struct ColumnGeom {
     uint32_t nblocks;
     uint32_t slices;           // row slices
     uint32_t rows_per_slice;
+    uint32_t stream_first;     // pass 1 reads with non-temporal loads: the tensor is too large for pass 2 to find it cached
 };
 
 // A thread's run of four columns in row o starts at element o * row + 4 * c: a group boundary when
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(kThreads) void block_column_max_kernel(const uint32
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             v[k] = make_uint4(0u, 0u, 0u, 0u);
-            if (o + k < o1) v[k] = column_load<ALIGNED>(in, (o + k) * cg.row + 4ull * c, have, false);   // cached: read again in pass 2
+                        if (o + k < o1) v[k] = column_load<ALIGNED>(in, (o + k) * cg.row + 4ull * c, have, cg.stream_first != 0u);
         }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -366,6 +367,7 @@ struct FlatGeom {
     uint32_t magic_row, magic_inner;   // floor(2^32 / d) + 1 (unused when d == 1)
     uint32_t wgs;
     uint32_t copies;             // copies of the LDS table in pass 1: a power of two, 1..64, copies * nblocks <= 4096
+    uint32_t stream_first;       // pass 1 reads with non-temporal loads (see ColumnGeom)
 };
 
 __device__ __forceinline__ uint32_t flat_block(const FlatGeom& fg, uint32_t pos /* < 2^16 */)
@@ -376,13 +378,14 @@ __device__ __forceinline__ uint32_t flat_block(const FlatGeom& fg, uint32_t pos 
 
 // The groups of one step.  A step that lies wholly inside the array (all but the last) issues its
 // loads back to back with nothing in between, so that all of them are in flight together.
+template <bool STREAM>
 __device__ __forceinline__ void flat_load_step(const uint32_t* in, uint64_t base, const FlatGeom& fg, uint4 (&v)[kFlatGpt])
 {
     if ((base + kFlatStepGroups) * 4 <= fg.n) {                              // wave-uniform
         const u32x4_at_dword* p = reinterpret_cast<const u32x4_at_dword*>(in + base * 4) + threadIdx.x;
 #pragma unroll
         for (int k = 0; k < kFlatGpt; ++k) {
-            const u32x4 w = __builtin_nontemporal_load(p + k * kThreads);
+            const u32x4 w = STREAM ? __builtin_nontemporal_load(p + k * kThreads) : p[k * kThreads];
             v[k] = to_uint4(w);
         }
     } else {
@@ -411,7 +414,8 @@ __global__ __launch_bounds__(kThreads) void block_flat_max_kernel(const uint32_t
     for (uint64_t base = (uint64_t)blockIdx.x * kFlatStepGroups; base < g1; base += (uint64_t)fg.wgs * kFlatStepGroups) {
         const uint32_t pos0 = (uint32_t)((base * 4) % fg.row);            // wave-uniform
         uint4 v[kFlatGpt];
-        flat_load_step(in, base, fg, v);
+        if (fg.stream_first) flat_load_step<true>(in, base, fg, v);               // wave-uniform
+        else flat_load_step<false>(in, base, fg, v);
 #pragma unroll
         for (int k = 0; k < kFlatGpt; ++k) {
             const uint64_t j = base + threadIdx.x + (uint64_t)k * kThreads;
@@ -483,7 +487,7 @@ __global__ __launch_bounds__(kThreads) void block_flat_apply_kernel(const uint32
     for (uint64_t base = (uint64_t)blockIdx.x * kFlatStepGroups; base < g1; base += (uint64_t)fg.wgs * kFlatStepGroups) {
         const uint32_t pos0 = (uint32_t)((base * 4) % fg.row);            // wave-uniform
         uint4 v[kFlatGpt];
-        flat_load_step(in, base, fg, v);
+        flat_load_step<true>(in, base, fg, v);
 #pragma unroll
         for (int k = 0; k < kFlatGpt; ++k) {
             const uint64_t j = base + threadIdx.x + (uint64_t)k * kThreads;
