@@ -209,7 +209,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
             if (s.workspace < bytes) s.workspace = bytes;
         }
     }
-    if (outer > 1 && inner >= 64 && inner <= (1ull << 22)) {
+    if (inner >= 64 && inner <= (1ull << 22)) {          // (contiguous blocks too: one segment each)
         const uint64_t seg_groups = (inner + 2) / 4 + 1;
         const unsigned __int128 block_groups = (unsigned __int128)outer * seg_groups;
         // (a block has workgroups of its own, four of which fit a CU: with fewer than eight loads per
@@ -403,6 +403,18 @@ static void launch_block_ragged(const uint32_t* in, uint32_t* out, const BlockGe
 }
 
 template <int MODE>
+static void launch_block_cluster_ragged(const uint32_t* in, uint32_t* out, const RaggedClusterGeom& geom, int wl, int symmetric,
+                                        const RngKey& key, uint32_t* slots, hipStream_t stream)
+{
+    RaggedClusterGeom cg = geom;
+    cg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
+    hipLaunchKernelGGL(block_sync_clear_kernel, folded((cg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, slots,
+                       cg.total_wgs);
+    hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, in, out, slots, cg,
+                       wl, symmetric, key);
+}
+
+template <int MODE>
 static int launch_block_mode(const float* in, float* out, const BlockSchedule& s, int wl, int symmetric,
                              const RngKey& key, void* workspace, hipStream_t stream)
 {
@@ -466,6 +478,10 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
                            partial, s.sg.slices, s.sg, wl, symmetric, key);
+    } else if (g.outer == 1 && s.strided_ragged && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
+        // contiguous blocks of up to 4 Mi elements whose length is not a multiple of four, or in
+        // arrays that are only dword aligned: single pass, block by block, over the array's own groups
+        launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, partial, stream);
     } else if (vec && s.strided_packed) {
         const uint64_t wgs = (g.nblocks + s.spg.blocks_per_wg - 1) / s.spg.blocks_per_wg;
         hipLaunchKernelGGL((block_strided_packed_kernel<MODE>), folded(wgs), dim3(kThreads), 0, stream, pin, pout, s.spg, wl,
@@ -481,12 +497,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                            partial, cg, wl, symmetric, key);
     } else if (s.strided_ragged && !short_segments && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // the same for segments of any length and alignment
-        RaggedClusterGeom cg = s.rcg;
-        cg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
-        hipLaunchKernelGGL(block_sync_clear_kernel, folded((cg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
-                           partial, cg.total_wgs);
-        hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
-                           partial, cg, wl, symmetric, key);
+        launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, partial, stream);
     } else if (s.flat && !(vec && g.inner > 128) && (!s.column || g.nblocks < 64 || s.fg.row < 2048)) {
         // short rows, unless long aligned segments stream well through the slice kernels: always when
         // the column form cannot run; otherwise where that form is weak (few blocks make its fold

@@ -374,7 +374,8 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
 }
 
 // The same for segments of any length from 64 elements at any alignment (inner % 4 != 0, or arrays
-// that are only dword aligned): per-channel blocks of an [N, C, 27, 27] tensor.  The unit is still
+// that are only dword aligned): per-channel blocks of an [N, C, 27, 27] tensor, and long contiguous
+// blocks (outer == 1, one segment each) of odd length.  The unit is still
 // a group of the ARRAY's numbering (elements 4j .. 4j + 3), so that one Philox block serves it;
 // a segment starting at element S is covered by groups S / 4 ... (S + inner - 1) / 4, of which the
 // first and the last may hold elements of a neighbouring block ("strangers": loaded, because one
@@ -401,17 +402,22 @@ constexpr uint32_t kRaggedSliceGroups = kThreads * 16u;
 // (bit e of `mask`; 0 for an unused slot).
 __device__ __forceinline__ void ragged_slot(const RaggedClusterGeom& cg, uint32_t b, uint32_t t, uint64_t& j, uint32_t& mask)
 {
-    uint32_t o = __umulhi(t, cg.magic_groups);            // t / G or one more (t < 2^20)
-    uint32_t u = t - o * cg.seg_groups;
-    if ((int32_t)u < 0) {
-        o -= 1u;
-        u += cg.seg_groups;
+    uint32_t o = 0u, u = t;
+    if (cg.block_groups != cg.seg_groups) {               // (uniform; a contiguous block is one segment)
+        o = __umulhi(t, cg.magic_groups);                 // t / G or one more (t < 2^20)
+        u = t - o * cg.seg_groups;
+        if ((int32_t)u < 0) {
+            o -= 1u;
+            u += cg.seg_groups;
+        }
     }
     const uint64_t start = ((uint64_t)o * cg.nblocks + b) * cg.inner;      // first element of the segment
     const uint32_t r = (uint32_t)start & 3u;
     j = (start >> 2) + u;
+    // (the last of contiguous blocks may be short)
+    const uint32_t len = start + cg.inner > cg.n ? (uint32_t)(cg.n - start) : cg.inner;
     // the segment is elements [lo, hi) of the group's own numbering
-    const int32_t lo = (int32_t)r - 4 * (int32_t)u, hi = (int32_t)(cg.inner + r) - 4 * (int32_t)u;
+    const int32_t lo = (int32_t)r - 4 * (int32_t)u, hi = (int32_t)(len + r) - 4 * (int32_t)u;
     const uint32_t below_hi = hi >= 4 ? 0xFu : hi <= 0 ? 0u : (1u << hi) - 1u;
     const uint32_t from_lo = lo <= 0 ? 0xFu : (0xFu << lo) & 0xFu;
     mask = below_hi & from_lo;
@@ -451,6 +457,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     // the array's last four elements instead (put right below, `shift` elements further on).
     uint4 v[GPT];
     uint32_t shifts = 0u;
+    uint32_t masks[2] = {0u, 0u};                                  // four bits per group
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
@@ -459,10 +466,11 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
             uint64_t j;
             uint32_t mask;
             ragged_slot(cg, b, t0 + t, j, mask);
+            masks[k / 8] |= mask << (4 * (k % 8));
             uint64_t at = 4u * j;
             if (mask == 0u) at -= 4u;
             if (at + 4u > cg.n) {
-                shifts |= (uint32_t)(at + 4u - cg.n) << (2 * k);
+                if (mask != 0u) shifts |= (uint32_t)(at + 4u - cg.n) << (2 * k);      // 1..3
                 at = cg.n - 4u;
             }
             v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4_at_dword*>(in + at)));
@@ -475,16 +483,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     uint32_t m = 0;
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        // (the slot is worked out again, here and below, rather than kept: sixteen group numbers and
-        // masks do not fit the registers next to sixteen groups; the empty asm keeps the compiler from
-        // finding out that it is the same computation)
-        uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
-        asm volatile("" : "+v"(t));
-        uint32_t mask = 0u;
-        if (t < nslots) {
-            uint64_t j;
-            ragged_slot(cg, b, t0 + t, j, mask);
-        }
+        const uint32_t mask = (masks[k / 8] >> (4 * (k % 8))) & 0xFu;
         if (short_tail) {
             const uint32_t sh = (shifts >> (2 * k)) & 3u;          // element e of the group was loaded as word e + sh
             if (sh == 1u) v[k] = make_uint4(v[k].y, v[k].z, v[k].w, 0u);
@@ -519,12 +518,16 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     const GridPlan p = block_plan(bm, wl, symmetric);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
+        // (the group number is worked out again rather than kept: sixteen of them do not fit the
+        // registers next to sixteen groups; the empty asm keeps the compiler from finding out that it
+        // is the same computation)
         uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
         asm volatile("" : "+v"(t));
         if (t < nslots) {
             uint64_t j;
-            uint32_t mask;
-            ragged_slot(cg, b, t0 + t, j, mask);
+            uint32_t unused;
+            ragged_slot(cg, b, t0 + t, j, unused);
+            const uint32_t mask = (masks[k / 8] >> (4 * (k % 8))) & 0xFu;
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) {
                 const uint4 w = parked[k * kThreads + threadIdx.x];

@@ -274,6 +274,29 @@ def test_block_lengths_that_are_not_whole_groups(rows, cols, short, rounding):
 
 
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("rows,cols,short", [(5, 70001, 0), (40, 29799, 0), (7, 29799, 29000), (3, 1342177, 5), (2, 4000003, 1),
+                                             (9, 16386, 16385), (3, 65536, 0), (1, 2000001, 0)])
+def test_block_long_rows_of_odd_length(rows, cols, short, rounding):
+    """Contiguous blocks longer than one workgroup holds whose length is not a multiple of four, or
+    that start at a misaligned address: single pass block by block over the tensor's own groups of
+    four (up to 4 Mi elements per block, two passes beyond); a short last block; in place."""
+    n = rows * cols - short
+    x = W.row_scaled_matrix(rows, cols, seed=rows + cols).reshape(-1)[:n].copy()
+    x[cols - 1] = np.float32(3.0e30)                   # the first block's maximum in its very last element
+    want = R.block_quantize(x, 1, rows, cols, 8, rounding, 0, 21, 5)
+    pad = dev(np.zeros(n + 8, np.float32))
+    for off in (0, 1, 2, 3):
+        view = pad[off:off + n]
+        view.copy_(torch.from_numpy(x))
+        out = torch.full((n + 8,), 7.0, device="cuda")
+        Q.block_quantize(view, 1, rows, cols, 8, rounding, 0, 21, 5, out=out[off:off + n])
+        assert_bit_equal(host(out[off:off + n]), want, f"{rows} blocks of {cols} less {short}, offset {off}")
+        assert bool((out[:off] == 7.0).all()) and bool((out[off + n:] == 7.0).all()), f"offset {off}: wrote outside"
+    Q.block_quantize(view, 1, rows, cols, 8, rounding, 0, 21, 5, out=view)
+    assert_bit_equal(host(view), want, "in place")
+
+
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
 @pytest.mark.parametrize("rows,cols,short", [(600, 20000, 0), (1100, 16388, 100), (270, 65536, 0), (530, 32772, 5000)])
 def test_block_many_long_rows(rows, cols, short, rounding):
     """More rows of 16 Ki to 64 Ki elements than the chip holds at once: one 1024-thread workgroup per row."""
