@@ -75,8 +75,8 @@ def _time(fn, reps):
     return a.elapsed_time(b) * 1e3 / reps
 
 
-BLOCK_ROW_LENGTHS = [1, 3, 4, 10, 16, 27, 64, 100, 256, 1000, 1001, 1024, 4096, 4098, 16384, 16388, 25088, 65536,
-                     1 << 20, 1 << 24, 1 << 26]
+BLOCK_ROW_LENGTHS = [1, 3, 4, 10, 16, 27, 64, 100, 256, 1000, 1001, 1024, 4096, 4098, 16384, 16388, 25088, 29799, 65536,
+                     1000003, 1 << 20, 1 << 24, 1 << 26]
 
 
 def block_shapes() -> int:
