@@ -103,7 +103,7 @@ def test_graph_replays_every_block_form():
     if not torch.cuda.is_available():
         pytest.fail("needs a GPU")
     shapes = [(32, 64, 3136), (2, 3000, 64), (5000, 3, 300), (300, 4096, 1), (9, 6, 20714), (1, 300, 70000), (1, 700, 1001),
-              (1, 1, 3 * (1 << 20) + 1), (2, 2, (1 << 21) + 1)]
+              (1, 1, 3 * (1 << 20) + 1), (2, 2, (1 << 21) + 1), (1, 40, 29799)]
     xs = [torch.empty(o * b * i, device="cuda") for o, b, i in shapes]
     outs = [torch.empty_like(x) for x in xs]
     wss = [torch.empty(max(Q.block_workspace_bytes(x.numel(), *s), 16), dtype=torch.uint8, device="cuda") for x, s in zip(xs, shapes)]
