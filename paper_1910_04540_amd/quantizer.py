@@ -8,6 +8,7 @@ carry the arguments of the corresponding entry point.
 """
 from __future__ import annotations
 
+import itertools
 import math
 from dataclasses import dataclass
 from typing import Optional, Union
@@ -116,16 +117,20 @@ class Quantizer(torch.nn.Module):
 
     Stochastic rounding draws from Philox streams ``2 * call`` (forward) and ``2 * call + 1``
     (backward) of ``seed``, where ``call`` counts this module's forward calls: a run is
-    reproducible from the seed, and no two calls share random words.
+    reproducible from the seed, and no two calls share random words.  Two modules with the same
+    seed would round with the same words, so without a seed every module takes the next of a
+    process-wide sequence (reproducible as long as the modules are created in the same order).
     """
+
+    _next_seed = itertools.count(1 << 32)
 
     def __init__(self, forward_number: Number = None, backward_number: Number = None,
                  forward_rounding: Union[str, int] = "nearest", backward_rounding: Union[str, int] = "nearest",
-                 seed: int = 0):
+                 seed: Optional[int] = None):
         super().__init__()
         self.forward_number, self.backward_number = forward_number, backward_number
         self.forward_rounding, self.backward_rounding = _rounding(forward_rounding), _rounding(backward_rounding)
-        self.seed = int(seed)
+        self.seed = int(seed) if seed is not None else next(Quantizer._next_seed)
         self.calls = 0
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:

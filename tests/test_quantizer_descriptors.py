@@ -43,3 +43,9 @@ def test_formats_of_the_sgd_step():
         sgd_format(Z.BlockFloatingPoint(8, dim=0))
     with pytest.raises(TypeError):
         sgd_format("fp16")
+
+
+def test_modules_without_a_seed_do_not_share_random_words():
+    a, b = Z.Quantizer(Z.FixedPoint(8, 6)), Z.Quantizer(Z.FixedPoint(8, 6))
+    assert a.seed != b.seed and a.seed >= 1 << 32 and b.seed >= 1 << 32
+    assert Z.Quantizer(Z.FixedPoint(8, 6), seed=7).seed == 7
