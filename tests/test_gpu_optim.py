@@ -118,3 +118,28 @@ def test_parameter_groups_with_their_own_hyper_parameters():
             assert_bit_equal(host(opt.quantized[t]), wq, f"step {step}, quantized copy of parameter {i}")
     with pytest.raises(ValueError):
         QuantSGD([{"params": params, "learning_rate": 0.1}], lr=0.1)
+
+
+def test_a_small_network_trains_through_the_quantizers():
+    """Activations and errors through Quantizer modules, the update through QuantSGD (Sec. 3.1
+    "Front-end interface"): a two-layer network on a fixed synthetic regression task must fit it.
+    Not a parity test (those are above): a check that the pieces work together under autograd."""
+    from paper_1910_04540_amd.quantizer import Quantizer
+
+    g = torch.Generator(device="cpu").manual_seed(0)
+    x = torch.randn(512, 32, generator=g).cuda()
+    y = torch.tanh(x @ torch.randn(32, 10, generator=g).cuda())
+    act = lambda: Quantizer(BlockFloatingPoint(8, dim=0), FloatingPoint(5, 2), "nearest", "stochastic")
+    torch.manual_seed(0)
+    model = torch.nn.Sequential(torch.nn.Linear(32, 64), torch.nn.ReLU(), act(), torch.nn.Linear(64, 10), act()).cuda()
+    opt = QuantSGD(model.parameters(), lr=0.05, momentum=0.9, grad_number=FloatingPoint(5, 10), momentum_number=FixedPoint(16, 12),
+                   weight_number=BlockFloatingPoint(8), chunk=256, weights="master", seed=1)
+    losses = []
+    for _ in range(60):
+        opt.zero_grad()
+        loss = torch.nn.functional.mse_loss(model(x), y)
+        loss.backward()
+        opt.step()
+        losses.append(float(loss.detach()))
+    assert all(np.isfinite(losses)), losses
+    assert losses[-1] < 0.5 * losses[0], (losses[0], losses[-1])
