@@ -276,6 +276,29 @@ def main() -> int:
                                             f"each split over {threads} threads ({dt:.2f} s wall, "
                                             f"{dt * threads:.0f} s of CPU work)",
                                   "single_thread_value": one}
+        if not args.no_formats:
+            # the oracle on samples of the other workloads (elements/s; block and SGD entries run on one thread)
+            def rate(fn, count):
+                t0 = time.perf_counter()
+                fn()
+                return count / (time.perf_counter() - t0)
+
+            acts = W.relu_activations((8, 256, 56, 56)).reshape(-1)
+            grads = W.lognormal_gradients((8, 256, 56, 56)).reshape(-1)
+            mat = W.row_scaled_matrix(512, 4096)
+            w, g, m = W.sgd_state(1 << 21)
+            fg, fm, fw = R.Format(1, 5, 2, 3, 3), R.Format(2, 16, 12, 3, 1), R.Format(3, 8, 256, 0, 0)
+            result["cpu_baseline"]["other_formats"] = {
+                "float_e8m7_stochastic_activations": rate(lambda: R.float_quantize(
+                    acts, 8, 7, R.STOCHASTIC, R.SATURATE | R.SUBNORMAL, seed=1234, threads=threads), acts.size),
+                "float_e5m10_nearest_even_gradients": rate(lambda: R.float_quantize(
+                    grads, 5, 10, R.RN_EVEN, R.SATURATE | R.SUBNORMAL, threads=threads), grads.size),
+                "block8_per_row_stochastic_one_thread": rate(lambda: R.block_quantize(
+                    mat, 1, mat.shape[0], mat.shape[1], 8, R.STOCHASTIC, 0, 1234, 0), mat.size),
+                "block8_whole_tensor_nearest_even_one_thread": rate(lambda: R.block_quantize(
+                    mat, 1, 1, mat.size, 8, R.RN_EVEN), mat.size),
+                "quant_sgd_step_one_thread": rate(lambda: R.quant_sgd_step(w, g, m, 0.1, 0.9, fg, fm, fw, 1234, 2), w.size),
+            }
     print(json.dumps(result))
     return 0
 
