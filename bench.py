@@ -185,6 +185,16 @@ def main() -> int:
                 extra={"note": "blocks along dimension 1; single pass, the workgroups of a channel meet among themselves"})
         del a_in, a_out, cws
         torch.cuda.empty_cache()
+        # the same per channel where the feature map is not a whole number of groups: [128, 64, 55, 55]
+        on, oc, ohw = 128, 64, 55 * 55
+        o_in, o_out = _rotating(W.relu_activations((on, oc, 55, 55)).reshape(-1), torch)
+        ows = torch.empty(max(Q.block_workspace_bytes(on * oc * ohw, on, oc, ohw), 16), dtype=torch.uint8, device="cuda")
+        for mode, tag in ((Q.RN_EVEN, "nearest_even"), (Q.STOCHASTIC, "stochastic")):
+            run(f"block8_per_channel_128x64x55x55_{tag}", lambda k, mode=mode: Q.block_quantize(
+                o_in[k % NSETS], on, oc, ohw, 8, mode, 0, 1234, k, out=o_out[k % NSETS], workspace=ows), on * oc * ohw,
+                extra={"note": "segments of 3025 elements: single pass over the tensor's own groups of four, shared edge groups masked"})
+        del o_in, o_out, ows
+        torch.cuda.empty_cache()
 
         m_host = W.row_scaled_matrix()
         rows, cols = m_host.shape
