@@ -161,6 +161,25 @@ def fixed_quantize(x, wl, fl, rounding=RN_EVEN, flags=SATURATE, seed=0, stream_i
                      stream_id)
 
 
+def _at(fn_at, x, index0, *args) -> np.ndarray:
+    """One call of an `_at` entry: the array holds elements index0 .. of a larger tensor."""
+    flat = _f32(x).reshape(-1)
+    out = np.empty_like(flat)
+    _check(fn_at(_ptr(flat), _ptr(out), flat.size, index0, *args))
+    return out.reshape(np.shape(x))
+
+
+def float_quantize_at(x, index0, exp_bits, man_bits, rounding=RN_EVEN, flags=SATURATE, seed=0,
+                      stream_id=0) -> np.ndarray:
+    return _at(lib().qsim_ref_float_quantize_at, x, index0, exp_bits, man_bits, rounding, flags, seed,
+               stream_id)
+
+
+def fixed_quantize_at(x, index0, wl, fl, rounding=RN_EVEN, flags=SATURATE, seed=0,
+                      stream_id=0) -> np.ndarray:
+    return _at(lib().qsim_ref_fixed_quantize_at, x, index0, wl, fl, rounding, flags, seed, stream_id)
+
+
 def block_quantize(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed=0,
                    stream_id=0) -> np.ndarray:
     flat = _f32(x).reshape(-1)

@@ -188,3 +188,28 @@ def test_threads_do_not_change_the_result():
     a = R.fixed_quantize(x, 8, 6, STOCHASTIC, SATURATE, seed=1234)
     b = R.fixed_quantize(x, 8, 6, STOCHASTIC, SATURATE, seed=1234, threads=7)
     assert_bit_equal(a, b, "thread split")
+
+
+@pytest.mark.parametrize("index0", [0, 4, 7, (1 << 32) - 4, (1 << 32) - 1, 1 << 34])
+def test_array_form_takes_the_word_of_the_elements_index(index0):
+    """Sec. 3.1 "Rounding mode", stochastic: element i of an array that starts at element index0 of a
+    tensor is rounded with random_word(seed, stream_id, role 0, index0 + i) — the scalar quantizer
+    and the word generator are pinned on their own; this pins how the array form wires them."""
+    seed, stream = 0xFEDCBA9876543210, 0x9E3779B9
+    x = W.uniform_with_outliers(301, seed=31)
+    got = R.fixed_quantize_at(x, index0, 8, 6, STOCHASTIC, SATURATE, seed=seed, stream_id=stream)
+    want = np.array([R.fixed_scalar(x[i], 8, 6, STOCHASTIC, SATURATE, R.random_word(seed, stream, 0, index0 + i))
+                     for i in range(x.size)], dtype=np.float32)
+    assert_bit_equal(got, want, f"array form at index0 = {index0}")
+    # the choice of word matters on this input: another role, stream, seed half or offset changes results
+    for other in (R.random_words(seed, stream, 1, x.size, index0), R.random_words(seed, stream + 1, 0, x.size, index0),
+                  R.random_words(seed >> 32, stream, 0, x.size, index0), R.random_words(seed, stream, 0, x.size, index0 + 1),
+                  R.random_words(seed, stream, 0, x.size, 0 if index0 else 4)):
+        alt = np.array([R.fixed_scalar(x[i], 8, 6, STOCHASTIC, SATURATE, int(other[i])) for i in range(x.size)],
+                       dtype=np.float32)
+        assert np.any(alt.view(np.uint32) != want.view(np.uint32))
+    # the plain form is the array form at index0 = 0, split over threads or not
+    if index0 == 0:
+        assert_bit_equal(R.fixed_quantize(x, 8, 6, STOCHASTIC, SATURATE, seed=seed, stream_id=stream), want, "plain form")
+        assert_bit_equal(R.fixed_quantize(x, 8, 6, STOCHASTIC, SATURATE, seed=seed, stream_id=stream, threads=5), want,
+                         "plain form over threads")

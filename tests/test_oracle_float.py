@@ -186,3 +186,28 @@ def test_nonfinite_and_validation():
     with pytest.raises(R.OracleError) as err:
         R.float_quantize(x, 5, 2, rounding=-1)
     assert err.value.status == 3
+
+
+@pytest.mark.parametrize("index0", [0, 4, 7, (1 << 32) - 4, (1 << 32) - 1, 1 << 34])
+@pytest.mark.parametrize("e,m,flags", [(5, 2, SATURATE | SUBNORMAL), (8, 7, 0)])
+def test_array_form_takes_the_word_of_the_elements_index(index0, e, m, flags):
+    """Sec. 3.1 "Rounding mode", stochastic: element i of an array that starts at element index0 of a
+    tensor is rounded with random_word(seed, stream_id, role 0, index0 + i); pins how the array form
+    wires the (separately pinned) scalar quantizer and word generator together."""
+    seed, stream = 0xFEDCBA9876543210, 0x9E3779B9
+    x = W.mixed_scales(301, seed=32)
+    x = x[np.isfinite(x)]
+    got = R.float_quantize_at(x, index0, e, m, STOCHASTIC, flags, seed=seed, stream_id=stream)
+    want = np.array([R.float_scalar(x[i], e, m, STOCHASTIC, flags, R.random_word(seed, stream, 0, index0 + i))
+                     for i in range(x.size)], dtype=np.float32)
+    assert_bit_equal(got, want, f"array form at index0 = {index0}")
+    for other in (R.random_words(seed, stream, 1, x.size, index0), R.random_words(seed, stream + 1, 0, x.size, index0),
+                  R.random_words(seed >> 32, stream, 0, x.size, index0), R.random_words(seed, stream, 0, x.size, index0 + 1),
+                  R.random_words(seed, stream, 0, x.size, 0 if index0 else 4)):
+        alt = np.array([R.float_scalar(x[i], e, m, STOCHASTIC, flags, int(other[i])) for i in range(x.size)],
+                       dtype=np.float32)
+        assert np.any(alt.view(np.uint32) != want.view(np.uint32))
+    if index0 == 0:
+        assert_bit_equal(R.float_quantize(x, e, m, STOCHASTIC, flags, seed=seed, stream_id=stream), want, "plain form")
+        assert_bit_equal(R.float_quantize(x, e, m, STOCHASTIC, flags, seed=seed, stream_id=stream, threads=5), want,
+                         "plain form over threads")
