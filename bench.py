@@ -9,6 +9,10 @@ the launch stream, the same figures for the other formats (`formats`), and the C
 the host cores as a reported baseline.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-formats] [--no-cpu]
+
+Before the W warm-up steps the headline kernel is launched RAMP more times, untimed, so that a run
+with a short warm-up does not time the clocks coming up after an idle phase; every row of `formats`
+times at least 200 launches after at least 100 warm-up launches of its own.
 """
 from __future__ import annotations
 
@@ -27,10 +31,23 @@ BYTES_PER_ELEMENT = 8          # one fp32 read + one fp32 write
 SGD_BYTES_PER_PARAM = 24       # three reads + three writes
 NSETS = 3
 
-# HBM traffic per launch of the headline kernel measured with rocprofv3 --pmc (FETCH_SIZE, then
-# WRITE_SIZE, each scaled by what the same counter reads for the device-to-device copy below);
-# the runs are summarised in profiles/fixed_sr_64Mi_hbm_counters.txt.
-MEASURED_TRAFFIC_BYTES = 536921236
+RAMP = 300                     # untimed launches ahead of the warm-up (about 25 ms)
+
+# HBM traffic per launch of the headline kernel, measured with rocprofv3 --pmc (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the same counter reads for the device-to-device copy below):
+# read from the summary of those runs, so that the figure and its evidence cannot drift apart.
+TRAFFIC_SUMMARY = os.path.join("profiles", "fixed_sr_64Mi_hbm_counters.txt")
+
+
+def _measured_traffic():
+    """Bytes per launch from the line 'Scaled traffic ... = N bytes' of the summary (None when it is missing)."""
+    import re
+    try:
+        with open(os.path.join(ROOT, TRAFFIC_SUMMARY)) as fh:
+            m = re.search(r"Scaled traffic of the qsim kernel per launch:.*=\s*(\d+) bytes", fh.read())
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def _time_launches(fn, steps, warmup, torch):
@@ -61,7 +78,7 @@ def _entry(name, elements, bytes_per_element, seconds, launches, extra=None):
     per = seconds / launches
     gbs = elements * bytes_per_element / per / 1e9
     d = {"elements": elements, "us_per_call": per * 1e6, "elements_per_s": elements / per, "GBps": gbs,
-         "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}
+         "frac_of_hbm_peak": gbs / HBM_PEAK_GBS, "launches_timed": launches}
     if extra:
         d.update(extra)
     return name, d
@@ -102,6 +119,8 @@ def main() -> int:
     def fixed_step(k):
         Q.fixed_quantize(ins[k % NSETS], 8, 6, Q.STOCHASTIC, Q.SATURATE, seed=1234, stream_id=k, out=outs[k % NSETS])
 
+    for k in range(RAMP):
+        fixed_step(k)
     wall, ev = _time_launches(fixed_step, args.steps, args.warmup, torch)
     # a plain device-to-device copy of the same tensor: the known-size reference that scales the
     # profiler's HBM byte counters (it is outside every timed region)
@@ -125,36 +144,46 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": "fixed_point_quantize 64Mi fp32 (90% U[-4,4) + 10% N(0,sd 10)), wl=8 fl=6, "
                                "stochastic (Philox seed 1234), saturate", "elements": n,
-                   "buffer_sets": NSETS, "in_place": False},
+                   "buffer_sets": NSETS, "in_place": False, "clock_ramp_launches": RAMP},
+        # `frac` is on the HIP-event clock (the kernel's launches alone); `frac_wall` is the same bytes
+        # over the host's clock, which is what `value` and `ms_per_step` are on
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": MEASURED_TRAFFIC_BYTES,
-                     "kernel": "elementwise_kernel<FixedOp, stochastic>", "algorithmic_bytes": n * BYTES_PER_ELEMENT,
-                     "avg_launch_us": ev / args.steps * 1e6},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": _measured_traffic(), "traffic_source": TRAFFIC_SUMMARY,
+                     "kernel": "qsim::elementwise_kernel<qsim::FixedOp, 3, 1>", "algorithmic_bytes": n * BYTES_PER_ELEMENT,
+                     "avg_launch_us": ev / args.steps * 1e6, "avg_launch_us_wall": wall / args.steps * 1e6,
+                     "frac_wall": n * BYTES_PER_ELEMENT / (wall / args.steps) / 1e9 / HBM_PEAK_GBS},
     }
 
     # ---- the other formats ---------------------------------------------------------------------
     if not args.no_formats:
         formats = {}
-        reps = max(10, args.steps // 4)
-        warm = max(10, args.warmup // 2)
+        reps = max(200, args.steps // 4)
+        warm = max(100, args.warmup // 2)
 
-        def run(name, fn, elements, bpe=BYTES_PER_ELEMENT, extra=None):
-            _, e = _time_launches(fn, reps, warm, torch)
-            k, d = _entry(name, elements, bpe, e, reps, extra)
+        def run(name, fn, elements, bpe=BYTES_PER_ELEMENT, extra=None, kernel=None, launches=reps):
+            """Times `launches` calls of fn after `warm` untimed ones; `kernel`: the kernel(s) of one call,
+            named as rocprofv3 prints them, so that the row can be found in profiles/."""
+            _, e = _time_launches(fn, launches, warm, torch)
+            k, d = _entry(name, elements, bpe, e, launches, extra)
+            if kernel:
+                d["kernel"] = kernel
             formats[k] = d
+            return d
 
         run("fixed_8_6_nearest_even", lambda k: Q.fixed_quantize(ins[k % NSETS], 8, 6, Q.RN_EVEN, Q.SATURATE,
-                                                                   out=outs[k % NSETS]), n)
+                                                                   out=outs[k % NSETS]), n,
+            kernel="qsim::elementwise_kernel<qsim::FixedOp, 0, 1>")
         run("fixed_8_6_stochastic_in_place", lambda k: Q.fixed_quantize(outs[k % NSETS], 8, 6, Q.STOCHASTIC, Q.SATURATE,
                                                                           seed=1234, stream_id=k, out=outs[k % NSETS]), n,
-            extra={"note": "input already quantized by the previous runs"})
+            extra={"note": "input already quantized by the previous runs"}, kernel="qsim::elementwise_kernel<qsim::FixedOp, 3, 1>")
         del ins, outs
         torch.cuda.empty_cache()
 
         small = torch.from_numpy(W.normal_tensor()).cuda()
         small_out = torch.empty_like(small)
         run("float_e5m2_nearest_even_1Mi", lambda k: Q.float_quantize(small, 5, 2, Q.RN_EVEN, Q.SATURATE, out=small_out),
-            small.numel(), extra={"note": "launch-latency bound, cache resident"})
+            small.numel(), extra={"note": "launch-latency bound, cache resident"},
+            kernel="qsim::elementwise_kernel<qsim::FloatShiftOp<false>, 0, 1>")
 
         # the same small call captured 16 times in a HIP graph: what remains when launch overhead is amortised
         graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
@@ -164,35 +193,42 @@ def main() -> int:
         _, e = _time_launches(lambda k: graph.replay(), max(10, reps // 4), 10, torch)
         name, d = _entry("float_e5m2_nearest_even_1Mi_in_a_graph_of_16", small.numel(), BYTES_PER_ELEMENT, e,
                          max(10, reps // 4) * 16, {"note": "per call, graph replay; cache resident"})
+        d["kernel"] = "qsim::elementwise_kernel<qsim::FloatShiftOp<false>, 0, 1>"
         formats[name] = d
         del graph
 
         a_in, a_out = _rotating(W.relu_activations().reshape(-1), torch)
         na = a_in[0].numel()
         run("float_e8m7_stochastic_activations", lambda k: Q.float_quantize(
-            a_in[k % NSETS], 8, 7, Q.STOCHASTIC, Q.SATURATE | Q.SUBNORMAL, seed=1234, stream_id=k, out=a_out[k % NSETS]), na)
+            a_in[k % NSETS], 8, 7, Q.STOCHASTIC, Q.SATURATE | Q.SUBNORMAL, seed=1234, stream_id=k, out=a_out[k % NSETS]), na,
+            kernel="qsim::elementwise_kernel<qsim::FloatShiftOp<false>, 3, 1>")
         g_host = W.lognormal_gradients().reshape(-1)
         for k in range(NSETS):
             a_in[k].copy_(torch.roll(torch.from_numpy(g_host).cuda(), 7654321 * k))
         run("float_e5m10_nearest_even_gradients", lambda k: Q.float_quantize(
-            a_in[k % NSETS], 5, 10, Q.RN_EVEN, Q.SATURATE | Q.SUBNORMAL, out=a_out[k % NSETS]), na)
+            a_in[k % NSETS], 5, 10, Q.RN_EVEN, Q.SATURATE | Q.SUBNORMAL, out=a_out[k % NSETS]), na,
+            kernel="qsim::elementwise_kernel<qsim::FloatGeneralOp, 0, 1>")
         # the same [128, 256, 56, 56] tensor with one shared exponent per channel (dimension 1)
         cn, cc, chw = 128, 256, 56 * 56
-        cws = torch.empty(max(Q.block_workspace_bytes(na, cn, cc, chw), 16), dtype=torch.uint8, device="cuda")
+        # (block rows: the workspace is one the caller keeps for the shape, zero-filled once, so no call
+        # launches anything but its one kernel; `gave_up_waiting` must stay 0 on an idle GPU)
+        cws = torch.zeros(max(Q.block_workspace_bytes(na, cn, cc, chw), 16), dtype=torch.uint8, device="cuda")
         for mode, tag in ((Q.RN_EVEN, "nearest_even"), (Q.STOCHASTIC, "stochastic")):
             run(f"block8_per_channel_128x256x56x56_{tag}", lambda k, mode=mode: Q.block_quantize(
-                a_in[k % NSETS], cn, cc, chw, 8, mode, 0, 1234, k, out=a_out[k % NSETS], workspace=cws), na,
-                extra={"note": "blocks along dimension 1; single pass, the workgroups of a channel meet among themselves"})
+                a_in[k % NSETS], cn, cc, chw, 8, mode, Q.WORKSPACE_KEPT, 1234, k, out=a_out[k % NSETS], workspace=cws), na,
+                extra={"note": "blocks along dimension 1; single pass, the workgroups of a channel meet among themselves"},
+                kernel=f"qsim::block_cluster_strided_kernel<{mode}>")["gave_up_waiting"] = Q.workspace_timeouts(cws)
         del a_in, a_out, cws
         torch.cuda.empty_cache()
         # the same per channel where the feature map is not a whole number of groups: [128, 64, 55, 55]
         on, oc, ohw = 128, 64, 55 * 55
         o_in, o_out = _rotating(W.relu_activations((on, oc, 55, 55)).reshape(-1), torch)
-        ows = torch.empty(max(Q.block_workspace_bytes(on * oc * ohw, on, oc, ohw), 16), dtype=torch.uint8, device="cuda")
+        ows = torch.zeros(max(Q.block_workspace_bytes(on * oc * ohw, on, oc, ohw), 16), dtype=torch.uint8, device="cuda")
         for mode, tag in ((Q.RN_EVEN, "nearest_even"), (Q.STOCHASTIC, "stochastic")):
             run(f"block8_per_channel_128x64x55x55_{tag}", lambda k, mode=mode: Q.block_quantize(
-                o_in[k % NSETS], on, oc, ohw, 8, mode, 0, 1234, k, out=o_out[k % NSETS], workspace=ows), on * oc * ohw,
-                extra={"note": "segments of 3025 elements: single pass over the tensor's own groups of four, shared edge groups masked"})
+                o_in[k % NSETS], on, oc, ohw, 8, mode, Q.WORKSPACE_KEPT, 1234, k, out=o_out[k % NSETS], workspace=ows), on * oc * ohw,
+                extra={"note": "segments of 3025 elements: single pass over the tensor's own groups of four, shared edge groups masked"},
+                kernel=f"qsim::block_cluster_ragged_kernel<{mode}>")["gave_up_waiting"] = Q.workspace_timeouts(ows)
         del o_in, o_out, ows
         torch.cuda.empty_cache()
 
@@ -202,13 +238,21 @@ def main() -> int:
         m_out = [torch.empty_like(m_in[0]) for _ in range(NSETS)]
         nm = rows * cols
         ws_bytes = Q.block_workspace_bytes(nm, 1, 1, nm)
-        ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+        ws = torch.zeros(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
         for mode, tag in ((Q.RN_EVEN, "nearest_even"), (Q.STOCHASTIC, "stochastic")):
             run(f"block8_per_row_{tag}", lambda k, mode=mode: Q.block_quantize(
-                m_in[k % NSETS], 1, rows, cols, 8, mode, 0, 1234, k, out=m_out[k % NSETS]), nm)
+                m_in[k % NSETS], 1, rows, cols, 8, mode, 0, 1234, k, out=m_out[k % NSETS]), nm,
+                kernel=f"qsim::block_cached_kernel<{mode}, 4, true, 256>")
             run(f"block8_whole_tensor_{tag}", lambda k, mode=mode: Q.block_quantize(
-                m_in[k % NSETS], 1, 1, nm, 8, mode, 0, 1234, k, out=m_out[k % NSETS], workspace=ws), nm,
-                extra={"note": "single pass: 1024 resident workgroups hold the tensor in registers and meet once"})
+                m_in[k % NSETS], 1, 1, nm, 8, mode, Q.WORKSPACE_KEPT, 1234, k, out=m_out[k % NSETS], workspace=ws), nm,
+                extra={"note": "single pass, one launch: 1024 resident workgroups hold the tensor in registers and meet once"},
+                kernel=f"qsim::block_resident_kernel<{mode}, 16, false>")["gave_up_waiting"] = Q.workspace_timeouts(ws)
+        # the same call from a caller that does not keep its workspace: a clearing launch goes first
+        loose = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device="cuda")
+        run("block8_whole_tensor_stochastic_workspace_not_kept", lambda k: Q.block_quantize(
+            m_in[k % NSETS], 1, 1, nm, 8, Q.STOCHASTIC, 0, 1234, k, out=m_out[k % NSETS], workspace=loose), nm,
+            extra={"note": "two launches: the workspace is cleared first"},
+            kernel="qsim::block_sync_clear_kernel + qsim::block_resident_kernel<3, 16, false>")
         # one GPU's share of the same tensor split over two: block maxima of the share, the elementwise
         # maximum that stands in for the max-all-reduce, then quantize with the given maxima
         half = nm // 2
@@ -223,7 +267,9 @@ def main() -> int:
                                       out=m_out[k % NSETS].reshape(-1)[:half])
 
         run("block8_whole_tensor_one_of_two_shards_stochastic", shard, half,
-            extra={"note": "block_max + maximum + block_quantize_with_max on half of the tensor: two passes, 12 B/element"})
+            extra={"note": "block_max + maximum + block_quantize_with_max on half of the tensor: two passes, 12 B/element"},
+            kernel="qsim::block_slice_max_kernel + qsim::block_fold_partials_wide_kernel + (torch maximum) + "
+                   "qsim::block_slice_apply_kernel<3>")
         del m_in, m_out
         torch.cuda.empty_cache()
 
@@ -238,7 +284,8 @@ def main() -> int:
         run("quant_sgd_step_25.6M", lambda k: Q.quant_sgd_step(sets[k % NSETS][0], sets[k % NSETS][1], sets[k % NSETS][2],
                                                                0.1, 0.9, fg, fm, fw, 1234, k + 2, w_q=sets[k % NSETS][3]),
             npar, bpe=SGD_BYTES_PER_PARAM,
-            extra={"note": "grad float(5,2) stochastic, momentum fixed(16,12) stochastic, weight block8 per 256 nearest"})
+            extra={"note": "grad float(5,2) stochastic, momentum fixed(16,12) stochastic, weight block8 per 256 nearest"},
+            kernel="qsim::sgd_step_kernel<true>")
         del sets
         torch.cuda.empty_cache()
 
@@ -250,15 +297,18 @@ def main() -> int:
         lists = [list(torch.split(f, sizes)) for f in flat]
         table = Q.SgdTensorList(lists[0], lists[1], lists[2], lists[3])
         run("quant_sgd_step_table_resnet50_161_tensors", lambda k: table.step(0.1, 0.9, fg, fm, fw, 1234, k + 2), total,
-            bpe=SGD_BYTES_PER_PARAM, extra={"note": "one call, one launch: the list is a table in device memory"})
+            bpe=SGD_BYTES_PER_PARAM, extra={"note": "one call, one launch: the list is a table in device memory"},
+            kernel="qsim::sgd_table_kernel<true>")
         run("quant_sgd_step_multi_resnet50_161_tensors", lambda k: table.step_batched(0.1, 0.9, fg, fm, fw, 1234, k + 2), total,
-            bpe=SGD_BYTES_PER_PARAM, extra={"note": "one call, three launches of up to 64 tensors (pointer arrays)"})
+            bpe=SGD_BYTES_PER_PARAM, extra={"note": "one call, three launches of up to 64 tensors (pointer arrays)"},
+            kernel="qsim::sgd_multi_kernel<true> x 3")
 
         def per_tensor(k):
             for t in range(len(sizes)):
                 Q.quant_sgd_step(lists[0][t], lists[1][t], lists[2][t], 0.1, 0.9, fg, fm, fw, 1234, k + 2 + t, w_q=lists[3][t])
 
-        run("quant_sgd_step_per_tensor_resnet50_161_calls", per_tensor, total, bpe=SGD_BYTES_PER_PARAM)
+        run("quant_sgd_step_per_tensor_resnet50_161_calls", per_tensor, total, bpe=SGD_BYTES_PER_PARAM,
+            kernel="qsim::sgd_step_kernel<true> x 161", launches=max(20, reps // 10))
         del flat, lists
         torch.cuda.empty_cache()
         result["formats"] = formats
@@ -282,6 +332,9 @@ def main() -> int:
         R.fixed_quantize(part, 8, 6, R.STOCHASTIC, R.SATURATE, seed=1234, stream_id=0, threads=1)
         one = part.size / (time.perf_counter() - t0)
         result["cpu_baseline"] = {"value": n * passes / dt, "unit": "elements/s", "cores": threads, "kind": "oracle",
+                                  "threads": threads, "host_cores": os.cpu_count(),
+                                  "note": "a GPU box gives one GPU's job 16 cores, whatever the host has: the oracle runs on "
+                                          "min(16, host cores) threads, and `cores` is that number",
                                   "sample": f"{passes} passes over the whole {n}-element tensor of the headline workload, "
                                             f"each split over {threads} threads ({dt:.2f} s wall, "
                                             f"{dt * threads:.0f} s of CPU work)",
@@ -309,9 +362,16 @@ def main() -> int:
                     mat, 1, 1, mat.size, 8, R.RN_EVEN), mat.size),
                 "quant_sgd_step_one_thread": rate(lambda: R.quant_sgd_step(w, g, m, 0.1, 0.9, fg, fm, fw, 1234, 2), w.size),
             }
-    print(json.dumps(result))
+    print(json.dumps(result), flush=True)
+    # leave nothing behind: everything queued has finished, device memory goes back now
+    torch.cuda.synchronize()
     return 0
 
 
 if __name__ == "__main__":
-    sys.exit(main())
+    rc = main()
+    # the result is printed and the device is idle: end the process at once rather than through the
+    # interpreter's teardown of several GB of tensors and library state, which outlives the last line
+    sys.stdout.flush()
+    sys.stderr.flush()
+    os._exit(rc)

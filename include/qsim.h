@@ -65,9 +65,10 @@ enum {
 enum { QSIM_RN_EVEN = 0, QSIM_RN_AWAY = 1, QSIM_RN_ZERO = 2, QSIM_STOCHASTIC = 3 };
 
 enum {
-    QSIM_SATURATE = 1u,   /* clamp to the format's range instead of leaving the range open */
-    QSIM_SUBNORMAL = 2u,  /* float only: gradual underflow below 2^emin instead of flush to zero */
-    QSIM_SYMMETRIC = 4u   /* fixed/block: drop the most negative two's-complement code */
+    QSIM_SATURATE = 1u,        /* clamp to the format's range instead of leaving the range open */
+    QSIM_SUBNORMAL = 2u,       /* float only: gradual underflow below 2^emin instead of flush to zero */
+    QSIM_SYMMETRIC = 4u,       /* fixed/block: drop the most negative two's-complement code */
+    QSIM_WORKSPACE_KEPT = 8u   /* qsim_block_quantize(_at) only: the caller keeps the workspace, see there */
 };
 
 /*
@@ -104,8 +105,22 @@ int qsim_fixed_quantize(const float* in, float* out, uint64_t n, int wl, int fl,
  * [-2^(wl-1), 2^(wl-1) - 1] (QSIM_SYMMETRIC as above).  The maximum is taken on the raw input.
  *
  * workspace: device scratch of at least qsim_block_workspace_bytes(...) bytes, 16-byte
- * aligned, used for per-block maxima when a block is spread over several workgroups; may be
- * NULL when that function returns 0.  Its contents are overwritten; it needs no initialisation.
+ * aligned, used when a block is spread over several workgroups; may be NULL when that function
+ * returns 0.  Its contents are overwritten; it needs no initialisation, and no two calls that are
+ * in flight at the same time may share it.
+ *
+ * QSIM_WORKSPACE_KEPT (in `flags`).  The single-pass forms (see qsim_set_barrier_wait_us) keep a
+ * few counters in the workspace that must be zero when their kernel starts.  By default every such
+ * call zeroes them with a small launch of its own before the kernel.  A caller that sets a
+ * workspace aside for the calls of ONE shape (n, outer, nblocks, inner) saves that launch: fill the
+ * workspace with zeros once, before its first use, and pass QSIM_WORKSPACE_KEPT with every call
+ * that uses it.  Each call then leaves the workspace ready for the next one (also when it is
+ * replayed from a graph, and also when its bounded wait ran out), provided that nothing but
+ * qsim_block_quantize(_at) calls of that shape, all with this flag, writes to it in between.
+ * The flag changes no result.  Forms that need no such state ignore it.
+ * The first 32-bit word of the workspace counts, since the workspace was last zeroed, the
+ * workgroups of single-pass calls that stopped waiting for the others (qsim_set_barrier_wait_us);
+ * it is there for callers and tests that want to know that this happened.
  */
 int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks,
                         uint64_t inner, int wl, int rounding, uint32_t flags, uint64_t seed,
@@ -117,11 +132,16 @@ size_t qsim_block_workspace_bytes(uint64_t n, uint64_t outer, uint64_t nblocks, 
  * Tuning and test knob of qsim_block_quantize.  A block that is too long for one workgroup but
  * fits in the register files of the chip (a whole tensor of up to 16 Mi elements; in larger
  * tensors every block of up to 1 Mi contiguous or 4 Mi strided elements) is quantized in a single
- * pass by workgroups that wait for each other once.  That wait is bounded: after `microseconds`
- * (default 2000) a workgroup stops waiting and derives the missing maxima from memory itself, so
- * the result is the same, only slower; this happens when the device is shared with other work and
- * not every workgroup got a slot.  0 makes every workgroup take that path at once.  Process-wide;
- * affects calls made after it returns.
+ * pass by workgroups that hold its slices in registers and wait for each other once.  For a whole
+ * tensor the grid is no larger than what the device holds at once; for many blocks the workgroups
+ * are numbered block by block and the forms count on the device starting them in that order, so
+ * that the workgroups of the lowest unfinished block are always running.  Neither holds when the
+ * device is shared with other work (other processes, other streams), so the wait is bounded: after
+ * `microseconds` (default 2000) a workgroup stops waiting and derives the missing maxima from
+ * memory itself.  The result is the same, only slower: a call that normally takes tens of
+ * microseconds then takes `microseconds` and more.  Such workgroups are counted in the first word of
+ * the workspace (see qsim_block_quantize).  0 makes every workgroup take that path at once.
+ * Process-wide: it affects every call made after it returns, on any thread.
  */
 void qsim_set_barrier_wait_us(uint32_t microseconds);
 

@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libqsim.so")
 
 RN_EVEN, RN_AWAY, RN_ZERO, STOCHASTIC = 0, 1, 2, 3
 SATURATE, SUBNORMAL, SYMMETRIC = 1, 2, 4
+WORKSPACE_KEPT = 8             # block_quantize only: see qsim_block_quantize in include/qsim.h
 KIND_IDENTITY, KIND_FLOAT, KIND_FIXED, KIND_BLOCK = 0, 1, 2, 3
 
 # Every symbol include/qsim.h declares.
@@ -187,15 +188,28 @@ def block_workspace_bytes(n, outer, nblocks, inner) -> int:
 
 
 _scratch = {}                    # (device index, stream handle) -> uint8 tensor, reused by calls on that stream
+_kept = {}                       # (device index, stream handle, n, outer, nblocks, inner) -> zero-filled uint8 tensor
 _SCRATCH_KEEP = 64 << 20         # larger scratch is allocated per call and released with it
+_KEPT_LIMIT = 4 << 20            # a shape whose scratch is larger shares the stream's scratch instead
 
 
-def _workspace(x, outer, nblocks, inner, workspace):
+def _workspace(x, outer, nblocks, inner, workspace, may_keep=False):
+    """Scratch for a block call: (pointer, bytes, the tensor that owns them, QSIM_WORKSPACE_KEPT or 0)."""
     need = block_workspace_bytes(x.numel(), outer, nblocks, inner)
     if not need:
-        return 0, 0, None
+        return 0, 0, None, 0
+    kept = 0
     if workspace is None:
-        if need > _SCRATCH_KEEP or torch.cuda.is_current_stream_capturing():
+        capturing = torch.cuda.is_current_stream_capturing()
+        if may_keep and need <= _KEPT_LIMIT and not capturing:
+            # one zero-filled buffer per stream and shape, written by nothing but these calls: the
+            # library then keeps its counters in it from call to call and launches no clearing kernel
+            key = (x.device.index, _stream(), x.numel(), outer, nblocks, inner)
+            workspace = _kept.get(key)
+            if workspace is None:
+                workspace = _kept[key] = torch.zeros(need, dtype=torch.uint8, device=x.device)
+            kept = WORKSPACE_KEPT
+        elif need > _SCRATCH_KEEP or capturing:
             # (memory allocated during a graph capture belongs to the graph: never shared with eager calls)
             workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
         else:
@@ -205,19 +219,23 @@ def _workspace(x, outer, nblocks, inner, workspace):
             if workspace is None or workspace.numel() < need:
                 workspace = torch.empty(max(need, 1 << 20), dtype=torch.uint8, device=x.device)
                 _scratch[key] = workspace
-    return workspace.data_ptr(), workspace.numel() * workspace.element_size(), workspace
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size(), workspace, kept
 
 
 def block_quantize(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed=0, stream_id=0, out=None,
                    workspace=None, index0=0):
     """qsim_block_quantize on a device tensor viewed as [outer, nblocks, inner].
 
-    ``workspace``: a device tensor of at least ``block_workspace_bytes(...)`` bytes; allocated
-    through torch when omitted and needed.  ``index0``: position of ``x[0]`` in the whole tensor
-    when ``x`` is a shard of whole blocks (qsim_block_quantize_at)."""
+    ``workspace``: a device tensor of at least ``block_workspace_bytes(...)`` bytes.  When omitted
+    and needed, the binding keeps a zero-filled one per stream and shape and passes
+    ``WORKSPACE_KEPT`` with it.  A caller who brings a workspace and has kept it as
+    ``include/qsim.h`` asks (zero-filled once, then used for this shape only) may add
+    ``WORKSPACE_KEPT`` to ``flags``.  ``index0``: position of ``x[0]`` in the whole tensor when
+    ``x`` is a shard of whole blocks (qsim_block_quantize_at)."""
     _device_f32(x, "x")
     out = _out_like(x, out)
-    ws_ptr, ws_bytes, workspace = _workspace(x, outer, nblocks, inner, workspace)
+    ws_ptr, ws_bytes, workspace, kept = _workspace(x, outer, nblocks, inner, workspace, may_keep=True)
+    flags |= kept
     if index0:
         _check(lib().qsim_block_quantize_at(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, index0, wl,
                                             rounding, flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
@@ -225,6 +243,18 @@ def block_quantize(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed
         _check(lib().qsim_block_quantize(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, wl, rounding,
                                          flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
     return out
+
+
+def kept_workspace(x, outer, nblocks, inner):
+    """The zero-filled scratch the binding keeps for block_quantize calls of this shape on the
+    current stream (None before the first such call, or when the shape needs none)."""
+    return _kept.get((x.device.index, _stream(), x.numel(), outer, nblocks, inner))
+
+
+def workspace_timeouts(workspace) -> int:
+    """Workgroups of single-pass block_quantize calls that stopped waiting for the others since
+    ``workspace`` was last zeroed (its first 32-bit word; waits for the device)."""
+    return int(workspace[:4].view(torch.int32).item()) if workspace is not None and workspace.numel() >= 4 else 0
 
 
 def block_max(x, outer, nblocks, inner, out=None, workspace=None):
@@ -235,7 +265,7 @@ def block_max(x, outer, nblocks, inner, out=None, workspace=None):
         out = torch.empty(nblocks, dtype=torch.int32, device=x.device)
     elif not out.is_cuda or out.dtype != torch.int32 or not out.is_contiguous() or out.numel() != nblocks:
         raise TypeError("out must be a contiguous int32 tensor of nblocks elements on the GPU")
-    ws_ptr, ws_bytes, workspace = _workspace(x, outer, nblocks, inner, workspace)
+    ws_ptr, ws_bytes, workspace, _ = _workspace(x, outer, nblocks, inner, workspace)
     _check(lib().qsim_block_max(x.data_ptr(), x.numel(), outer, nblocks, inner, out.data_ptr(), ws_ptr, ws_bytes, _stream()))
     return out
 
@@ -300,6 +330,10 @@ class SgdTensorList:
         self._table_memory = None
 
     def _build_table(self) -> None:
+        if torch.cuda.is_current_stream_capturing():
+            # qsim_sgd_table_build copies the table to the device and waits for the copy
+            raise RuntimeError("the device table of an SgdTensorList cannot be built during a stream capture: "
+                               "call build_table() (or take one eager step) before capturing")
         k = self.count
         table = SgdTable()
         need = int(lib().qsim_sgd_table_bytes(k, self.sizes))
@@ -309,6 +343,12 @@ class SgdTensorList:
                                           self._table_memory.data_ptr() if need else None, need, _stream(),
                                           ctypes.byref(table)))
         self.table = table
+
+    def build_table(self) -> None:
+        """Builds the device table now (``step`` does it on its first call otherwise); needed before
+        a stream capture, which can record ``step`` but not the building of the table."""
+        if self.table is None:
+            self._build_table()
 
     def step(self, lr, momentum, fmt_grad: Format, fmt_mom: Format, fmt_weight: Format, seed=0, stream_id=0,
              options: SgdOptions = None) -> None:

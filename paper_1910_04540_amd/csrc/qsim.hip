@@ -14,7 +14,14 @@
 
 namespace qsim {
 
-static hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+// The caller's stream.  Called once by every entry point, after validation and before its first
+// launch: an error that an earlier, unrelated HIP call of the caller left pending is dropped here,
+// so that launch_status() reports this call's launches only.
+static hipStream_t as_stream(void* s)
+{
+    (void)hipGetLastError();
+    return reinterpret_cast<hipStream_t>(s);
+}
 static int launch_status() { return hipGetLastError() == hipSuccess ? QSIM_OK : QSIM_ERR_LAUNCH; }
 static RngKey make_key(uint64_t seed, uint32_t stream_id, uint64_t index0)
 {
@@ -93,7 +100,15 @@ struct BlockSchedule {
     FlatGeom fg;
     bool column;           // outer > 1 and short blocks: the column form (any row length, any alignment)
     ColumnGeom cg;
-    size_t workspace;      // bytes of scratch needed (the largest of the forms the shape may take)
+    // The scratch has two parts, so that a caller may keep it between calls (QSIM_WORKSPACE_KEPT):
+    // the words of the single-pass forms' meetings come first, and only the meetings write there;
+    // the partial maxima of the two-pass forms start at `partial_offset`.
+    uint64_t sync_counters; // 64-bit words of header and counters of the single-pass forms the shape may take: the largest
+    uint64_t sync_tagged;  // the same for their tagged words, which start behind sync_counters in every form
+    size_t sync_bytes;     // (sync_counters + sync_tagged) * 8
+    size_t partial_bytes;  // the largest scratch of its two-pass forms
+    size_t partial_offset; // sync_bytes rounded up to 256
+    size_t workspace;      // partial_offset + partial_bytes
 };
 
 constexpr uint64_t kCachedMaxInner = 16384;      // 256 threads x 16 groups x 4 elements
@@ -106,6 +121,7 @@ constexpr uint32_t kMaxSlices = 1024;
 constexpr uint64_t kMinSliceLen = 16384;
 constexpr uint64_t kTileLen = 4ull * kTileGroups;
 constexpr uint32_t kMaxResidentWgs = 4096;       // bound of the single-pass form's scratch
+constexpr uint32_t kMaxResidentGroups = 128;     // counters (and blocks) of one resident launch: a line each
 constexpr uint64_t kPackedSmallTensor = 1ull << 23;   // elements; see block_schedule
 constexpr uint64_t kRaggedMinGroups = 2048;      // smallest block, in group slots, for the single pass over odd segments
 constexpr uint64_t kCachedTensorElements = 96ull << 20;   // 384 MiB: see column_geometry
@@ -150,6 +166,47 @@ static size_t column_bytes(const ColumnGeom& cg)
     return ((size_t)cg.slices + fewer) * (size_t)cg.row_groups * 4 * sizeof(uint32_t) + (size_t)cg.nblocks * sizeof(uint32_t);
 }
 
+static std::atomic<uint32_t> g_barrier_wait_us{2000u};
+
+// Words of the meetings of `nblocks` blocks of `slices` workgroups each (see meet_in_block): the
+// counters right behind the header, the tagged words from `tagged` on, which is the same for every
+// form a shape may take, so that no form ever leaves a tagged word where another has a counter.
+struct MeetLayout {
+    MeetGeom geom;
+    uint64_t counter_words;   // header and counters
+    uint64_t tagged_words;    // flags and slots
+};
+
+static MeetLayout meet_layout(uint64_t nblocks, uint32_t slices, uint32_t stride, uint64_t tagged = 0)
+{
+    MeetLayout l;
+    MeetGeom& g = l.geom;
+    g.nblocks = nblocks;
+    g.slices = slices;
+    g.groups = (slices + kMeetGroup - 1) / kMeetGroup;
+    g.stride = stride;
+    g.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
+    g.counters = kMeetHeaderWords;
+    g.tops = g.counters + nblocks * g.groups * stride;
+    g.finished = g.tops + nblocks * stride;
+    l.counter_words = g.finished + (nblocks + kMeetBlocksPerWord - 1) / kMeetBlocksPerWord;
+    g.flags = tagged ? tagged : l.counter_words;
+    g.slots = g.flags + nblocks * g.groups * stride;
+    l.tagged_words = nblocks * g.groups * stride + nblocks * slices;
+    return l;
+}
+
+// The resident form gives every counter and flag a line of its own while they are few; its scratch is at most this.
+constexpr uint64_t kResidentCounterWords = kMeetHeaderWords + 2ull * kMaxResidentGroups * kMeetLine + 1;
+constexpr uint64_t kResidentTaggedWords = (uint64_t)kMaxResidentGroups * kMeetLine + kMaxResidentWgs;
+
+// Zeroes what a launch with this layout reads of a scratch that its caller does not keep.
+static void clear_scratch(uint64_t* scratch, const MeetLayout& l, hipStream_t stream)
+{
+    const uint64_t words = l.geom.flags + l.tagged_words;
+    hipLaunchKernelGGL(block_sync_clear_kernel, folded((words + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, scratch, words);
+}
+
 static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner)
 {
     BlockSchedule s;
@@ -169,17 +226,26 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
     slices = (s.sg.block_len + slice_len - 1) / slice_len;
     s.sg.slice_len = slice_len;
     s.sg.slices = (uint32_t)slices;
-    s.workspace = (size_t)(nblocks * slices * sizeof(uint32_t));
-    // the single-pass form keeps its counter and one slot per workgroup in the same scratch
-    const size_t resident = (size_t)(kSyncSlots0 + kMaxResidentWgs) * sizeof(uint32_t);
-    if (outer == 1 && s.workspace < resident) s.workspace = resident;
-    // the same kernel meeting block by block: one slot per workgroup of 16,384 elements
+    auto sync_needs = [&s](uint64_t counter_words, uint64_t tagged_words) {
+        if (s.sync_counters < counter_words) s.sync_counters = counter_words;
+        if (s.sync_tagged < tagged_words) s.sync_tagged = tagged_words;
+    };
+    auto meeting = [&](uint32_t slices_each) {
+        const MeetLayout l = meet_layout(nblocks, slices_each, 1);
+        sync_needs(l.counter_words, l.tagged_words);
+    };
+    auto partial_needs = [&s](size_t bytes) {
+        if (s.partial_bytes < bytes) s.partial_bytes = bytes;
+    };
+    partial_needs((size_t)(nblocks * slices * sizeof(uint32_t)));
+    // the single-pass form over resident workgroups
+    if (outer == 1) sync_needs(kResidentCounterWords, kResidentTaggedWords);
+    // the same kernel meeting block by block: workgroups of 16,384 elements
     const uint64_t cluster_slices = (inner + kClusterSliceLen - 1) / kClusterSliceLen;
     if (outer == 1 && inner > kWideCachedMaxInner && cluster_slices <= kClusterMaxSlices &&
         nblocks * cluster_slices <= kClusterMaxWgs) {
         s.cluster = true;
-        const size_t bytes = (size_t)(kSyncSlots0 + nblocks * cluster_slices) * sizeof(uint32_t);
-        if (s.workspace < bytes) s.workspace = bytes;
+        meeting((uint32_t)cluster_slices);
     }
     // (the runs a workgroup reads are 16 KiB / outer long: only for few outer indices, or for a
     // tensor small enough that one launch instead of three or four outweighs the scattered reads:
@@ -205,8 +271,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
             s.scg.inner = (uint32_t)inner;
             s.scg.magic_inner = (uint32_t)((1ull << 32) / inner) + 1u;
             s.scg.total_wgs = (uint32_t)(nblocks * slices_each);
-            const size_t bytes = (size_t)s.scg.total_wgs * sizeof(uint32_t);
-            if (s.workspace < bytes) s.workspace = bytes;
+            meeting(s.scg.slices);
         }
     }
     if (inner >= 64 && inner <= (1ull << 22)) {          // (contiguous blocks too: one segment each)
@@ -227,8 +292,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
                 s.rcg.slices = (uint32_t)slices_each;
                 s.rcg.slice_groups = (uint32_t)(((uint64_t)block_groups + slices_each - 1) / slices_each);
                 s.rcg.total_wgs = (uint32_t)(nblocks * slices_each);
-                const size_t bytes = (size_t)s.rcg.total_wgs * sizeof(uint32_t);
-                if (s.workspace < bytes) s.workspace = bytes;
+                meeting(s.rcg.slices);
             }
         }
     }
@@ -251,8 +315,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         fg.stream_first = n > kCachedTensorElements ? 1u : 0u;
         fg.copies = 1;
         while (fg.copies < 64 && 2 * fg.copies * fg.nblocks <= (uint32_t)kFlatMaxBlocks) fg.copies *= 2;
-        const size_t flat_bytes = (size_t)(kFlatWorkgroups + kFlatParts + 1) * nblocks * sizeof(uint32_t);
-        if (s.workspace < flat_bytes) s.workspace = flat_bytes;
+        partial_needs((size_t)(kFlatWorkgroups + kFlatParts + 1) * nblocks * sizeof(uint32_t));
     }
     // the column form: short segments (a thread walking down a column jumps a whole row per step, which
     // only pays when the alternative would do a division per run of a short segment), and segments of
@@ -266,14 +329,15 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
          (inner <= kColumnMaxInner && nblocks >= kColumnManyBlocks))) {
         s.column = true;
         s.cg = column_geometry(outer, nblocks, inner);
-        const size_t bytes = column_bytes(s.cg);
-        if (s.workspace < bytes) s.workspace = bytes;
+        partial_needs(column_bytes(s.cg));
     }
+    s.sync_bytes = (size_t)((s.sync_counters + s.sync_tagged) * sizeof(uint64_t));
+    s.partial_offset = (s.sync_bytes + 255) & ~(size_t)255;
+    s.workspace = s.partial_offset + s.partial_bytes;
     return s;
 }
 
 // ---- single pass over resident workgroups ----------------------------------------------------
-static std::atomic<uint32_t> g_barrier_wait_us{2000u};
 
 // Workgroups of block_resident_kernel<MODE, GPT> that are certain to be resident together on the
 // current device: four per CU at most.  At that occupancy every resource is accounted for by
@@ -309,22 +373,25 @@ static uint32_t resident_capacity()
 // path, so residency is a matter of speed, not of correctness or termination.
 template <int MODE, int GPT>
 static bool try_resident(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
-                         uint32_t* sync, hipStream_t stream)
+                         uint64_t* scratch, uint64_t tagged, bool kept, hipStream_t stream)
 {
     const uint64_t slice_len = 4ull * kThreads * GPT;
     const uint64_t slices = (g.inner + slice_len - 1) / slice_len;
     const uint64_t total = slices * g.nblocks;
-    if (total > kMaxResidentWgs || total > kSyncGroup * kSyncMaxGroups || total > resident_capacity<MODE, GPT>()) return false;
+    if (total > kMaxResidentWgs || total > resident_capacity<MODE, GPT>()) return false;
+    // a line for every counter, flag and epoch while they are few; packed otherwise (many small blocks)
+    const uint64_t groups = g.nblocks * ((slices + kMeetGroup - 1) / kMeetGroup);
+    const MeetLayout meet = meet_layout(g.nblocks, (uint32_t)slices, groups <= kMaxResidentGroups ? kMeetLine : 1u, tagged);
+    if (meet.counter_words > kResidentCounterWords || meet.tagged_words > kResidentTaggedWords) return false;
     ResidentGeom rg;
     rg.sg.g = g;
     rg.sg.block_len = g.inner;
     rg.sg.slice_len = slice_len;
     rg.sg.slices = (uint32_t)slices;
     rg.total_wgs = (uint32_t)total;
-    rg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
-    const uint32_t words = kSyncSlots0 + (uint32_t)total;
-    hipLaunchKernelGGL(block_sync_clear_kernel, dim3((words + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, sync, words);
-    hipLaunchKernelGGL((block_resident_kernel<MODE, GPT>), dim3((unsigned)total), dim3(kThreads), 0, stream, in, out, sync, rg,
+    rg.meet = meet.geom;
+    if (!kept) clear_scratch(scratch, meet, stream);
+    hipLaunchKernelGGL((block_resident_kernel<MODE, GPT>), dim3((unsigned)total), dim3(kThreads), 0, stream, in, out, scratch, rg,
                        wl, symmetric, key);
     return true;
 }
@@ -332,35 +399,34 @@ static bool try_resident(const uint32_t* in, uint32_t* out, const BlockGeom& g, 
 // The single-pass form block by block, for more blocks than the chip holds at once (see the kernel).
 template <int MODE>
 static bool try_cluster(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
-                        uint32_t* sync, hipStream_t stream)
+                        uint64_t* scratch, uint64_t tagged, bool kept, hipStream_t stream)
 {
     const uint64_t slices = (g.inner + kClusterSliceLen - 1) / kClusterSliceLen;
     if (resident_capacity<MODE, 16>() < kClusterMaxSlices) return false;     // a block's workgroups must fit together
+    const MeetLayout meet = meet_layout(g.nblocks, (uint32_t)slices, 1u, tagged);
     ResidentGeom rg;
     rg.sg.g = g;
     rg.sg.block_len = g.inner;
     rg.sg.slice_len = kClusterSliceLen;
     rg.sg.slices = (uint32_t)slices;
     rg.total_wgs = (uint32_t)(slices * g.nblocks);
-    rg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
-    uint32_t* slots = sync + kSyncSlots0;
-    hipLaunchKernelGGL(block_sync_clear_kernel, folded((rg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
-                       slots, rg.total_wgs);
-    hipLaunchKernelGGL((block_resident_kernel<MODE, 16, true>), folded(rg.total_wgs), dim3(kThreads), 0, stream, in, out, sync,
+    rg.meet = meet.geom;
+    if (!kept) clear_scratch(scratch, meet, stream);
+    hipLaunchKernelGGL((block_resident_kernel<MODE, 16, true>), folded(rg.total_wgs), dim3(kThreads), 0, stream, in, out, scratch,
                        rg, wl, symmetric, key);
     return true;
 }
 
 template <int MODE>
 static bool try_resident_any(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
-                             uint32_t* sync, hipStream_t stream)
+                             uint64_t* scratch, uint64_t tagged, bool kept, hipStream_t stream)
 {
     // fewest groups per thread that still fit: more workgroups in flight hide more latency
-    return try_resident<MODE, 1>(in, out, g, wl, symmetric, key, sync, stream) ||
-           try_resident<MODE, 2>(in, out, g, wl, symmetric, key, sync, stream) ||
-           try_resident<MODE, 4>(in, out, g, wl, symmetric, key, sync, stream) ||
-           try_resident<MODE, 8>(in, out, g, wl, symmetric, key, sync, stream) ||
-           try_resident<MODE, 16>(in, out, g, wl, symmetric, key, sync, stream);
+    return try_resident<MODE, 1>(in, out, g, wl, symmetric, key, scratch, tagged, kept, stream) ||
+           try_resident<MODE, 2>(in, out, g, wl, symmetric, key, scratch, tagged, kept, stream) ||
+           try_resident<MODE, 4>(in, out, g, wl, symmetric, key, scratch, tagged, kept, stream) ||
+           try_resident<MODE, 8>(in, out, g, wl, symmetric, key, scratch, tagged, kept, stream) ||
+           try_resident<MODE, 16>(in, out, g, wl, symmetric, key, scratch, tagged, kept, stream);
 }
 
 template <int MODE, int GPT, bool WHOLE>
@@ -404,19 +470,19 @@ static void launch_block_ragged(const uint32_t* in, uint32_t* out, const BlockGe
 
 template <int MODE>
 static void launch_block_cluster_ragged(const uint32_t* in, uint32_t* out, const RaggedClusterGeom& geom, int wl, int symmetric,
-                                        const RngKey& key, uint32_t* slots, hipStream_t stream)
+                                        const RngKey& key, uint64_t* scratch, uint64_t tagged, bool kept, hipStream_t stream)
 {
     RaggedClusterGeom cg = geom;
-    cg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
-    hipLaunchKernelGGL(block_sync_clear_kernel, folded((cg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, slots,
-                       cg.total_wgs);
-    hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, in, out, slots, cg,
+    const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, tagged);
+    cg.meet = meet.geom;
+    if (!kept) clear_scratch(scratch, meet, stream);
+    hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, in, out, scratch, cg,
                        wl, symmetric, key);
 }
 
 template <int MODE>
 static int launch_block_mode(const float* in, float* out, const BlockSchedule& s, int wl, int symmetric,
-                             const RngKey& key, void* workspace, hipStream_t stream)
+                             const RngKey& key, void* workspace, bool kept, hipStream_t stream)
 {
     const uint32_t* pin = u32(in);
     uint32_t* pout = u32(out);
@@ -451,7 +517,9 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         }
         return launch_status();
     }
-    uint32_t* partial = reinterpret_cast<uint32_t*>(workspace);
+    // meetings of the single-pass forms at the start of the scratch, partial maxima of the others behind them
+    uint64_t* scratch = reinterpret_cast<uint64_t*>(workspace);
+    uint32_t* partial = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + s.partial_offset);
     const dim3 grid = folded_xz(g.nblocks, s.sg.slices);
     // Segments of at most 128 elements that do not start and end on 64-byte lines: a kernel that
     // works block by block writes their first and last lines in two parts at different times, and
@@ -461,7 +529,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
     if (vec && g.outer == 1) {
         // single pass when the blocks fit in the chip's registers, else the streaming two-pass form:
         // blocks on grid.y (folded when there are more than 65535), slices on grid.x
-        if (try_resident_any<MODE>(pin, pout, g, wl, symmetric, key, partial, stream)) return launch_status();
+        if (try_resident_any<MODE>(pin, pout, g, wl, symmetric, key, scratch, s.sync_counters, kept, stream)) return launch_status();
         if (g.inner <= kWideCachedMaxInner) {
             // too many blocks to hold at once, but each fits the registers of one large workgroup, 16
             // groups per lane: two workgroups of 512 threads per CU, or one of 1024
@@ -473,7 +541,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                                    stream, pin, pout, g, 10, wl, symmetric, key);
             return launch_status();
         }
-        if (s.cluster && try_cluster<MODE>(pin, pout, g, wl, symmetric, key, partial, stream)) return launch_status();
+        if (s.cluster && try_cluster<MODE>(pin, pout, g, wl, symmetric, key, scratch, s.sync_counters, kept, stream)) return launch_status();
         const unsigned by = (unsigned)(g.nblocks < 65535 ? g.nblocks : 65535);
         hipLaunchKernelGGL(block_slice_max_kernel, dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, partial, s.sg);
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
@@ -481,7 +549,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
     } else if (g.outer == 1 && s.strided_ragged && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // contiguous blocks of up to 4 Mi elements whose length is not a multiple of four, or in
         // arrays that are only dword aligned: single pass, block by block, over the array's own groups
-        launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, partial, stream);
+        launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, scratch, s.sync_counters, kept, stream);
     } else if (vec && s.strided_packed) {
         const uint64_t wgs = (g.nblocks + s.spg.blocks_per_wg - 1) / s.spg.blocks_per_wg;
         hipLaunchKernelGGL((block_strided_packed_kernel<MODE>), folded(wgs), dim3(kThreads), 0, stream, pin, pout, s.spg, wl,
@@ -490,14 +558,14 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // single pass, block by block (see the kernel): the workgroups of a block must fit together
         StridedClusterGeom cg = s.scg;
-        cg.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
-        hipLaunchKernelGGL(block_sync_clear_kernel, folded((cg.total_wgs + kThreads - 1) / kThreads), dim3(kThreads), 0, stream,
-                           partial, cg.total_wgs);
+        const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, s.sync_counters);
+        cg.meet = meet.geom;
+        if (!kept) clear_scratch(scratch, meet, stream);
         hipLaunchKernelGGL((block_cluster_strided_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
-                           partial, cg, wl, symmetric, key);
+                           scratch, cg, wl, symmetric, key);
     } else if (s.strided_ragged && !short_segments && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // the same for segments of any length and alignment
-        launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, partial, stream);
+        launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, scratch, s.sync_counters, kept, stream);
     } else if (s.flat && !(vec && g.inner > 128) && (!s.column || g.nblocks < 64 || s.fg.row < 2048)) {
         // short rows, unless long aligned segments stream well through the slice kernels: always when
         // the column form cannot run; otherwise where that form is weak (few blocks make its fold
@@ -526,7 +594,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         uint32_t* fewer = partial + (size_t)cg.slices * row_words;
         uint32_t* blockmax = fewer + (cg.slices > 2 * kColumnParts ? (size_t)kColumnParts * row_words : 0);
         const dim3 cgrid((cg.row_groups + kThreads - 1) / kThreads, cg.slices);
-        uint4* colmax = reinterpret_cast<uint4*>(workspace);
+        uint4* colmax = reinterpret_cast<uint4*>(partial);
         if (wide) hipLaunchKernelGGL(block_column_max_kernel<true>, cgrid, dim3(kThreads), 0, stream, pin, colmax, cg);
         else hipLaunchKernelGGL(block_column_max_kernel<false>, cgrid, dim3(kThreads), 0, stream, pin, colmax, cg);
         // fold: over slices first when there are many (neighbouring threads on neighbouring columns),
@@ -677,33 +745,51 @@ int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer,
                                   workspace_bytes, hip_stream);
 }
 
-int qsim_block_quantize_at(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner,
-                           uint64_t index0, int wl, int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id,
-                           void* workspace, size_t workspace_bytes, void* hip_stream)
+// Everything of qsim_block_quantize_at after the validation that does not depend on whose the scratch is.
+static int block_quantize_checked(const float* in, float* out, uint64_t n, const BlockSchedule& s, uint64_t index0, int wl,
+                                  int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id, void* workspace,
+                                  hipStream_t stream)
+{
+    const RngKey key = make_key(seed, stream_id, index0);
+    const int symmetric = (flags & QSIM_SYMMETRIC) ? 1 : 0;
+    const bool kept = (flags & QSIM_WORKSPACE_KEPT) != 0;
+    (void)n;
+    switch (rounding) {
+    case QSIM_RN_EVEN: return launch_block_mode<QSIM_RN_EVEN>(in, out, s, wl, symmetric, key, workspace, kept, stream);
+    case QSIM_RN_AWAY: return launch_block_mode<QSIM_RN_AWAY>(in, out, s, wl, symmetric, key, workspace, kept, stream);
+    case QSIM_RN_ZERO: return launch_block_mode<QSIM_RN_ZERO>(in, out, s, wl, symmetric, key, workspace, kept, stream);
+    default:           return launch_block_mode<QSIM_STOCHASTIC>(in, out, s, wl, symmetric, key, workspace, kept, stream);
+    }
+}
+
+// Validation of a block-quantize call up to (not including) the scratch.
+static int check_block_call(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner,
+                            uint64_t index0, int wl, int rounding, uint32_t flags)
 {
     if (!valid_rounding(rounding)) return QSIM_ERR_ROUNDING;
-    if (!valid_block_wl(wl) || !valid_flags(flags)) return QSIM_ERR_FORMAT;
+    if (!valid_block_wl(wl) || !valid_block_flags(flags)) return QSIM_ERR_FORMAT;
     if (n > kMaxElements || !valid_index0(index0)) return QSIM_ERR_SHAPE;
     if (n == 0) return QSIM_OK;
     if (!valid_block_shape(n, outer, nblocks, inner)) return QSIM_ERR_SHAPE;
     if (!in || !out) return QSIM_ERR_NULL;
     if (partial_overlap(in, out, n)) return QSIM_ERR_OVERLAP;
-    const BlockSchedule s = block_schedule(n, outer, nblocks, inner);
     if (nblocks > 0x7fffffffull) return QSIM_ERR_UNSUPPORTED;
+    return QSIM_OK;
+}
+
+int qsim_block_quantize_at(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner,
+                           uint64_t index0, int wl, int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id,
+                           void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    const int status = check_block_call(in, out, n, outer, nblocks, inner, index0, wl, rounding, flags);
+    if (status != QSIM_OK || n == 0) return status;
+    const BlockSchedule s = block_schedule(n, outer, nblocks, inner);
     if (s.workspace) {
         if (!workspace || !aligned16(workspace) || workspace_bytes < s.workspace) return QSIM_ERR_WORKSPACE;
         if (ranges_overlap(workspace, s.workspace, in, n * 4) || ranges_overlap(workspace, s.workspace, out, n * 4))
             return QSIM_ERR_OVERLAP;
     }
-    const RngKey key = make_key(seed, stream_id, index0);
-    const int symmetric = (flags & QSIM_SYMMETRIC) ? 1 : 0;
-    hipStream_t stream = as_stream(hip_stream);
-    switch (rounding) {
-    case QSIM_RN_EVEN: return launch_block_mode<QSIM_RN_EVEN>(in, out, s, wl, symmetric, key, workspace, stream);
-    case QSIM_RN_AWAY: return launch_block_mode<QSIM_RN_AWAY>(in, out, s, wl, symmetric, key, workspace, stream);
-    case QSIM_RN_ZERO: return launch_block_mode<QSIM_RN_ZERO>(in, out, s, wl, symmetric, key, workspace, stream);
-    default:           return launch_block_mode<QSIM_STOCHASTIC>(in, out, s, wl, symmetric, key, workspace, stream);
-    }
+    return block_quantize_checked(in, out, n, s, index0, wl, rounding, flags, seed, stream_id, workspace, as_stream(hip_stream));
 }
 
 int qsim_block_max(const float* in, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner, uint32_t* block_max,
@@ -717,11 +803,12 @@ int qsim_block_max(const float* in, uint64_t n, uint64_t outer, uint64_t nblocks
     const SliceGeom sg = two_pass_geometry(s);
     uint32_t* partial = block_max;                       // one slice per block: pass 1 writes the result itself
     if (sg.slices > 1) {
-        const size_t need = (size_t)nblocks * sg.slices * sizeof(uint32_t);
+        // (behind the words a kept scratch holds for qsim_block_quantize, like every two-pass form)
+        const size_t need = s.partial_offset + (size_t)nblocks * sg.slices * sizeof(uint32_t);
         if (!workspace || !aligned16(workspace) || workspace_bytes < need) return QSIM_ERR_WORKSPACE;
         if (ranges_overlap(workspace, need, in, n * 4) || ranges_overlap(workspace, need, block_max, nblocks * sizeof(uint32_t)))
             return QSIM_ERR_OVERLAP;
-        partial = static_cast<uint32_t*>(workspace);
+        partial = reinterpret_cast<uint32_t*>(static_cast<unsigned char*>(workspace) + s.partial_offset);
     }
     hipStream_t stream = as_stream(hip_stream);
     const dim3 grid = folded_xz(nblocks, sg.slices);
@@ -842,12 +929,13 @@ int qsim_quant_sgd_step_at(float* w_master, float* w_q, const float* grad, float
     const unsigned blocks = (unsigned)(tiles < kGridX ? tiles : kGridX);       // the kernel strides over the tiles
     const bool vec = aligned16(w_master) && aligned16(grad) && aligned16(mom) && (!w_q || aligned16(w_q));
     const SgdHyper h = make_hyper(lr, momentum, options);
+    hipStream_t stream = as_stream(hip_stream);
     if (vec)
-        hipLaunchKernelGGL((sgd_step_kernel<true>), dim3(blocks), dim3(kThreads), 0, as_stream(hip_stream), u32(w_master),
-                           u32(w_q), u32(grad), u32(mom), n, tiles, h, fg, fm, fw, key);
+        hipLaunchKernelGGL((sgd_step_kernel<true>), dim3(blocks), dim3(kThreads), 0, stream, u32(w_master), u32(w_q), u32(grad),
+                           u32(mom), n, tiles, h, fg, fm, fw, key);
     else
-        hipLaunchKernelGGL((sgd_step_kernel<false>), dim3(blocks), dim3(kThreads), 0, as_stream(hip_stream), u32(w_master),
-                           u32(w_q), u32(grad), u32(mom), n, tiles, h, fg, fm, fw, key);
+        hipLaunchKernelGGL((sgd_step_kernel<false>), dim3(blocks), dim3(kThreads), 0, stream, u32(w_master), u32(w_q), u32(grad),
+                           u32(mom), n, tiles, h, fg, fm, fw, key);
     return launch_status();
 }
 
@@ -870,6 +958,7 @@ int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* co
         if (status != QSIM_OK) return status;
     }
     const SgdHyper h = make_hyper(lr, momentum, options);
+    hipStream_t stream = as_stream(hip_stream);
     // one launch per batch of up to kMultiTensors consecutive non-empty tensors (fewer than 2^31
     // tiles); entry c of a batch is tensor first + c, which is what the kernel adds to the stream
     int t = 0;
@@ -908,12 +997,8 @@ int qsim_quant_sgd_step_multi_ex(int ntensors, float* const* w_master, float* co
             continue;
         }
         const RngKey key = make_key(seed, stream_id + (uint32_t)first, 0);
-        if (vec)
-            hipLaunchKernelGGL((sgd_multi_kernel<true>), folded(tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
-                               fg, fm, fw, key);
-        else
-            hipLaunchKernelGGL((sgd_multi_kernel<false>), folded(tiles), dim3(kThreads), 0, as_stream(hip_stream), tab, h,
-                               fg, fm, fw, key);
+        if (vec) hipLaunchKernelGGL((sgd_multi_kernel<true>), folded(tiles), dim3(kThreads), 0, stream, tab, h, fg, fm, fw, key);
+        else hipLaunchKernelGGL((sgd_multi_kernel<false>), folded(tiles), dim3(kThreads), 0, stream, tab, h, fg, fm, fw, key);
         if (hipGetLastError() != hipSuccess) return QSIM_ERR_LAUNCH;
     }
     return QSIM_OK;
@@ -986,8 +1071,9 @@ int qsim_sgd_table_build(int ntensors, float* const* w_master, float* const* w_q
         ++c;
     }
     // the host copy lives only until this function returns, so the copy is waited for
-    if (hipMemcpyAsync(table_device, host.data(), need, hipMemcpyHostToDevice, as_stream(hip_stream)) != hipSuccess ||
-        hipStreamSynchronize(as_stream(hip_stream)) != hipSuccess) {
+    hipStream_t stream = as_stream(hip_stream);
+    if (hipMemcpyAsync(table_device, host.data(), need, hipMemcpyHostToDevice, stream) != hipSuccess ||
+        hipStreamSynchronize(stream) != hipSuccess) {
         (void)hipGetLastError();
         return QSIM_ERR_LAUNCH;
     }
@@ -1019,12 +1105,13 @@ int qsim_quant_sgd_step_table(const qsim_sgd_table* table, float lr, float momen
     const SgdTableEntry* entries = static_cast<const SgdTableEntry*>(table->device);
     const uint32_t* owner =
         reinterpret_cast<const uint32_t*>(static_cast<const unsigned char*>(table->device) + table_owner_offset(table->count));
+    hipStream_t stream = as_stream(hip_stream);
     if (table->aligned)
-        hipLaunchKernelGGL((sgd_table_kernel<true>), folded(table->tiles), dim3(kThreads), 0, as_stream(hip_stream), entries,
-                           owner, table->tiles, h, fg, fm, fw, key);
+        hipLaunchKernelGGL((sgd_table_kernel<true>), folded(table->tiles), dim3(kThreads), 0, stream, entries, owner, table->tiles, h,
+                           fg, fm, fw, key);
     else
-        hipLaunchKernelGGL((sgd_table_kernel<false>), folded(table->tiles), dim3(kThreads), 0, as_stream(hip_stream), entries,
-                           owner, table->tiles, h, fg, fm, fw, key);
+        hipLaunchKernelGGL((sgd_table_kernel<false>), folded(table->tiles), dim3(kThreads), 0, stream, entries, owner, table->tiles, h,
+                           fg, fm, fw, key);
     return launch_status();
 }
 

@@ -8,72 +8,226 @@
 
 namespace qsim {
 
-// Single pass for contiguous blocks that fit in the register files of the whole chip (for instance
-// a 4096 x 4096 tensor quantized as one block).  The grid is small enough for every workgroup to be
-// resident at the same time; each loads its slice of 256 * GPT groups into registers, publishes the
-// slice's maximum, waits until all workgroups have arrived, folds the maxima of its block and
-// quantizes out of registers: HBM sees each element once in and once out.
+// ---------------------------------------------------------------------------------------------
+// The meeting.  The workgroups that hold the slices of one block each know the largest magnitude of
+// their slice and need the largest of the block.  They count themselves into counters that carry the
+// running maximum along; the last to arrive publishes the block's maximum in flags the others poll.
 //
-// Scratch layout (zeroed by block_sync_clear_kernel before the launch; every counter and flag has
-// a 64-byte line to itself):
-//   sync[0]                              arrivals of whole groups of 32 workgroups
-//   sync[16 * (1 + c)],   c < 32         "everyone has arrived" flag, 32 copies
-//   sync[16 * (33 + g)],  g < 128        arrivals inside group g = workgroup / 32
-//   sync[kSyncSlots0 + w]                slot of workgroup w: its maximum with the top bit set as a
-//                                        "published" mark (magnitude encodings have that bit clear)
-// Arrival is two-level and the wait polls one of 32 flag copies, so no address sees more than a
-// few dozen device-scope operations: a single counter polled by a thousand workgroups serialises
-// at its memory channel and costs far more than the kernel's whole memory traffic.
+// Scratch: 64-bit words of device memory.  All communication is through relaxed device-scope
+// atomics on words only atomics touch: nothing else has to become visible between workgroups, so no
+// release or acquire fence (each of which writes back or invalidates a whole L2 on this multi-die
+// part) is needed; order is kept by waiting for the returned value of one atomic before the next one
+// is issued.  The words (`stride` apart, 16 = a 128-byte line each while they are few, so that no
+// address sees more than a few dozen operations: a single word polled by a thousand workgroups
+// serialises at its memory channel and costs more than the kernel's whole memory traffic):
+//   word 0                                      workgroups that gave up waiting (statistics only)
+//   word 1                                      the epoch: number of the last launch that met here
+//   word 2                                      groups of 256 blocks whose meetings are over
+//   counters (must be zero when a launch starts, and are zero again when it ends)
+//     counter of group q = b * groups + s / 32  low half: largest magnitude so far; high half: arrivals.
+//                                               A workgroup first folds its maximum in, waits for that
+//                                               to be done, then counts itself; so the one that counts
+//                                               last reads the group's final maximum with its count,
+//                                               and puts the counter back to zero.
+//     top counter of block b                    the same over the groups of a block (groups > 1)
+//     blocks whose meetings are over            one word per 256 blocks
+//   tagged words (count only when their high half is this launch's tag = epoch + 1; never cleaned)
+//     flag of group q                           tag << 32 | published | the block's maximum: written by
+//                                               the last arrival of the block, polled by the group
+//     slot of workgroup w                       tag << 32 | published | its maximum: read only by a
+//                                               workgroup whose wait ran out
+// Every workgroup reads the epoch before anything else; the last arrival of the last block, which
+// knows that everybody has read it, stores the new one.  So a scratch that is all zero before its
+// first launch stays usable launch after launch, also when a launch is replayed from a graph, and
+// whichever of the forms in this file a launch takes (the counters of all of them lie before the
+// tagged words of any, see MeetGeom::tagged).
 //
 // The wait is bounded in time.  A workgroup whose wait runs out (the device is shared with other
-// work, so not every workgroup got a slot) still produces the right result: for every slot of its block that is not yet published
-// it computes the slice's maximum from memory itself.  That is safe even in place, because a
-// workgroup writes its output only after its own wait, which starts after it has published; so if
-// the slot is still unpublished after the read, the read saw nothing but input.
-constexpr uint32_t kSyncFlagCopies = 32;
-constexpr uint32_t kSyncGroup = 32;                // workgroups per first-level counter
-constexpr uint32_t kSyncMaxGroups = 128;
-constexpr uint32_t kSyncSlots0 = 16 * (1 + kSyncFlagCopies + kSyncMaxGroups);
+// work, so not every workgroup of the block got a place) still produces the right result: for every
+// slot of its block that is not published it computes the slice's maximum from memory itself.  That
+// is safe even in place, because a workgroup writes its output only after its own wait, which starts
+// after it has published; so if the slot is still unpublished after the read, the read saw nothing
+// but input.
+// ---------------------------------------------------------------------------------------------
 constexpr uint32_t kPublished = 0x80000000u;
+constexpr uint32_t kMeetGroup = 32;              // workgroups per first-level counter
+constexpr uint32_t kMeetHeaderWords = 16;        // words 0..2 as above, the rest of the line unused
+constexpr uint32_t kMeetLine = 16;               // 64-bit words of a 128-byte line
+constexpr uint32_t kMeetBlocksPerWord = 256;     // blocks counted into one "meetings over" word
 
-__global__ void block_sync_clear_kernel(uint32_t* sync, uint32_t words)
-{
-    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < words) sync[i] = 0u;
-}
-
-struct ResidentGeom {
-    SliceGeom sg;            // slice_len = 1024 * GPT elements; slices = workgroups per block
-    uint32_t total_wgs;      // nblocks * slices
-    uint32_t wait_us;        // microseconds a workgroup waits for the others before the fallback
+struct MeetGeom {
+    uint64_t nblocks;
+    uint32_t slices;        // workgroups per block
+    uint32_t groups;        // first-level counters per block: ceil(slices / kMeetGroup)
+    uint32_t stride;        // words from one counter or flag to the next
+    uint32_t wait_us;       // how long a workgroup waits for the others before it helps itself
+    uint64_t counters, tops, finished;     // first word of each kind of counter
+    uint64_t flags, slots;                 // first word of each kind of tagged word; flags == the first tagged word
 };
 
+// Zeroes the scratch of a launch whose caller does not keep it between calls.
+__global__ void block_sync_clear_kernel(uint64_t* sync, uint64_t words)
+{
+    const uint64_t i = linear_block() * blockDim.x + threadIdx.x;
+    if (i < words) sync[i] = 0ull;
+}
+
+// Tag of this launch's meetings; to be read before the workgroup does anything else.  (An ordinary,
+// cached load: the word was written by an earlier launch, and no workgroup of this one reads it
+// after this launch's only write to it, which waits for all of them to have arrived.)
+__device__ __forceinline__ uint32_t meet_tag(const uint64_t* scratch)
+{
+    const uint32_t next = (uint32_t)__hip_atomic_load(&scratch[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) + 1u;
+    return next == 0u ? 1u : next;       // (zero is what an unused word holds)
+}
+
+// Workgroup s of block b brings the maximum m of its slice and gets the block's maximum back.
+// `tag` is meet_tag() as thread 0 read it (the other threads' value is not used); slice_max(i) gives
+// each thread's share of the maximum of slice i of the block, from memory.  Called by every thread.
+// `last_of_block` comes back true in thread 0 of the workgroup that arrived last: it owes a call of
+// meet_is_over(), which may wait until the workgroup's own stores are on their way.
+template <class SliceMax>
+__device__ __forceinline__ uint32_t meet_in_block(uint64_t* scratch, const MeetGeom& mg, uint64_t b, uint32_t s, uint32_t tag,
+                                                  uint32_t m, uint32_t* lds, uint32_t& shared_word, bool& last_of_block,
+                                                  SliceMax slice_max)
+{
+    uint64_t* slots = scratch + mg.slots + b * mg.slices;
+    last_of_block = false;
+    if (threadIdx.x == 0) {
+        const uint64_t mark = ((uint64_t)tag << 32) | kPublished;
+        const uint32_t gi = s / kMeetGroup;
+        const uint64_t q = b * mg.groups + gi;
+        const uint32_t members = mg.slices - gi * kMeetGroup < kMeetGroup ? mg.slices - gi * kMeetGroup : kMeetGroup;
+        uint64_t* counter = scratch + mg.counters + q * mg.stride;
+        __hip_atomic_store(&slots[s], mark | m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        uint32_t before = __hip_atomic_fetch_max(reinterpret_cast<uint32_t*>(counter), m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(before) : : "memory");      // slot written, maximum folded in: now count
+        const uint64_t r = __hip_atomic_fetch_add(counter, 1ull << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((uint32_t)(r >> 32) == members - 1u) {
+            // last of the group: everybody's maximum was in before they counted themselves
+            uint32_t bm = (uint32_t)r;
+            bool last = true;
+            __hip_atomic_store(counter, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (mg.groups > 1u) {
+                uint64_t* top = scratch + mg.tops + b * mg.stride;
+                uint32_t before2 = __hip_atomic_fetch_max(reinterpret_cast<uint32_t*>(top), bm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                asm volatile("s_waitcnt vmcnt(0)" : "+v"(before2) : : "memory");
+                const uint64_t r2 = __hip_atomic_fetch_add(top, 1ull << 32, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                last = (uint32_t)(r2 >> 32) == mg.groups - 1u;
+                bm = (uint32_t)r2;
+                if (last) __hip_atomic_store(top, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (last) {
+                for (uint32_t i = 0; i < mg.groups; ++i)
+                    __hip_atomic_store(&scratch[mg.flags + (b * mg.groups + i) * mg.stride], mark | bm, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                last_of_block = true;
+            }
+        }
+        const uint64_t* flag = scratch + mg.flags + q * mg.stride;
+        const uint64_t start = __builtin_amdgcn_s_memrealtime();          // 100 MHz
+        const uint64_t budget = (uint64_t)mg.wait_us * 100u;
+        uint64_t a = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        while ((uint32_t)(a >> 32) != tag && __builtin_amdgcn_s_memrealtime() - start < budget) {
+            __builtin_amdgcn_s_sleep(1);
+            a = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        shared_word = (uint32_t)(a >> 32) == tag ? (uint32_t)a : 0u;        // a valid flag has the published bit
+    }
+    __syncthreads();
+    if (shared_word & kPublished) return shared_word & ~kPublished;
+
+    // the wait ran out
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(reinterpret_cast<uint32_t*>(scratch), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t bm = 0;
+    for (uint32_t i = 0; i < mg.slices; ++i) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint64_t a = __hip_atomic_load(&slots[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            shared_word = (uint32_t)(a >> 32) == tag ? (uint32_t)a : 0u;
+        }
+        __syncthreads();
+        uint32_t a = shared_word;
+        if (!(a & kPublished)) {
+            // the owner of slice i has not published, so it has not written any output yet:
+            // read its input; if the slot is still unpublished afterwards, the read was clean
+            const uint32_t own = workgroup_max(slice_max(i), lds);
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                const uint64_t again = __hip_atomic_load(&slots[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                shared_word = (uint32_t)(again >> 32) == tag ? (uint32_t)again : 0u;
+            }
+            __syncthreads();
+            a = (shared_word & kPublished) ? shared_word : own;
+        }
+        a &= ~kPublished;
+        bm = bm > a ? bm : a;
+    }
+    return bm;
+}
+
+// The last arrival of block b reports that the block's meeting is over (thread 0 only); the one that
+// reports the last block of the launch moves the epoch on, when every workgroup of the launch has
+// arrived and therefore read it.
+__device__ __forceinline__ void meet_is_over(uint64_t* scratch, const MeetGeom& mg, uint64_t b, uint32_t tag)
+{
+    bool all = mg.nblocks == 1;
+    if (!all) {
+        const uint64_t w = b / kMeetBlocksPerWord;
+        const uint64_t here = mg.nblocks - w * kMeetBlocksPerWord < kMeetBlocksPerWord ? mg.nblocks - w * kMeetBlocksPerWord
+                                                                                         : kMeetBlocksPerWord;
+        uint64_t* word = scratch + mg.finished + w;
+        if (__hip_atomic_fetch_add(word, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == here - 1u) {
+            __hip_atomic_store(word, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t words = (mg.nblocks + kMeetBlocksPerWord - 1) / kMeetBlocksPerWord;
+            if (__hip_atomic_fetch_add(&scratch[2], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == words - 1u) {
+                __hip_atomic_store(&scratch[2], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                all = true;
+            }
+        }
+    }
+    if (all) __hip_atomic_store(&scratch[1], (uint64_t)tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Single pass for contiguous blocks that fit in the register files of the whole chip (for instance
+// a 4096 x 4096 tensor quantized as one block).  The grid is small enough for every workgroup to be
+// resident at the same time; each loads its slice of 256 * GPT groups into registers, brings the
+// slice's maximum to the meeting of its block, and quantizes out of registers: HBM sees each element
+// once in and once out.
+//
 // With 16 groups per thread the kernel must keep to 128 VGPRs (four waves per SIMD, four workgroups
 // per CU): that is what lets 1024 workgroups hold a 16 Mi-element tensor.
 //
-// CLUSTER: the tensor as a whole does not fit, but each block does (at most 64 slices), and the
-// grid may be far larger than the chip.  Only the workgroups of one block meet: each publishes its
-// slot and polls the slots of its block (one lane per slot) instead of the counters and flags.
-// Workgroups are numbered block by block and dispatched in that order, so the workgroups of the
-// lowest unfinished block are always among the resident ones and the grid drains block after
-// block; should the dispatcher ever do otherwise, the bounded wait and the exact fallback below
-// still end every workgroup with the right result.
+// CLUSTER: the tensor as a whole does not fit, but each block does, and the grid may be far larger
+// than the chip.  Workgroups are numbered block by block and dispatched in that order, so the
+// workgroups of the lowest unfinished block are always among the resident ones and the grid drains
+// block after block; should the dispatcher ever do otherwise, the bounded wait and the exact
+// fallback still end every workgroup with the right result.
+struct ResidentGeom {
+    SliceGeom sg;            // slice_len = 1024 * GPT elements; slices = workgroups per block
+    uint32_t total_wgs;      // nblocks * slices
+    MeetGeom meet;
+};
+
 template <int MODE, int GPT, bool CLUSTER = false>
-__global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_kernel(const uint32_t* in, uint32_t* out, uint32_t* sync,
+__global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
                                                                   ResidentGeom rg, int wl, int symmetric, RngKey key)
 {
     // Stochastic rounding: the random words of the first PRE groups are drawn while the loads are
-    // in flight and parked in LDS (36 KiB at most, so four workgroups still share a CU); after the
-    // wait only the remaining groups pay for Philox, and the arithmetic hides behind the stores.
+    // in flight and parked in LDS (36 KiB at most, so four workgroups still share a CU), those of
+    // HELD more groups stay in registers; after the wait only the remaining groups pay for Philox,
+    // and the arithmetic hides behind the stores.
     constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 9 ? GPT : 9) : 0;
+    constexpr int HELD = MODE == QSIM_STOCHASTIC && GPT >= 16 ? 1 : 0;
     __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
     __shared__ uint32_t lds[kThreads / 64];
     __shared__ uint32_t shared_word;
     const uint32_t wg = CLUSTER ? (uint32_t)linear_block() : blockIdx.x;
     if (CLUSTER && wg >= rg.total_wgs) return;                   // the whole workgroup leaves together
     const uint32_t b = wg / rg.sg.slices, s = wg - b * rg.sg.slices;
+    uint32_t tag = 0;
+    if (threadIdx.x == 0) tag = meet_tag(scratch);
     const SliceView sv = slice_view(rg.sg, b, s);
-    uint32_t* slots = sync + kSyncSlots0;
 
     // the slice is addressed from a wave-uniform base with small per-thread offsets, which keeps
     // the address arithmetic out of the vector registers that hold the data
@@ -104,6 +258,13 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
         const Words4 r = random_words(sv.j0 + (uint64_t)((int)threadIdx.x + k * kThreads), key, 0u);
         parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
     }
+    Words4 held[HELD > 0 ? HELD : 1];
+#pragma unroll
+    for (int k = 0; k < HELD; ++k) {
+        held[k] = random_words(sv.j0 + (uint64_t)((int)threadIdx.x + (PRE + k) * kThreads), key, 0u);
+        // (pinned here: left alone, the compiler sinks the computation below the wait to save registers)
+        asm volatile("" : "+v"(held[k].w[0]), "+v"(held[k].w[1]), "+v"(held[k].w[2]), "+v"(held[k].w[3]));
+    }
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t gm = max4_mag(v[k]);
@@ -111,81 +272,9 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
     }
     m = workgroup_max(m, lds);
 
-    // All communication is through relaxed device-scope atomics on words that only atomics touch:
-    // nothing else has to become visible between workgroups, so no release or acquire fence (each
-    // of which writes back or invalidates a whole L2 on this multi-die part) is needed.  Order is
-    // kept by waiting for the returned value of one atomic before the next one is issued.
-    if (CLUSTER) {
-        if (threadIdx.x == 0) {
-            uint32_t old = __hip_atomic_exchange(&slots[wg], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
-        }
-        if (threadIdx.x < 64) {
-            // the first wavefront polls: lane i watches slot i of the block (slices <= 64)
-            const uint32_t* watched = slots + (uint64_t)b * rg.sg.slices + (threadIdx.x < rg.sg.slices ? threadIdx.x : 0u);
-            const uint64_t t0 = __builtin_amdgcn_s_memrealtime();        // 100 MHz
-            const uint64_t budget = (uint64_t)rg.wait_us * 100u;
-            bool all = __all((__hip_atomic_load(watched, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kPublished) != 0u);
-            while (!all && __builtin_amdgcn_s_memrealtime() - t0 < budget) {
-                __builtin_amdgcn_s_sleep(2);
-                all = __all((__hip_atomic_load(watched, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kPublished) != 0u);
-            }
-            if (threadIdx.x == 0) shared_word = all ? 1u : 0u;
-        }
-    } else if (threadIdx.x == 0) {
-        uint32_t old = __hip_atomic_exchange(&slots[wg], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");       // the slot is published before we count
-        const uint32_t group = wg / kSyncGroup;
-        const uint32_t ngroups_sync = (rg.total_wgs + kSyncGroup - 1) / kSyncGroup;
-        const uint32_t in_group = (group + 1 == ngroups_sync) ? rg.total_wgs - group * kSyncGroup : kSyncGroup;
-        uint32_t* flags = sync + 16;
-        if (__hip_atomic_fetch_add(&sync[16 * (1 + kSyncFlagCopies + group)], 1u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT) == in_group - 1u) {
-            if (__hip_atomic_fetch_add(&sync[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == ngroups_sync - 1u) {
-                for (uint32_t c = 0; c < kSyncFlagCopies; ++c)
-                    __hip_atomic_store(&flags[16 * c], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        const uint32_t* my_flag = &flags[16 * (wg % kSyncFlagCopies)];
-        const uint64_t t0 = __builtin_amdgcn_s_memrealtime();            // 100 MHz
-        const uint64_t budget = (uint64_t)rg.wait_us * 100u;
-        bool all = __hip_atomic_load(my_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
-        while (!all && __builtin_amdgcn_s_memrealtime() - t0 < budget) {
-            __builtin_amdgcn_s_sleep(2);
-            all = __hip_atomic_load(my_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
-        }
-        shared_word = all ? 1u : 0u;
-    }
-    __syncthreads();
-    const bool all_arrived = shared_word != 0u;
-
-    uint32_t bm = 0;
-    uint32_t* mine = slots + (uint64_t)b * rg.sg.slices;
-    if (all_arrived) {
-        for (uint32_t i = threadIdx.x; i < rg.sg.slices; i += kThreads) {
-            const uint32_t a = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ~kPublished;
-            bm = bm > a ? bm : a;
-        }
-        bm = workgroup_max(bm, lds);
-    } else {
-        for (uint32_t i = 0; i < rg.sg.slices; ++i) {
-            __syncthreads();
-            if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            uint32_t a = shared_word;
-            if (!(a & kPublished)) {
-                // the owner of slice i has not published, so it has not written any output yet:
-                // read its input; if the slot is still unpublished afterwards, the read was clean
-                const uint32_t own = workgroup_max(slice_max(in, slice_view(rg.sg, b, i)), lds);
-                __syncthreads();
-                if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __syncthreads();
-                a = (shared_word & kPublished) ? shared_word : own;
-            }
-            a &= ~kPublished;
-            bm = bm > a ? bm : a;
-        }
-    }
+    bool last_of_block;
+    const uint32_t bm = meet_in_block(scratch, rg.meet, b, s, tag, m, lds, shared_word, last_of_block,
+                                      [&](uint32_t i) { return slice_max_frugal(in, slice_view(rg.sg, b, i)); });
 
     const GridPlan p = block_plan(bm, wl, symmetric);
 #pragma unroll
@@ -196,6 +285,8 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
             if (k < PRE) {
                 const uint4 w = parked[k * kThreads + threadIdx.x];
                 r = Words4{{w.x, w.y, w.z, w.w}};
+            } else if (k < PRE + HELD) {
+                r = held[k - PRE < 0 ? 0 : k - PRE];
             } else if (MODE == QSIM_STOCHASTIC) {
                 r = random_words(sv.j0 + (uint64_t)t, key, 0u);
             }
@@ -204,66 +295,7 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
             else store_group<true>(sout, (uint64_t)t, slice_end, o);
         }
     }
-}
-
-// The meeting of the workgroups of one block, as in the kernel above: workgroup s publishes its
-// maximum m in slot s of the block's `slices` slots (zeroed before the launch) and gets the block's
-// maximum back.  The first wavefront polls, every lane up to slices / 64 slots, for at most wait_us;
-// when that runs out, every slot still unpublished is recomputed from memory with
-// slice_max(i), each thread's share of the maximum of slice i (safe for the reason given above).
-// Called by every thread of the workgroup.
-template <class SliceMax>
-__device__ __forceinline__ uint32_t meet_in_block(uint32_t* mine, uint32_t s, uint32_t slices, uint32_t m, uint32_t wait_us,
-                                                  uint32_t* lds, uint32_t& shared_word, SliceMax slice_max)
-{
-    // relaxed device-scope atomics on words only atomics touch; order by waiting for returned values
-    if (threadIdx.x == 0) {
-        uint32_t old = __hip_atomic_exchange(&mine[s], m | kPublished, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" : "+v"(old) : : "memory");
-    }
-    if (threadIdx.x < 64) {
-        const uint64_t start = __builtin_amdgcn_s_memrealtime();     // 100 MHz
-        const uint64_t budget = (uint64_t)wait_us * 100u;
-        bool all;
-        for (;;) {
-            bool ok = true;
-            for (uint32_t i = threadIdx.x; i < slices; i += 64u)
-                ok = ok && (__hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & kPublished) != 0u;
-            all = __all(ok);
-            if (all || __builtin_amdgcn_s_memrealtime() - start >= budget) break;
-            __builtin_amdgcn_s_sleep(2);
-        }
-        if (threadIdx.x == 0) shared_word = all ? 1u : 0u;
-    }
-    __syncthreads();
-    const bool all_arrived = shared_word != 0u;
-
-    uint32_t bm = 0;
-    if (all_arrived) {
-        for (uint32_t i = threadIdx.x; i < slices; i += kThreads) {
-            const uint32_t a = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & ~kPublished;
-            bm = bm > a ? bm : a;
-        }
-        return workgroup_max(bm, lds);
-    }
-    for (uint32_t i = 0; i < slices; ++i) {
-        __syncthreads();
-        if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        uint32_t a = shared_word;
-        if (!(a & kPublished)) {
-            // the owner of slice i has not published, so it has not written any output yet:
-            // read its input; if the slot is still unpublished afterwards, the read was clean
-            const uint32_t own = workgroup_max(slice_max(i), lds);
-            __syncthreads();
-            if (threadIdx.x == 0) shared_word = __hip_atomic_load(&mine[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __syncthreads();
-            a = (shared_word & kPublished) ? shared_word : own;
-        }
-        a &= ~kPublished;
-        bm = bm > a ? bm : a;
-    }
-    return bm;
+    if (last_of_block) meet_is_over(scratch, rg.meet, b, tag);
 }
 
 // The same block-by-block single pass for blocks along an inner dimension (outer > 1) made of
@@ -271,8 +303,7 @@ __device__ __forceinline__ uint32_t meet_in_block(uint32_t* mine, uint32_t s, ui
 // [N, C, H, W] tensor.  Slice s of block b is elements [s * 16384, ...) of the block's own
 // numbering t = o * inner + i; a group's place in the array follows from one division by `inner`
 // (multiply-high with a reciprocal rounded up, corrected by at most one).  Up to 256 slices per
-// block; every lane of the polling wavefront watches up to four slots.  `slots`: one word per
-// workgroup, zeroed before the launch.
+// block, which meet as above (counters, flags and epochs packed, one word after the other).
 constexpr uint32_t kStridedSliceLen = 4u * kThreads * 16u;
 constexpr uint32_t kStridedMaxSlices = 256;
 
@@ -283,7 +314,7 @@ struct StridedClusterGeom {
     uint32_t inner;          // a multiple of 4, at least 64
     uint32_t magic_inner;    // floor(2^32 / inner) + 1
     uint32_t total_wgs;
-    uint32_t wait_us;
+    MeetGeom meet;
 };
 
 // Group number, in the array, of the group at element tt (a multiple of 4) of block b.
@@ -306,7 +337,7 @@ __device__ __forceinline__ uint32_t strided_slice_groups(const StridedClusterGeo
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(const uint32_t* in, uint32_t* out, uint32_t* slots,
+__global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
                                                                             StridedClusterGeom cg, int wl, int symmetric,
                                                                             RngKey key)
 {
@@ -318,6 +349,8 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     const uint32_t wg = (uint32_t)linear_block();
     if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
     const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
+    uint32_t tag = 0;
+    if (threadIdx.x == 0) tag = meet_tag(scratch);
     const uint32_t t0 = s * kStridedSliceLen;
     const uint32_t ngroups = strided_slice_groups(cg, s);
 
@@ -343,8 +376,8 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     }
     m = workgroup_max(m, lds);
 
-    uint32_t* mine = slots + (uint64_t)b * cg.slices;
-    const uint32_t bm = meet_in_block(mine, s, cg.slices, m, cg.wait_us, lds, shared_word, [&](uint32_t i) {
+    bool last_of_block;
+    const uint32_t bm = meet_in_block(scratch, cg.meet, b, s, tag, m, lds, shared_word, last_of_block, [&](uint32_t i) {
         uint32_t own = 0;
         const uint32_t count = strided_slice_groups(cg, i);
         for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
@@ -371,6 +404,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
             __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + j);
         }
     }
+    if (last_of_block) meet_is_over(scratch, cg.meet, b, tag);
 }
 
 // The same for segments of any length from 64 elements at any alignment (inner % 4 != 0, or arrays
@@ -393,7 +427,7 @@ struct RaggedClusterGeom {
     uint32_t slices;         // ceil(block_groups / 4096)
     uint32_t slice_groups;   // ceil(block_groups / slices): the slots are dealt out evenly
     uint32_t total_wgs;
-    uint32_t wait_us;
+    MeetGeom meet;
 };
 
 constexpr uint32_t kRaggedSliceGroups = kThreads * 16u;
@@ -436,7 +470,7 @@ __device__ __forceinline__ uint4 keep_masked(const uint4& v, uint32_t mask)
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const uint32_t* in, uint32_t* out, uint32_t* slots,
+__global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
                                                                            RaggedClusterGeom cg, int wl, int symmetric,
                                                                            RngKey key)
 {
@@ -448,6 +482,8 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     const uint32_t wg = (uint32_t)linear_block();
     if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
     const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
+    uint32_t tag = 0;
+    if (threadIdx.x == 0) tag = meet_tag(scratch);
     const uint32_t t0 = s * cg.slice_groups;
     const uint32_t nslots = ragged_slice_slots(cg, s);
     const bool short_tail = (cg.n & 3u) != 0u;                     // the array's last group is not whole
@@ -495,8 +531,8 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     }
     m = workgroup_max(m, lds);
 
-    uint32_t* mine = slots + (uint64_t)b * cg.slices;
-    const uint32_t bm = meet_in_block(mine, s, cg.slices, m, cg.wait_us, lds, shared_word, [&](uint32_t i) {
+    bool last_of_block;
+    const uint32_t bm = meet_in_block(scratch, cg.meet, b, s, tag, m, lds, shared_word, last_of_block, [&](uint32_t i) {
         // slice i of this block from memory, element by element where a group is shared
         uint32_t own = 0;
         const uint32_t count = ragged_slice_slots(cg, i);
@@ -547,6 +583,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
             }
         }
     }
+    if (last_of_block) meet_is_over(scratch, cg.meet, b, tag);
 }
 
 // Blocks along an inner dimension that are SHORT (outer * inner <= 2048 elements, inner % 4 == 0,

@@ -561,6 +561,18 @@ __device__ __forceinline__ uint32_t slice_max(const uint32_t* in, const SliceVie
     return m;
 }
 
+// The same with one load in flight and few registers: for the rarely taken paths of kernels that
+// hold a slice of their own in registers meanwhile.
+__device__ __forceinline__ uint32_t slice_max_frugal(const uint32_t* in, const SliceView& sv)
+{
+    uint32_t m = 0;
+    for (uint64_t t = threadIdx.x; t < sv.groups; t += kThreads) {
+        const uint32_t gm = max4_mag(load_group<false>(in, sv.j0 + t, sv.end));
+        m = m > gm ? m : gm;
+    }
+    return m;
+}
+
 __global__ __launch_bounds__(kThreads) void block_slice_max_kernel(const uint32_t* in, uint32_t* partial, SliceGeom sg)
 {
     __shared__ uint32_t lds[kThreads / 64];

@@ -17,6 +17,8 @@ constexpr uint64_t kMaxElements = 1ull << 38;   // keeps every grid below 2^31 w
 inline bool valid_index0(uint64_t index0) { return index0 % 4 == 0 && index0 <= (1ull << 62); }
 inline bool valid_rounding(int r) { return r >= QSIM_RN_EVEN && r <= QSIM_STOCHASTIC; }
 inline bool valid_flags(uint32_t f) { return (f & ~(QSIM_SATURATE | QSIM_SUBNORMAL | QSIM_SYMMETRIC)) == 0; }
+// Block quantize also takes the flag that says whose the scratch is.
+inline bool valid_block_flags(uint32_t f) { return valid_flags(f & ~(uint32_t)QSIM_WORKSPACE_KEPT); }
 inline bool valid_fixed(int wl, int fl) { return wl >= 1 && wl <= 24 && fl >= wl - 128 && fl <= 149; }
 inline bool valid_float(int e, int m) { return e >= 2 && e <= 8 && m >= 1 && m <= 23; }
 inline bool valid_block_wl(int wl) { return wl >= 2 && wl <= 24; }

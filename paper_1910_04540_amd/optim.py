@@ -51,7 +51,7 @@ class _Group:
         self.momentum_buffers = [torch.zeros_like(p.data) for p in self.params]
         self.quantized = [torch.empty_like(p.data) for p in self.params] if weights == "master" else None
         self._list: Optional[Q.SgdTensorList] = None
-        self._grad_ptrs: Optional[list] = None
+        self._ptrs: Optional[list] = None
 
     def tensor_list(self) -> Q.SgdTensorList:
         grads = []
@@ -59,12 +59,18 @@ class _Group:
             if p.grad is None:
                 raise RuntimeError("every parameter needs a gradient (run backward() first)")
             grads.append(p.grad.contiguous())
-        ptrs = [g.data_ptr() for g in grads]
-        if self._list is None or ptrs != self._grad_ptrs:      # PyTorch handed out new gradient tensors
+        # the list (and its device table) holds addresses: of the gradients, which PyTorch may hand out
+        # anew, and of the parameters' storage, which `p.data = ...`, `model.float()` and the like replace
+        ptrs = [g.data_ptr() for g in grads] + [p.data.data_ptr() for p in self.params]
+        if self._list is None or ptrs != self._ptrs:
             data = [p.data for p in self.params]
+            for d, m in zip(data, self.momentum_buffers):
+                Q._device_f32(d, "parameter")
+                if d.numel() != m.numel() or d.device != m.device:
+                    raise RuntimeError("a parameter changed its size or device after the optimizer was built")
             w_q = self.quantized if self.weights == "master" else (data if self.weights == "in_place" else None)
             self._list = Q.SgdTensorList(data, grads, self.momentum_buffers, w_q)
-            self._grad_ptrs = ptrs
+            self._ptrs = ptrs
         return self._list
 
 

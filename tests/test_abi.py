@@ -81,6 +81,12 @@ def test_block_validation_without_gpu():
     assert B.block_workspace_bytes(4096 * 4096, 1, 4096, 4096) == 0                 # one workgroup per row
     assert B.block_workspace_bytes(0, 1, 1, 1) == 0
     assert B.block_workspace_bytes(7, 2, 2, 2) == 0                                 # invalid shape: nothing to do
+    # the flag that says the caller keeps the workspace belongs to block quantize alone
+    assert call(0, 1, 1, 1, flags=B.WORKSPACE_KEPT) == 0 and call(6, 1, 1, 6, flags=16) == 2
+    assert call(n, 1, 1, n, flags=B.WORKSPACE_KEPT) == 6                            # kept or not, it has to be there
+    assert L.qsim_fixed_quantize(FAKE, FAKE, 8, 8, 6, 0, B.WORKSPACE_KEPT, 0, 0, None) == 2
+    assert L.qsim_float_quantize(FAKE, FAKE, 8, 5, 2, 0, B.WORKSPACE_KEPT, 0, 0, None) == 2
+    assert L.qsim_block_quantize_with_max(FAKE, FAKE, 8, 1, 1, 8, 0, 8, 0, B.WORKSPACE_KEPT, 0, 0, FAKE + (1 << 20), None) == 2
 
 
 def test_sgd_validation_without_gpu():

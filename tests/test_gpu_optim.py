@@ -68,6 +68,36 @@ def test_three_steps_match_the_oracle(weights, new_grad_tensors):
     assert opt.steps == 3
 
 
+@pytest.mark.parametrize("weights", ["master", "in_place"])
+def test_parameter_storage_replaced_between_steps(weights):
+    """`p.data = ...` (what `model.float()` or a checkpoint load do) gives a parameter new storage: the
+    next step must update the new storage, not the one the device table was built for."""
+    params = [torch.nn.Parameter(torch.from_numpy(w).cuda()) for w, _ in _state(0)]
+    opt = QuantSGD(params, lr=0.05, momentum=0.9, grad_number=FloatingPoint(5, 2, subnormal=True),
+                   momentum_number=FixedPoint(16, 12), weight_number=BlockFloatingPoint(8), chunk=64, weights=weights, seed=5)
+    fg = R.Format(R.KIND_FLOAT, 5, 2, R.STOCHASTIC, R.SATURATE | R.SUBNORMAL)
+    fm = R.Format(R.KIND_FIXED, 16, 12, R.STOCHASTIC, R.SATURATE)
+    fw = R.Format(R.KIND_BLOCK, 8, 64, R.RN_EVEN, 0)
+    ref_w = [w.reshape(-1).copy() for w, _ in _state(0)]
+    ref_m = [np.zeros_like(w) for w in ref_w]
+    for step in range(3):
+        grads = [g for _, g in _state(step)]
+        for p, g in zip(params, grads):
+            p.grad = torch.from_numpy(g).cuda() if p.grad is None else p.grad.copy_(torch.from_numpy(g))
+        if step == 1:
+            old = [p.data for p in params]
+            for p in params:
+                p.data = p.data.clone()                      # new storage, same values
+        opt.step()
+        for t in range(len(SHAPES)):
+            w, _, m = R.quant_sgd_step(ref_w[t], grads[t], ref_m[t], 0.05, 0.9, fg, fm, fw, 5, step * len(SHAPES) + t,
+                                       want_wq=weights == "master", in_place_weights=weights == "in_place")
+            if step == 1:
+                assert_bit_equal(host(old[t]), ref_w[t], f"the storage parameter {t} left behind is untouched")
+            ref_w[t], ref_m[t] = w, m
+            assert_bit_equal(host(params[t].data), w, f"step {step}, weights of parameter {t}")
+
+
 def test_a_small_model_trains():
     """End to end through autograd: a linear least-squares model under stochastically rounded
     8-bit block weights and fixed-point gradients still reduces its loss."""

@@ -208,6 +208,9 @@ def test_float_every_exponent_and_dropped_bit_class(e, m, flags, rounding):
     ("float", 8, 7, RN_AWAY, 0),         # constant mask, flush with the fp32-denormal side path, no saturation
     ("fixed", 8, 6, STOCHASTIC, 1),      # fixed grid, saturating
     ("fixed", 12, 20, RN_ZERO, 0),       # fixed grid, open range
+    ("fixed", 16, 12, STOCHASTIC, 1),    # the momentum format of the optimizer workload
+    ("float", 5, 10, RN_EVEN, 0),        # the gradient workload's format with flags clear: flush to zero, open range
+    ("float", 5, 2, RN_EVEN, 3),         # the first workload's format with gradual underflow
 ])
 def test_exhaustive_all_fp32_encodings(kind, a, b, rounding, flags):
     """All 2^32 fp32 encodings (NaN and Inf included) through one format, against the oracle."""
@@ -539,6 +542,77 @@ def test_block_per_channel_single_pass_when_the_wait_runs_out():
         assert_bit_equal(host(d), want, "in place")
     finally:
         Q.set_barrier_wait_us(2000)
+
+
+KEPT_SHAPES = [(1, 1, 4096 * 4096), (1, 3, 2000000), (1, 300, 70000), (64, 96, 3136), (128, 6, 729), (40, 64, 3025)]
+
+
+@pytest.mark.parametrize("shape", KEPT_SHAPES)
+def test_block_single_pass_with_a_kept_workspace(shape):
+    """A caller keeps one zero-filled workspace for the calls of a shape and says so
+    (QSIM_WORKSPACE_KEPT): no clearing launch, and call after call on new data, with either
+    rounding, in place or not, aligned or one element off (which takes another single-pass form on
+    the same workspace), stays exact; no workgroup ever gives up waiting on the idle GPU."""
+    outer, nblocks, inner = shape
+    n = outer * nblocks * inner
+    ws = torch.zeros(Q.block_workspace_bytes(n, outer, nblocks, inner), dtype=torch.uint8, device="cuda")
+    pad = torch.zeros(n + 8, device="cuda")
+    for call, (seed, mode, off, in_place) in enumerate([(1, RN_EVEN, 0, False), (2, STOCHASTIC, 0, True), (3, STOCHASTIC, 1, False),
+                                                        (4, RN_EVEN, 0, False), (5, STOCHASTIC, 3, True), (6, STOCHASTIC, 0, False)]):
+        x = W.lognormal_gradients((n,), seed=seed)
+        x[(seed * 7919) % n] = np.float32(3.0e5 * seed)             # the block maximum moves from call to call
+        want = R.block_quantize(x, outer, nblocks, inner, 8, mode, 0, 77, call)
+        view = pad[off:off + n]
+        view.copy_(torch.from_numpy(x))
+        out = view if in_place else torch.empty_like(view)
+        Q.block_quantize(view, outer, nblocks, inner, 8, mode, Q.WORKSPACE_KEPT, 77, call, out=out, workspace=ws)
+        assert_bit_equal(host(out), want, f"{shape} call {call}")
+    assert Q.workspace_timeouts(ws) == 0
+
+
+@pytest.mark.parametrize("shape", KEPT_SHAPES[:5])
+def test_block_kept_workspace_survives_waits_that_run_out(shape):
+    """With the wait forced to zero the workgroups help themselves (and are counted); the kept
+    workspace is as usable afterwards as before."""
+    outer, nblocks, inner = shape
+    n = outer * nblocks * inner
+    ws = torch.zeros(Q.block_workspace_bytes(n, outer, nblocks, inner), dtype=torch.uint8, device="cuda")
+    x = W.lognormal_gradients((n,), seed=21)
+    d = dev(x)
+    wants = {mode: R.block_quantize(x, outer, nblocks, inner, 8, mode, 0, 5, 9) for mode in (RN_EVEN, STOCHASTIC)}
+
+    def run(mode):
+        return host(Q.block_quantize(d, outer, nblocks, inner, 8, mode, Q.WORKSPACE_KEPT, 5, 9, workspace=ws))
+
+    assert_bit_equal(run(STOCHASTIC), wants[STOCHASTIC], "before")
+    assert Q.workspace_timeouts(ws) == 0
+    Q.set_barrier_wait_us(0)
+    try:
+        assert_bit_equal(run(STOCHASTIC), wants[STOCHASTIC], "no waiting, stochastic")
+        assert_bit_equal(run(RN_EVEN), wants[RN_EVEN], "no waiting, nearest")
+    finally:
+        Q.set_barrier_wait_us(2000)
+    gave_up = Q.workspace_timeouts(ws)
+    assert gave_up > 0
+    assert_bit_equal(run(RN_EVEN), wants[RN_EVEN], "after")
+    assert_bit_equal(run(STOCHASTIC), wants[STOCHASTIC], "after, stochastic")
+    assert Q.workspace_timeouts(ws) == gave_up
+
+
+def test_block_single_pass_clears_a_workspace_that_is_not_kept():
+    """Without the flag the workspace may hold anything: every call clears what it needs first."""
+    for shape in KEPT_SHAPES[:5]:
+        outer, nblocks, inner = shape
+        n = outer * nblocks * inner
+        x = W.lognormal_gradients((n,), seed=33)
+        want = R.block_quantize(x, outer, nblocks, inner, 8, STOCHASTIC, 0, 1, 2)
+        d = dev(x)
+        ws = torch.full((Q.block_workspace_bytes(n, outer, nblocks, inner),), 0xFF, dtype=torch.uint8, device="cuda")
+        for fill in (0xFF, 0x80, 0x01):
+            ws.fill_(fill)
+            assert_bit_equal(host(Q.block_quantize(d, outer, nblocks, inner, 8, STOCHASTIC, 0, 1, 2, workspace=ws)), want,
+                             f"{shape} workspace filled with {fill:#x}")
+        assert Q.workspace_timeouts(ws) == 0
 
 
 @pytest.mark.parametrize("log2n", [20, 22, 23, 24])
