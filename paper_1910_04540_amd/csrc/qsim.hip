@@ -177,22 +177,23 @@ struct MeetLayout {
     uint64_t tagged_words;    // flags and slots
 };
 
-static MeetLayout meet_layout(uint64_t nblocks, uint32_t slices, uint32_t stride, uint64_t tagged = 0)
+static MeetLayout meet_layout(uint64_t nblocks, uint32_t slices, uint32_t stride, bool poll_slots, uint64_t tagged = 0)
 {
     MeetLayout l;
     MeetGeom& g = l.geom;
     g.nblocks = nblocks;
     g.slices = slices;
-    g.groups = (slices + kMeetGroup - 1) / kMeetGroup;
+    g.groups = poll_slots ? 1u : (slices + kMeetGroup - 1) / kMeetGroup;
     g.stride = stride;
     g.wait_us = g_barrier_wait_us.load(std::memory_order_relaxed);
     g.counters = kMeetHeaderWords;
     g.tops = g.counters + nblocks * g.groups * stride;
-    g.finished = g.tops + nblocks * stride;
+    g.finished = g.tops + (poll_slots ? 0 : nblocks * stride);
     l.counter_words = g.finished + (nblocks + kMeetBlocksPerWord - 1) / kMeetBlocksPerWord;
     g.flags = tagged ? tagged : l.counter_words;
-    g.slots = g.flags + nblocks * g.groups * stride;
-    l.tagged_words = nblocks * g.groups * stride + nblocks * slices;
+    const uint64_t flag_words = poll_slots ? 0 : nblocks * g.groups * stride;
+    g.slots = g.flags + flag_words;
+    l.tagged_words = flag_words + nblocks * slices;
     return l;
 }
 
@@ -231,7 +232,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         if (s.sync_tagged < tagged_words) s.sync_tagged = tagged_words;
     };
     auto meeting = [&](uint32_t slices_each) {
-        const MeetLayout l = meet_layout(nblocks, slices_each, 1);
+        const MeetLayout l = meet_layout(nblocks, slices_each, 1, true);
         sync_needs(l.counter_words, l.tagged_words);
     };
     auto partial_needs = [&s](size_t bytes) {
@@ -381,7 +382,7 @@ static bool try_resident(const uint32_t* in, uint32_t* out, const BlockGeom& g, 
     if (total > kMaxResidentWgs || total > resident_capacity<MODE, GPT>()) return false;
     // a line for every counter, flag and epoch while they are few; packed otherwise (many small blocks)
     const uint64_t groups = g.nblocks * ((slices + kMeetGroup - 1) / kMeetGroup);
-    const MeetLayout meet = meet_layout(g.nblocks, (uint32_t)slices, groups <= kMaxResidentGroups ? kMeetLine : 1u, tagged);
+    const MeetLayout meet = meet_layout(g.nblocks, (uint32_t)slices, groups <= kMaxResidentGroups ? kMeetLine : 1u, false, tagged);
     if (meet.counter_words > kResidentCounterWords || meet.tagged_words > kResidentTaggedWords) return false;
     ResidentGeom rg;
     rg.sg.g = g;
@@ -403,7 +404,7 @@ static bool try_cluster(const uint32_t* in, uint32_t* out, const BlockGeom& g, i
 {
     const uint64_t slices = (g.inner + kClusterSliceLen - 1) / kClusterSliceLen;
     if (resident_capacity<MODE, 16>() < kClusterMaxSlices) return false;     // a block's workgroups must fit together
-    const MeetLayout meet = meet_layout(g.nblocks, (uint32_t)slices, 1u, tagged);
+    const MeetLayout meet = meet_layout(g.nblocks, (uint32_t)slices, 1u, true, tagged);
     ResidentGeom rg;
     rg.sg.g = g;
     rg.sg.block_len = g.inner;
@@ -473,7 +474,7 @@ static void launch_block_cluster_ragged(const uint32_t* in, uint32_t* out, const
                                         const RngKey& key, uint64_t* scratch, uint64_t tagged, bool kept, hipStream_t stream)
 {
     RaggedClusterGeom cg = geom;
-    const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, tagged);
+    const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, true, tagged);
     cg.meet = meet.geom;
     if (!kept) clear_scratch(scratch, meet, stream);
     hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, in, out, scratch, cg,
@@ -558,7 +559,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // single pass, block by block (see the kernel): the workgroups of a block must fit together
         StridedClusterGeom cg = s.scg;
-        const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, s.sync_counters);
+        const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, true, s.sync_counters);
         cg.meet = meet.geom;
         if (!kept) clear_scratch(scratch, meet, stream);
         hipLaunchKernelGGL((block_cluster_strided_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,

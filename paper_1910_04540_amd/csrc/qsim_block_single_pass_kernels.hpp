@@ -30,6 +30,7 @@ namespace qsim {
 //                                               last reads the group's final maximum with its count,
 //                                               and puts the counter back to zero.
 //     top counter of block b                    the same over the groups of a block (groups > 1)
+//     (forms that poll slots instead, see meet_in_block: one counter per block, arrivals only)
 //     blocks whose meetings are over            one word per 256 blocks
 //   tagged words (count only when their high half is this launch's tag = epoch + 1; never cleaned)
 //     flag of group q                           tag << 32 | published | the block's maximum: written by
@@ -72,28 +73,64 @@ __global__ void block_sync_clear_kernel(uint64_t* sync, uint64_t words)
     if (i < words) sync[i] = 0ull;
 }
 
-// Tag of this launch's meetings; to be read before the workgroup does anything else.  (An ordinary,
-// cached load: the word was written by an earlier launch, and no workgroup of this one reads it
-// after this launch's only write to it, which waits for all of them to have arrived.)
+// Tag of this launch's meetings; every thread reads it before the workgroup does anything else.  (An
+// ordinary load of a wave-uniform address: the word was written by an earlier launch, and this
+// launch's only write to it waits for every workgroup to have arrived, that is, to have read it.
+// The compiler cannot repeat the load further down, past this kernel's own atomics on the scratch.)
 __device__ __forceinline__ uint32_t meet_tag(const uint64_t* scratch)
 {
-    const uint32_t next = (uint32_t)__hip_atomic_load(&scratch[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) + 1u;
+    const uint32_t next = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)scratch[1]) + 1u;
     return next == 0u ? 1u : next;       // (zero is what an unused word holds)
 }
 
 // Workgroup s of block b brings the maximum m of its slice and gets the block's maximum back.
-// `tag` is meet_tag() as thread 0 read it (the other threads' value is not used); slice_max(i) gives
+// `tag` is meet_tag(); slice_max(i) gives
 // each thread's share of the maximum of slice i of the block, from memory.  Called by every thread.
-// `last_of_block` comes back true in thread 0 of the workgroup that arrived last: it owes a call of
-// meet_is_over(), which may wait until the workgroup's own stores are on their way.
-template <class SliceMax>
+// `ticket` comes back equal to mg.slices - 1 in thread 0 of one workgroup of the block, which then
+// knows that every workgroup of the block has arrived: it owes a call of meet_is_over(), for which
+// meet_leave() at the end of the kernel is the place (the workgroup's own stores are on their way then).
+//
+// POLL_SLOTS false: the counters described above (a whole tensor on a thousand workgroups: nobody
+// reads more than one flag).  POLL_SLOTS true, for the forms that meet block by block with at most
+// a few hundred workgroups per block: a workgroup publishes its slot and the first wavefront polls the
+// block's slots until all carry the tag; nothing is waited for but the slots themselves.  The
+// block's counter then only counts, after the meeting, who has been there.
+template <bool POLL_SLOTS, class SliceMax>
 __device__ __forceinline__ uint32_t meet_in_block(uint64_t* scratch, const MeetGeom& mg, uint64_t b, uint32_t s, uint32_t tag,
-                                                  uint32_t m, uint32_t* lds, uint32_t& shared_word, bool& last_of_block,
+                                                  uint32_t m, uint32_t* lds, uint32_t& shared_word, uint32_t& ticket,
                                                   SliceMax slice_max)
 {
     uint64_t* slots = scratch + mg.slots + b * mg.slices;
-    last_of_block = false;
-    if (threadIdx.x == 0) {
+    ticket = ~0u;
+    if (POLL_SLOTS) {
+        if (threadIdx.x < 64) {
+            const uint64_t mark = ((uint64_t)tag << 32) | kPublished;
+            if (threadIdx.x == 0) __hip_atomic_store(&slots[s], mark | m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint64_t start = __builtin_amdgcn_s_memrealtime();          // 100 MHz
+            const uint64_t budget = (uint64_t)mg.wait_us * 100u;
+            uint32_t acc;
+            bool all;
+            for (;;) {
+                bool ok = true;
+                acc = 0u;
+                for (uint32_t i = threadIdx.x; i < mg.slices; i += 64u) {
+                    const uint64_t a = __hip_atomic_load(&slots[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ok = ok && (uint32_t)(a >> 32) == tag;
+                    const uint32_t mag = (uint32_t)a & ~kPublished;
+                    acc = acc > mag ? acc : mag;
+                }
+                all = __all(ok);
+                if (all || __builtin_amdgcn_s_memrealtime() - start >= budget) break;
+                __builtin_amdgcn_s_sleep(1);
+            }
+            acc = wave_max(acc);
+            if (threadIdx.x == 0) {
+                shared_word = all ? (acc | kPublished) : 0u;
+                // been there (and read the epoch long before): counted now, looked at in meet_leave()
+                ticket = (uint32_t)__hip_atomic_fetch_add(scratch + mg.counters + b, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    } else if (threadIdx.x == 0) {
         const uint64_t mark = ((uint64_t)tag << 32) | kPublished;
         const uint32_t gi = s / kMeetGroup;
         const uint64_t q = b * mg.groups + gi;
@@ -121,7 +158,7 @@ __device__ __forceinline__ uint32_t meet_in_block(uint64_t* scratch, const MeetG
                 for (uint32_t i = 0; i < mg.groups; ++i)
                     __hip_atomic_store(&scratch[mg.flags + (b * mg.groups + i) * mg.stride], mark | bm, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
-                last_of_block = true;
+                ticket = mg.slices - 1u;
             }
         }
         const uint64_t* flag = scratch + mg.flags + q * mg.stride;
@@ -189,6 +226,16 @@ __device__ __forceinline__ void meet_is_over(uint64_t* scratch, const MeetGeom& 
     if (all) __hip_atomic_store(&scratch[1], (uint64_t)tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// At the end of a kernel: the workgroup that holds the block's last ticket settles the block's account.
+template <bool POLL_SLOTS>
+__device__ __forceinline__ void meet_leave(uint64_t* scratch, const MeetGeom& mg, uint64_t b, uint32_t tag, uint32_t ticket)
+{
+    if (threadIdx.x == 0 && ticket == mg.slices - 1u) {
+        if (POLL_SLOTS) __hip_atomic_store(scratch + mg.counters + b, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        meet_is_over(scratch, mg, b, tag);
+    }
+}
+
 // Single pass for contiguous blocks that fit in the register files of the whole chip (for instance
 // a 4096 x 4096 tensor quantized as one block).  The grid is small enough for every workgroup to be
 // resident at the same time; each loads its slice of 256 * GPT groups into registers, brings the
@@ -218,15 +265,14 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
     // HELD more groups stay in registers; after the wait only the remaining groups pay for Philox,
     // and the arithmetic hides behind the stores.
     constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 9 ? GPT : 9) : 0;
-    constexpr int HELD = MODE == QSIM_STOCHASTIC && GPT >= 16 ? 1 : 0;
+    constexpr int HELD = MODE == QSIM_STOCHASTIC && GPT >= 16 && !CLUSTER ? 1 : 0;
     __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
     __shared__ uint32_t lds[kThreads / 64];
     __shared__ uint32_t shared_word;
     const uint32_t wg = CLUSTER ? (uint32_t)linear_block() : blockIdx.x;
     if (CLUSTER && wg >= rg.total_wgs) return;                   // the whole workgroup leaves together
     const uint32_t b = wg / rg.sg.slices, s = wg - b * rg.sg.slices;
-    uint32_t tag = 0;
-    if (threadIdx.x == 0) tag = meet_tag(scratch);
+    const uint32_t tag = meet_tag(scratch);
     const SliceView sv = slice_view(rg.sg, b, s);
 
     // the slice is addressed from a wave-uniform base with small per-thread offsets, which keeps
@@ -272,9 +318,9 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
     }
     m = workgroup_max(m, lds);
 
-    bool last_of_block;
-    const uint32_t bm = meet_in_block(scratch, rg.meet, b, s, tag, m, lds, shared_word, last_of_block,
-                                      [&](uint32_t i) { return slice_max_frugal(in, slice_view(rg.sg, b, i)); });
+    uint32_t ticket;
+    const uint32_t bm = meet_in_block<CLUSTER>(scratch, rg.meet, b, s, tag, m, lds, shared_word, ticket,
+                                               [&](uint32_t i) { return slice_max_frugal(in, slice_view(rg.sg, b, i)); });
 
     const GridPlan p = block_plan(bm, wl, symmetric);
 #pragma unroll
@@ -295,7 +341,7 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
             else store_group<true>(sout, (uint64_t)t, slice_end, o);
         }
     }
-    if (last_of_block) meet_is_over(scratch, rg.meet, b, tag);
+    meet_leave<CLUSTER>(scratch, rg.meet, b, tag, ticket);
 }
 
 // The same block-by-block single pass for blocks along an inner dimension (outer > 1) made of
@@ -349,8 +395,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     const uint32_t wg = (uint32_t)linear_block();
     if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
     const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
-    uint32_t tag = 0;
-    if (threadIdx.x == 0) tag = meet_tag(scratch);
+    const uint32_t tag = meet_tag(scratch);
     const uint32_t t0 = s * kStridedSliceLen;
     const uint32_t ngroups = strided_slice_groups(cg, s);
 
@@ -376,8 +421,8 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     }
     m = workgroup_max(m, lds);
 
-    bool last_of_block;
-    const uint32_t bm = meet_in_block(scratch, cg.meet, b, s, tag, m, lds, shared_word, last_of_block, [&](uint32_t i) {
+    uint32_t ticket;
+    const uint32_t bm = meet_in_block<true>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
         uint32_t own = 0;
         const uint32_t count = strided_slice_groups(cg, i);
         for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
@@ -404,7 +449,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
             __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + j);
         }
     }
-    if (last_of_block) meet_is_over(scratch, cg.meet, b, tag);
+    meet_leave<true>(scratch, cg.meet, b, tag, ticket);
 }
 
 // The same for segments of any length from 64 elements at any alignment (inner % 4 != 0, or arrays
@@ -482,8 +527,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     const uint32_t wg = (uint32_t)linear_block();
     if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
     const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
-    uint32_t tag = 0;
-    if (threadIdx.x == 0) tag = meet_tag(scratch);
+    const uint32_t tag = meet_tag(scratch);
     const uint32_t t0 = s * cg.slice_groups;
     const uint32_t nslots = ragged_slice_slots(cg, s);
     const bool short_tail = (cg.n & 3u) != 0u;                     // the array's last group is not whole
@@ -531,8 +575,8 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     }
     m = workgroup_max(m, lds);
 
-    bool last_of_block;
-    const uint32_t bm = meet_in_block(scratch, cg.meet, b, s, tag, m, lds, shared_word, last_of_block, [&](uint32_t i) {
+    uint32_t ticket;
+    const uint32_t bm = meet_in_block<true>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
         // slice i of this block from memory, element by element where a group is shared
         uint32_t own = 0;
         const uint32_t count = ragged_slice_slots(cg, i);
@@ -583,7 +627,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
             }
         }
     }
-    if (last_of_block) meet_is_over(scratch, cg.meet, b, tag);
+    meet_leave<true>(scratch, cg.meet, b, tag, ticket);
 }
 
 // Blocks along an inner dimension that are SHORT (outer * inner <= 2048 elements, inner % 4 == 0,
