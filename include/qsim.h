@@ -15,7 +15,8 @@
  *     only.  The first qsim_block_quantize of a single-pass shape on a device asks the runtime for
  *     the kernel's occupancy once; make that first call outside a capture.
  *   - The library allocates and frees no device memory.  Scratch memory and tables, where needed,
- *     are the caller's (`workspace`, `table_device`).
+ *     are the caller's (`workspace`, `table_device`); qsim_block_quantize_static alone uses an
+ *     array of fixed size that is part of the library's image on the device.
  *   - in == out (exactly the same array) is allowed; any other overlap between arrays of one
  *     call is rejected with QSIM_ERR_OVERLAP.
  *   - n == 0 is a successful no-op.  n is limited to 2^38 elements.
@@ -127,6 +128,28 @@ int qsim_block_quantize(const float* in, float* out, uint64_t n, uint64_t outer,
                         uint32_t stream_id, void* workspace, size_t workspace_bytes,
                         void* hip_stream);
 size_t qsim_block_workspace_bytes(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner);
+
+/*
+ * qsim_block_quantize for callers that cannot provide device memory of their own for the scratch and
+ * cannot allocate it either: code under a stream capture, tight serving loops, harnesses that
+ * forbid allocation.  Same arguments and results as qsim_block_quantize without the workspace:
+ * the scratch is an array of QSIM_STATIC_SCRATCH_BYTES that the library holds in device memory on
+ * every GPU it runs on, from the time it is loaded until the process ends.  The call allocates and
+ * frees nothing and launches kernels only (it clears what it needs of the array with a kernel of
+ * its own first, so what an earlier call left there does not matter).
+ *   - A shape whose qsim_block_workspace_bytes exceeds QSIM_STATIC_SCRATCH_BYTES is rejected with
+ *     QSIM_ERR_WORKSPACE; nothing is launched.
+ *   - QSIM_WORKSPACE_KEPT is not accepted here (QSIM_ERR_FORMAT).
+ *   - All calls on one GPU share the one array: two such calls that are in flight on that GPU at
+ *     the same time (two streams, two threads) race and give undefined results.  Calls on one
+ *     stream, or otherwise ordered one after the other, are fine.
+ *   - The first call on a device looks the array's address up (and, for a single-pass shape, asks
+ *     for the kernel's occupancy); neither allocates.
+ */
+#define QSIM_STATIC_SCRATCH_BYTES (4u << 20)
+int qsim_block_quantize_static(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks,
+                               uint64_t inner, int wl, int rounding, uint32_t flags, uint64_t seed,
+                               uint32_t stream_id, void* hip_stream);
 
 /*
  * Tuning and test knob of qsim_block_quantize.  A block that is too long for one workgroup but

@@ -25,7 +25,8 @@ EXPORTS = ("qsim_float_quantize", "qsim_fixed_quantize", "qsim_block_quantize", 
            "qsim_set_barrier_wait_us", "qsim_quant_sgd_step", "qsim_quant_sgd_step_multi", "qsim_quant_sgd_step_ex",
            "qsim_quant_sgd_step_multi_ex", "qsim_sgd_table_bytes", "qsim_sgd_table_build", "qsim_quant_sgd_step_table",
            "qsim_float_quantize_at", "qsim_fixed_quantize_at", "qsim_block_quantize_at", "qsim_quant_sgd_step_at",
-           "qsim_block_max", "qsim_block_quantize_with_max", "qsim_status_string")
+           "qsim_block_max", "qsim_block_quantize_with_max", "qsim_block_quantize_static", "qsim_status_string")
+STATIC_SCRATCH_BYTES = 4 << 20   # QSIM_STATIC_SCRATCH_BYTES
 
 
 class Format(ctypes.Structure):
@@ -71,6 +72,8 @@ def lib() -> ctypes.CDLL:
     L.qsim_block_quantize_at.argtypes = [vp, vp, u64, u64, u64, u64, u64, ci, ci, u32, u64, u32, vp, sz, vp]
     L.qsim_block_max.argtypes = [vp, u64, u64, u64, u64, vp, vp, sz, vp]
     L.qsim_block_quantize_with_max.argtypes = [vp, vp, u64, u64, u64, u64, u64, ci, ci, u32, u64, u32, vp, vp]
+    L.qsim_block_quantize_static.argtypes = [vp, vp, u64, u64, u64, u64, ci, ci, u32, u64, u32, vp]
+    L.qsim_block_quantize_static.restype = ci
     L.qsim_block_workspace_bytes.argtypes = [u64, u64, u64, u64]
     L.qsim_block_workspace_bytes.restype = sz
     L.qsim_quant_sgd_step.argtypes = [vp, vp, vp, vp, u64, ctypes.c_float, ctypes.c_float,
@@ -242,6 +245,17 @@ def block_quantize(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed
     else:
         _check(lib().qsim_block_quantize(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, wl, rounding,
                                          flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
+    return out
+
+
+def block_quantize_static(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed=0, stream_id=0, out=None):
+    """qsim_block_quantize_static: the scratch is the library's own array on the GPU, nothing is
+    allocated (pass ``out``, or the binding allocates the result).  Calls that are in flight on one
+    GPU at the same time race."""
+    _device_f32(x, "x")
+    out = _out_like(x, out)
+    _check(lib().qsim_block_quantize_static(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, wl, rounding,
+                                            flags, seed, stream_id, _stream()))
     return out
 
 

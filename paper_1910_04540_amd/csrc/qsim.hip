@@ -793,6 +793,43 @@ int qsim_block_quantize_at(const float* in, float* out, uint64_t n, uint64_t out
     return block_quantize_checked(in, out, n, s, index0, wl, rounding, flags, seed, stream_id, workspace, as_stream(hip_stream));
 }
 
+// Scratch of qsim_block_quantize_static: one array per GPU, held from load to exit.  In host code the
+// array's name is only a handle for the runtime; its address on a device comes from
+// hipGetSymbolAddress with that device current, once per device, and only that address is used.
+static __device__ __align__(256) unsigned char scratch[QSIM_STATIC_SCRATCH_BYTES];
+
+static void* static_scratch()
+{
+    static std::atomic<void*> address[64];      // per device; NULL = not looked up yet
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    void* p = address[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        address[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
+int qsim_block_quantize_static(const float* in, float* out, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner,
+                               int wl, int rounding, uint32_t flags, uint64_t seed, uint32_t stream_id, void* hip_stream)
+{
+    if (flags & QSIM_WORKSPACE_KEPT) return QSIM_ERR_FORMAT;      // the array is shared by every shape: always cleared
+    const int status = check_block_call(in, out, n, outer, nblocks, inner, 0, wl, rounding, flags);
+    if (status != QSIM_OK || n == 0) return status;
+    const BlockSchedule s = block_schedule(n, outer, nblocks, inner);
+    if (s.workspace > (size_t)QSIM_STATIC_SCRATCH_BYTES) return QSIM_ERR_WORKSPACE;
+    void* workspace = nullptr;
+    if (s.workspace) {
+        workspace = static_scratch();
+        if (!workspace) return QSIM_ERR_LAUNCH;
+    }
+    return block_quantize_checked(in, out, n, s, 0, wl, rounding, flags, seed, stream_id, workspace, as_stream(hip_stream));
+}
+
 int qsim_block_max(const float* in, uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner, uint32_t* block_max,
                    void* workspace, size_t workspace_bytes, void* hip_stream)
 {
