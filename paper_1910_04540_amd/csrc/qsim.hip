@@ -476,7 +476,7 @@ static void launch_block_cluster_ragged(const uint32_t* in, uint32_t* out, const
     RaggedClusterGeom cg = geom;
     const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, true, tagged);
     cg.meet = meet.geom;
-    if (!kept) clear_scratch(scratch, meet, stream);
+    if (!kept && cg.slices > 1u) clear_scratch(scratch, meet, stream);       // (one workgroup per block: nothing meets)
     hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, in, out, scratch, cg,
                        wl, symmetric, key);
 }
@@ -559,9 +559,19 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // single pass, block by block (see the kernel): the workgroups of a block must fit together
         StridedClusterGeom cg = s.scg;
+        if (cg.slices > 1u && cg.block_len <= 4u * 1024u * 16u) {
+            // two to four workgroups per block: one large workgroup holds it alone, with nobody to meet
+            if (cg.block_len <= 4u * 512u * 16u)
+                hipLaunchKernelGGL((block_strided_wide_kernel<MODE, 512>), folded(cg.nblocks), dim3(512), 0, stream, pin, pout, cg, wl,
+                                   symmetric, key);
+            else
+                hipLaunchKernelGGL((block_strided_wide_kernel<MODE, 1024>), folded(cg.nblocks), dim3(1024), 0, stream, pin, pout, cg,
+                                   wl, symmetric, key);
+            return launch_status();
+        }
         const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, true, s.sync_counters);
         cg.meet = meet.geom;
-        if (!kept) clear_scratch(scratch, meet, stream);
+        if (!kept && cg.slices > 1u) clear_scratch(scratch, meet, stream);   // (one workgroup per block: nothing meets)
         hipLaunchKernelGGL((block_cluster_strided_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
                            scratch, cg, wl, symmetric, key);
     } else if (s.strided_ragged && !short_segments && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {

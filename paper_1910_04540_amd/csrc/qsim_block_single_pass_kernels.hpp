@@ -395,7 +395,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     const uint32_t wg = (uint32_t)linear_block();
     if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
     const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
-    const uint32_t tag = meet_tag(scratch);
+    const uint32_t tag = cg.slices == 1u ? 0u : meet_tag(scratch);
     const uint32_t t0 = s * kStridedSliceLen;
     const uint32_t ngroups = strided_slice_groups(cg, s);
 
@@ -421,8 +421,9 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     }
     m = workgroup_max(m, lds);
 
-    uint32_t ticket;
-    const uint32_t bm = meet_in_block<true>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
+    // (a block that one workgroup holds alone has nobody to meet and leaves the scratch alone)
+    uint32_t ticket = ~0u;
+    const uint32_t bm = cg.slices == 1u ? m : meet_in_block<true>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
         uint32_t own = 0;
         const uint32_t count = strided_slice_groups(cg, i);
         for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
@@ -449,7 +450,62 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
             __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + j);
         }
     }
-    meet_leave<true>(scratch, cg.meet, b, tag, ticket);
+    if (cg.slices > 1u) meet_leave<true>(scratch, cg.meet, b, tag, ticket);
+}
+
+// The same blocks when one of them fits a single LARGE workgroup (512 or 1024 threads, 16 groups per
+// thread: up to 32 Ki or 64 Ki elements): nobody to meet, no scratch; the block's maximum is a
+// reduction through LDS.  For the small activation tensors of a network on small images
+// ([128, 128, 16, 16] per channel: blocks of 32 Ki elements), where two workgroups of 256 threads
+// per block would spend more time finding each other than moving the data.
+template <int MODE, int THREADS>
+__global__ __launch_bounds__(THREADS) void block_strided_wide_kernel(const uint32_t* in, uint32_t* out, StridedClusterGeom cg, int wl,
+                                                                     int symmetric, RngKey key)
+{
+    constexpr int GPT = 16;
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? 9 : 0;          // random words parked in LDS while the loads are in flight
+    __shared__ uint4 parked[PRE > 0 ? PRE * THREADS : 1];
+    __shared__ uint32_t lds[THREADS / 64];
+    const uint32_t b = (uint32_t)linear_block();
+    if (b >= cg.nblocks) return;                                   // the whole workgroup leaves together
+    const uint32_t ngroups = cg.block_len / 4u;
+
+    uint4 v[GPT];
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * THREADS;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (t < ngroups) {
+            const uint64_t j = strided_group(cg, b, 4u * t);
+            v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in) + j));
+            if (k < PRE) {
+                const Words4 r = random_words(j, key, 0u);
+                parked[k * THREADS + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+            }
+        }
+    }
+    uint32_t m = 0;
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t gm = max4_mag(v[k]);
+        m = m > gm ? m : gm;
+    }
+    const GridPlan p = block_plan(workgroup_max<THREADS>(m, lds), wl, symmetric);
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * THREADS;
+        if (t < ngroups) {
+            const uint64_t j = strided_group(cg, b, 4u * t);
+            Words4 r = {{0u, 0u, 0u, 0u}};
+            if (k < PRE) {
+                const uint4 w = parked[k * THREADS + threadIdx.x];
+                r = Words4{{w.x, w.y, w.z, w.w}};
+            } else if (MODE == QSIM_STOCHASTIC) {
+                r = random_words(j, key, 0u);
+            }
+            __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + j);
+        }
+    }
 }
 
 // The same for segments of any length from 64 elements at any alignment (inner % 4 != 0, or arrays
@@ -527,7 +583,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     const uint32_t wg = (uint32_t)linear_block();
     if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
     const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
-    const uint32_t tag = meet_tag(scratch);
+    const uint32_t tag = cg.slices == 1u ? 0u : meet_tag(scratch);
     const uint32_t t0 = s * cg.slice_groups;
     const uint32_t nslots = ragged_slice_slots(cg, s);
     const bool short_tail = (cg.n & 3u) != 0u;                     // the array's last group is not whole
@@ -575,8 +631,8 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     }
     m = workgroup_max(m, lds);
 
-    uint32_t ticket;
-    const uint32_t bm = meet_in_block<true>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
+    uint32_t ticket = ~0u;
+    const uint32_t bm = cg.slices == 1u ? m : meet_in_block<true>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
         // slice i of this block from memory, element by element where a group is shared
         uint32_t own = 0;
         const uint32_t count = ragged_slice_slots(cg, i);
@@ -627,7 +683,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
             }
         }
     }
-    meet_leave<true>(scratch, cg.meet, b, tag, ticket);
+    if (cg.slices > 1u) meet_leave<true>(scratch, cg.meet, b, tag, ticket);
 }
 
 // Blocks along an inner dimension that are SHORT (outer * inner <= 2048 elements, inner % 4 == 0,

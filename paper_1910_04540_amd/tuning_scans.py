@@ -1,6 +1,7 @@
 """Developer scans of block floating point over shapes: which kernel form serves which shape, and
 how well.  Not part of the library's surface; kept because the summaries under profiles/ name these
-commands.
+commands.  Every call leaves the scratch to the binding, which keeps a zero-filled one per shape
+(QSIM_WORKSPACE_KEPT), as a training loop that calls the same shapes every step would.
 
     python -m paper_1910_04540_amd.tuning_scans --block-shapes
 
@@ -43,7 +44,6 @@ def block_shapes() -> int:
     for cols in BLOCK_ROW_LENGTHS:
         rows = total // cols
         n = rows * cols
-        ws = torch.empty(max(Q.block_workspace_bytes(n, 1, rows, cols), 16), dtype=torch.uint8, device="cuda")
         cells = []
         for mode in (Q.RN_EVEN, Q.STOCHASTIC):
             turn = [0]
@@ -51,7 +51,7 @@ def block_shapes() -> int:
             def call():
                 k = turn[0] % 3
                 turn[0] += 1
-                Q.block_quantize(xs[k][:n], 1, rows, cols, 8, mode, 0, 1, 0, out=outs[k][:n], workspace=ws)
+                Q.block_quantize(xs[k][:n], 1, rows, cols, 8, mode, 0, 1, 0, out=outs[k][:n])
 
             for _ in range(100):
                 call()
@@ -80,14 +80,13 @@ def channel_shapes() -> int:
         n = batch * channels * inner
         xs = [torch.randn(n, device="cuda") for _ in range(3)]
         out = torch.empty(n, device="cuda")
-        ws = torch.empty(max(Q.block_workspace_bytes(n, batch, channels, inner), 16), dtype=torch.uint8, device="cuda")
         cells = []
         for mode in (Q.RN_EVEN, Q.STOCHASTIC):
             turn = [0]
 
             def call():
                 turn[0] += 1
-                Q.block_quantize(xs[turn[0] % 3], batch, channels, inner, 8, mode, 0, 1, 0, out=out, workspace=ws)
+                Q.block_quantize(xs[turn[0] % 3], batch, channels, inner, 8, mode, 0, 1, 0, out=out)
 
             for _ in range(30):
                 call()
@@ -95,7 +94,7 @@ def channel_shapes() -> int:
             cells.append((us, n * 8 / us / 1e3 / 80.0))
         label = ", ".join(str(v) for v in shape)
         print(f"{label:>20} {n:>10} | {cells[0][0]:10.1f} {cells[0][1]:11.1f} | {cells[1][0]:13.1f} {cells[1][1]:11.1f}", flush=True)
-        del xs, out, ws
+        del xs, out
         torch.cuda.empty_cache()
     return 0
 
@@ -124,14 +123,12 @@ def shape_scan(seed: int) -> int:
         need = Q.block_workspace_bytes(n, outer, nblocks, inner)
         if need > (1 << 31):
             continue
-        ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
         for mode, name in ((Q.RN_EVEN, "nearest"), (Q.STOCHASTIC, "stochastic")):
-            call = lambda: Q.block_quantize(x[:n], outer, nblocks, inner, 8, mode, 0, 1, 0, out=out[:n], workspace=ws)
+            call = lambda: Q.block_quantize(x[:n], outer, nblocks, inner, 8, mode, 0, 1, 0, out=out[:n])
             for _ in range(4):
                 call()
             us = _time(call, 8)
             rows.append((n * 8 / us / 1e3 / 80.0, us, outer, nblocks, inner, n, name))
-        del ws
     rows.sort()
     print(f"{len(rows)} timings (shape x rounding), % of 8 TB/s at 8 B per element; slowest first")
     for r in rows[:12]:

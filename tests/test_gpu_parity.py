@@ -515,6 +515,23 @@ def test_block_per_channel_single_pass_with_odd_segments(shape, rounding):
     assert_bit_equal(host(view), want, f"{shape} in place")
 
 
+@pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
+@pytest.mark.parametrize("shape", [(128, 16, 256), (100, 9, 256), (4, 6, 16000), (65, 700, 252), (2, 3, 32768), (17, 2, 3852)])
+def test_block_per_channel_one_large_workgroup_per_block(shape, rounding):
+    """Blocks along an inner dimension of 16 Ki to 64 Ki elements: one workgroup of 512 or 1024
+    threads holds a block alone (full, partly filled, and exactly full workgroups)."""
+    outer, nblocks, inner = shape
+    g = np.random.Generator(np.random.PCG64(sum(shape)))
+    scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
+    x = (g.standard_normal(shape, dtype=np.float32) * scale[None, :, None]).astype(np.float32)
+    x[outer - 1, nblocks - 1, inner - 1] = np.float32(7.0e22)          # a maximum in the tensor's very last element
+    want = R.block_quantize(x, outer, nblocks, inner, 8, rounding, 0, 6, 1).reshape(-1)
+    d = dev(x.reshape(-1))
+    assert_bit_equal(host(Q.block_quantize(d, outer, nblocks, inner, 8, rounding, 0, 6, 1)), want, f"{shape}")
+    Q.block_quantize(d, outer, nblocks, inner, 8, rounding, 0, 6, 1, out=d)
+    assert_bit_equal(host(d), want, f"{shape} in place")
+
+
 def test_block_per_channel_single_pass_with_odd_segments_when_the_wait_runs_out():
     Q.set_barrier_wait_us(0)
     try:
