@@ -363,15 +363,15 @@ def main() -> int:
                 "quant_sgd_step_one_thread": rate(lambda: R.quant_sgd_step(w, g, m, 0.1, 0.9, fg, fm, fw, 1234, 2), w.size),
             }
     print(json.dumps(result), flush=True)
-    # leave nothing behind: everything queued has finished, device memory goes back now
+    # leave nothing behind: everything queued has finished, and the tensors that are still alive go
+    # back now rather than in the interpreter's teardown
     torch.cuda.synchronize()
+    x_host = None
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
     return 0
 
 
 if __name__ == "__main__":
-    rc = main()
-    # the result is printed and the device is idle: end the process at once rather than through the
-    # interpreter's teardown of several GB of tensors and library state, which outlives the last line
-    sys.stdout.flush()
-    sys.stderr.flush()
-    os._exit(rc)
+    sys.exit(main())
