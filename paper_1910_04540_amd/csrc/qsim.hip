@@ -131,7 +131,6 @@ constexpr uint64_t kColumnMaxInner = 4096;       // to keep the one-wavefront-pe
 constexpr uint64_t kColumnManyBlocks = 1024;      // (a quarter of both also qualifies: 256 blocks of up to 1024)
 constexpr uint32_t kColumnParts = 8;             // slices left after the first, coalesced fold of its column maxima
 constexpr uint64_t kFlatWorkgroups = 1024;       // workgroups of the flat form (four per CU)
-constexpr uint32_t kFlatParts = 32;              // parts of its first fold
 constexpr uint64_t kMultiTiles = 1ull << 30;     // tiles of one multi-tensor launch (running counts are 32-bit)
 
 // Row slices of the column form: a thread owns a run of four columns.
@@ -208,6 +207,14 @@ static void clear_scratch(uint64_t* scratch, const MeetLayout& l, hipStream_t st
     hipLaunchKernelGGL(block_sync_clear_kernel, folded((words + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, scratch, words);
 }
 
+// The walk of a thread over its groups when the workgroup has `threads` threads (see StridedClusterGeom).
+static void strided_steps(StridedClusterGeom& cg, uint32_t threads)
+{
+    const uint32_t step = 4u * threads;
+    cg.step_rest = step % cg.inner;
+    cg.step_groups = (uint32_t)((uint64_t)(step / cg.inner) * cg.row_groups + cg.step_rest / 4u);      // modulo 2^32
+}
+
 static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks, uint64_t inner)
 {
     BlockSchedule s;
@@ -261,7 +268,8 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         s.spg.magic_inner = (uint32_t)((1ull << 32) / inner) + 1u;
         s.spg.blocks_per_wg = 1024u / s.spg.groups_per_block;
     }
-    if (outer > 1 && inner % 4 == 0 && inner >= 64 && inner <= (1ull << 22) &&
+    // (these two forms count groups and elements from a block's start in 32 bits)
+    if (outer > 1 && inner % 4 == 0 && inner >= 64 && inner <= (1ull << 22) && n < (1ull << 34) &&
         s.sg.block_len <= (uint64_t)kStridedMaxSlices * kStridedSliceLen) {
         const uint64_t slices_each = (s.sg.block_len + kStridedSliceLen - 1) / kStridedSliceLen;
         if (nblocks * slices_each <= kClusterMaxWgs) {
@@ -272,10 +280,13 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
             s.scg.inner = (uint32_t)inner;
             s.scg.magic_inner = (uint32_t)((1ull << 32) / inner) + 1u;
             s.scg.total_wgs = (uint32_t)(nblocks * slices_each);
+            s.scg.row_groups = (uint32_t)(nblocks * inner / 4);
+            s.scg.wrap_groups = s.scg.row_groups - (uint32_t)(inner / 4);
+            strided_steps(s.scg, kThreads);
             meeting(s.scg.slices);
         }
     }
-    if (inner >= 64 && inner <= (1ull << 22)) {          // (contiguous blocks too: one segment each)
+    if (inner >= 64 && inner <= (1ull << 22) && n < (1ull << 32)) {          // (contiguous blocks too: one segment each)
         const uint64_t seg_groups = (inner + 2) / 4 + 1;
         const unsigned __int128 block_groups = (unsigned __int128)outer * seg_groups;
         // (a block has workgroups of its own, four of which fit a CU: with fewer than eight loads per
@@ -293,6 +304,9 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
                 s.rcg.slices = (uint32_t)slices_each;
                 s.rcg.slice_groups = (uint32_t)(((uint64_t)block_groups + slices_each - 1) / slices_each);
                 s.rcg.total_wgs = (uint32_t)(nblocks * slices_each);
+                s.rcg.row_elems = outer > 1 ? (uint32_t)(nblocks * inner) : 0u;
+                s.rcg.step_rest = (uint32_t)(kThreads % seg_groups);
+                s.rcg.step_elems = (uint32_t)((kThreads / seg_groups) * s.rcg.row_elems);
                 meeting(s.rcg.slices);
             }
         }
@@ -315,8 +329,8 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         fg.wgs = (uint32_t)((fg.groups + fg.groups_per_wg - 1) / fg.groups_per_wg);
         fg.stream_first = n > kCachedTensorElements ? 1u : 0u;
         fg.copies = 1;
-        while (fg.copies < 64 && 2 * fg.copies * fg.nblocks <= (uint32_t)kFlatMaxBlocks) fg.copies *= 2;
-        partial_needs((size_t)(kFlatWorkgroups + kFlatParts + 1) * nblocks * sizeof(uint32_t));
+        while (fg.copies < 64 && 2 * fg.copies * ((fg.nblocks + 3u) & ~3u) <= (uint32_t)kFlatMaxBlocks) fg.copies *= 2;
+        partial_needs((size_t)(kFlatWorkgroups + 1) * nblocks * sizeof(uint32_t));
     }
     // the column form: short segments (a thread walking down a column jumps a whole row per step, which
     // only pays when the alternative would do a division per run of a short segment), and segments of
@@ -561,6 +575,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         StridedClusterGeom cg = s.scg;
         if (cg.slices > 1u && cg.block_len <= 4u * 1024u * 16u) {
             // two to four workgroups per block: one large workgroup holds it alone, with nobody to meet
+            strided_steps(cg, cg.block_len <= 4u * 512u * 16u ? 512u : 1024u);
             if (cg.block_len <= 4u * 512u * 16u)
                 hipLaunchKernelGGL((block_strided_wide_kernel<MODE, 512>), folded(cg.nblocks), dim3(512), 0, stream, pin, pout, cg, wl,
                                    symmetric, key);
@@ -582,19 +597,10 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         // the column form cannot run; otherwise where that form is weak (few blocks make its fold
         // serial, short rows give it few threads per row)
         const FlatGeom& fg = s.fg;
-        uint32_t* folded_once = partial + (size_t)kFlatWorkgroups * fg.nblocks;
-        uint32_t* blockmax = folded_once + (size_t)kFlatParts * fg.nblocks;
-        const unsigned bx = (fg.nblocks + kThreads - 1) / kThreads;
-        hipLaunchKernelGGL(block_flat_max_kernel, dim3(fg.wgs), dim3(kThreads), 0, stream, pin, partial, fg);
-        if (fg.wgs > kFlatParts) {
-            hipLaunchKernelGGL(block_fold_rows_kernel, dim3(bx, kFlatParts), dim3(kThreads), 0, stream, partial, folded_once,
-                               fg.nblocks, fg.wgs, kFlatParts);
-            hipLaunchKernelGGL(block_fold_rows_kernel, dim3(bx, 1), dim3(kThreads), 0, stream, folded_once, blockmax, fg.nblocks,
-                               kFlatParts, 1u);
-        } else {
-            hipLaunchKernelGGL(block_fold_rows_kernel, dim3(bx, 1), dim3(kThreads), 0, stream, partial, blockmax, fg.nblocks,
-                               fg.wgs, 1u);
-        }
+        uint32_t* blockmax = partial + (size_t)kFlatWorkgroups * fg.nblocks;
+        hipLaunchKernelGGL(block_flat_max_kernel, dim3(fg.wgs), dim3(kThreads), 0, stream, pin, partial, blockmax, fg);
+        hipLaunchKernelGGL(block_fold_rows_once_kernel, dim3((fg.nblocks + 31u) / 32u, (fg.wgs + kFoldOnceRows - 1u) / kFoldOnceRows),
+                           dim3(kThreads), 0, stream, partial, blockmax, fg.nblocks, fg.wgs);
         hipLaunchKernelGGL((block_flat_apply_kernel<MODE>), dim3(fg.wgs), dim3(kThreads), 0, stream, pin, pout, blockmax, fg, wl,
                            symmetric, key);
     } else if (s.column) {

@@ -68,6 +68,7 @@ __global__ __launch_bounds__(THREADS) void block_cached_kernel(const uint32_t* i
     }
     m = WHOLE_WORKGROUP ? workgroup_max<THREADS>(m, lds) : group_max(m, team);
     const GridPlan p = block_plan(m, wl, symmetric);
+    const bool finite = wave_plans_are_finite<MODE>(p);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = lane + (uint32_t)k * stride;
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(THREADS) void block_cached_kernel(const uint32_t* i
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) r = early[k];
             else if (MODE == QSIM_STOCHASTIC) r = random_words(j0 + (g0 + t), key, 0u);
-            store_group<true>(wout, (uint64_t)(g0 + t), (uint64_t)end, quantize_group_to_grid<MODE>(v[k], p, r));
+            store_group<true>(wout, (uint64_t)(g0 + t), (uint64_t)end, quantize_group_of_block<MODE>(v[k], p, r, finite));
         }
     }
 }
@@ -159,6 +160,17 @@ __global__ __launch_bounds__(kThreads) void block_ragged_kernel(const uint32_t* 
         }
     }
     __syncthreads();
+    int all_finite = 1;
+    for (uint32_t t = threadIdx.x; t < nrows; t += kThreads)
+        if (!plan_is_finite<MODE>(block_plan(rowmax[t], wl, symmetric))) all_finite = 0;
+    // none of the workgroup's blocks holds Inf or NaN (nearly always): the table then holds exponent
+    // fields, from which a plan per element is cheap
+    const bool finite = __syncthreads_and(all_finite) != 0;
+    if (finite) {
+        for (uint32_t t = threadIdx.x; t < nrows; t += kThreads) rowmax[t] = clamped_field23(rowmax[t]);
+        __syncthreads();
+    }
+    const FieldPlan fp = field_plan(wl, symmetric);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
@@ -171,8 +183,11 @@ __global__ __launch_bounds__(kThreads) void block_ragged_kernel(const uint32_t* 
             const uint32_t row[4] = {rows01[k] & 0xffffu, rows01[k] >> 16, rows23[k] & 0xffffu, rows23[k] >> 16};
             uint32_t o[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e)
-                o[e] = quantize_to_grid<MODE>(bits[e], block_plan(rowmax[row[e]], wl, symmetric), r.w[e]);
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t entry = rowmax[row[e]];
+                o[e] = finite ? quantize_finite_to_grid<MODE>(bits[e], plan_of_field(entry, fp), r.w[e])
+                              : quantize_to_grid<MODE>(bits[e], block_plan(entry, wl, symmetric), r.w[e]);
+            }
             const uint32_t at = t * 4u;
             if (at >= lead && at + 3u - lead < span) {
                 store_group<VEC>(out, j, g.n, make_uint4(o[0], o[1], o[2], o[3]));
@@ -203,11 +218,12 @@ __global__ __launch_bounds__(kThreads) void block_rows_kernel(const uint32_t* in
         m = m > a ? m : a;
     }
     const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
+    const bool finite = wave_plans_are_finite<MODE>(p);
     for (uint64_t t = threadIdx.x; t < len; t += kThreads) {
         const uint64_t i = start + t;
         uint32_t r = 0;
         if (MODE == QSIM_STOCHASTIC) r = random_words(i >> 2, key, 0u).w[i & 3];
-        out[i] = quantize_to_grid<MODE>(in[i], p, r);
+        out[i] = finite ? quantize_finite_to_grid<MODE>(in[i], p, r) : quantize_to_grid<MODE>(in[i], p, r);
     }
 }
 

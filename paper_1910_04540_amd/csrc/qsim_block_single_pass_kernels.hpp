@@ -323,6 +323,7 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
                                                [&](uint32_t i) { return slice_max_frugal(in, slice_view(rg.sg, b, i)); });
 
     const GridPlan p = block_plan(bm, wl, symmetric);
+    const bool finite = wave_plans_are_finite<MODE>(p);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const int t = (int)threadIdx.x + k * kThreads;
@@ -336,7 +337,7 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
             } else if (MODE == QSIM_STOCHASTIC) {
                 r = random_words(sv.j0 + (uint64_t)t, key, 0u);
             }
-            const uint4 o = quantize_group_to_grid<MODE>(v[k], p, r);
+            const uint4 o = quantize_group_of_block<MODE>(v[k], p, r, finite);
             if (full) __builtin_nontemporal_store(to_u32x4(o), reinterpret_cast<u32x4*>(sout) + t);
             else store_group<true>(sout, (uint64_t)t, slice_end, o);
         }
@@ -360,8 +361,43 @@ struct StridedClusterGeom {
     uint32_t inner;          // a multiple of 4, at least 64
     uint32_t magic_inner;    // floor(2^32 / inner) + 1
     uint32_t total_wgs;
+    // A thread's groups are 4 * THREADS elements of the block apart.  Counted in groups from the
+    // block's first element, the group at element (o, i) sits at o * row_groups + i / 4; from one of a
+    // thread's groups to its next that grows by step_groups, and by wrap_groups more when i, having
+    // grown by step_rest, passes `inner` (all modulo 2^32: the array has fewer than 2^32 groups).
+    uint32_t row_groups;     // nblocks * inner / 4
+    uint32_t step_rest;      // (4 * THREADS) % inner
+    uint32_t step_groups;    // ((4 * THREADS) / inner) * row_groups + step_rest / 4
+    uint32_t wrap_groups;    // row_groups - inner / 4
     MeetGeom meet;
 };
+
+// A thread's walk over its groups of a block: `off` is the current group, counted from the block's
+// first; two additions and a compare per step instead of a division and a 64-bit product per group.
+struct StridedWalk {
+    uint32_t i, off;
+};
+
+__device__ __forceinline__ StridedWalk strided_walk(const StridedClusterGeom& cg, uint32_t tt)
+{
+    uint32_t o = __umulhi(tt, cg.magic_inner);           // tt / inner or one more (tt < 2^22)
+    uint32_t i = tt - o * cg.inner;
+    if ((int32_t)i < 0) {
+        o -= 1u;
+        i += cg.inner;
+    }
+    return StridedWalk{i, o * cg.row_groups + i / 4u};
+}
+
+__device__ __forceinline__ void strided_step(const StridedClusterGeom& cg, StridedWalk& w)
+{
+    w.i += cg.step_rest;
+    w.off += cg.step_groups;
+    if (w.i >= cg.inner) {
+        w.i -= cg.inner;
+        w.off += cg.wrap_groups;
+    }
+}
 
 // Group number, in the array, of the group at element tt (a multiple of 4) of block b.
 __device__ __forceinline__ uint64_t strided_group(const StridedClusterGeom& cg, uint32_t b, uint32_t tt)
@@ -399,19 +435,24 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     const uint32_t t0 = s * kStridedSliceLen;
     const uint32_t ngroups = strided_slice_groups(cg, s);
 
+    const uint64_t jbase = (uint64_t)b * (cg.inner / 4u);           // the block's first group
+    StridedWalk walk = strided_walk(cg, t0 + 4u * threadIdx.x);
     uint4 v[GPT];
+    uint32_t where[GPT];                                           // kept for the stores
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
         v[k] = make_uint4(0u, 0u, 0u, 0u);
+        where[k] = walk.off;
         if (t < ngroups) {
-            const uint64_t j = strided_group(cg, b, t0 + 4u * t);
+            const uint64_t j = jbase + walk.off;
             v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in) + j));
             if (k < PRE) {
                 const Words4 r = random_words(j, key, 0u);
                 parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
             }
         }
+        strided_step(cg, walk);
     }
     uint32_t m = 0;
 #pragma unroll
@@ -435,11 +476,12 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     });
 
     const GridPlan p = block_plan(bm, wl, symmetric);
+    const bool finite = wave_plans_are_finite<MODE>(p);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
         if (t < ngroups) {
-            const uint64_t j = strided_group(cg, b, t0 + 4u * t);
+            const uint64_t j = jbase + where[k];
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) {
                 const uint4 w = parked[k * kThreads + threadIdx.x];
@@ -447,7 +489,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
             } else if (MODE == QSIM_STOCHASTIC) {
                 r = random_words(j, key, 0u);
             }
-            __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + j);
+            __builtin_nontemporal_store(to_u32x4(quantize_group_of_block<MODE>(v[k], p, r, finite)), reinterpret_cast<u32x4*>(out) + j);
         }
     }
     if (cg.slices > 1u) meet_leave<true>(scratch, cg.meet, b, tag, ticket);
@@ -470,19 +512,24 @@ __global__ __launch_bounds__(THREADS) void block_strided_wide_kernel(const uint3
     if (b >= cg.nblocks) return;                                   // the whole workgroup leaves together
     const uint32_t ngroups = cg.block_len / 4u;
 
+    const uint64_t jbase = (uint64_t)b * (cg.inner / 4u);           // the block's first group
+    StridedWalk walk = strided_walk(cg, 4u * threadIdx.x);
     uint4 v[GPT];
+    uint32_t where[GPT];                                           // kept for the stores
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = threadIdx.x + (uint32_t)k * THREADS;
         v[k] = make_uint4(0u, 0u, 0u, 0u);
+        where[k] = walk.off;
         if (t < ngroups) {
-            const uint64_t j = strided_group(cg, b, 4u * t);
+            const uint64_t j = jbase + walk.off;
             v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in) + j));
             if (k < PRE) {
                 const Words4 r = random_words(j, key, 0u);
                 parked[k * THREADS + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
             }
         }
+        strided_step(cg, walk);
     }
     uint32_t m = 0;
 #pragma unroll
@@ -491,11 +538,12 @@ __global__ __launch_bounds__(THREADS) void block_strided_wide_kernel(const uint3
         m = m > gm ? m : gm;
     }
     const GridPlan p = block_plan(workgroup_max<THREADS>(m, lds), wl, symmetric);
+    const bool finite = wave_plans_are_finite<MODE>(p);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = threadIdx.x + (uint32_t)k * THREADS;
         if (t < ngroups) {
-            const uint64_t j = strided_group(cg, b, 4u * t);
+            const uint64_t j = jbase + where[k];
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) {
                 const uint4 w = parked[k * THREADS + threadIdx.x];
@@ -503,7 +551,7 @@ __global__ __launch_bounds__(THREADS) void block_strided_wide_kernel(const uint3
             } else if (MODE == QSIM_STOCHASTIC) {
                 r = random_words(j, key, 0u);
             }
-            __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + j);
+            __builtin_nontemporal_store(to_u32x4(quantize_group_of_block<MODE>(v[k], p, r, finite)), reinterpret_cast<u32x4*>(out) + j);
         }
     }
 }
@@ -528,6 +576,11 @@ struct RaggedClusterGeom {
     uint32_t slices;         // ceil(block_groups / 4096)
     uint32_t slice_groups;   // ceil(block_groups / slices): the slots are dealt out evenly
     uint32_t total_wgs;
+    // A thread's slots are kThreads apart: from one to its next, u grows by step_rest and the
+    // segment's first element by step_elems, and by row_elems more when u passes G.
+    uint32_t row_elems;      // nblocks * inner: from a segment of a block to its next (0 for a contiguous block)
+    uint32_t step_rest;      // kThreads % G
+    uint32_t step_elems;     // (kThreads / G) * row_elems
     MeetGeom meet;
 };
 
@@ -556,6 +609,15 @@ __device__ __forceinline__ void ragged_slot(const RaggedClusterGeom& cg, uint32_
     const uint32_t below_hi = hi >= 4 ? 0xFu : hi <= 0 ? 0u : (1u << hi) - 1u;
     const uint32_t from_lo = lo <= 0 ? 0xFu : (0xFu << lo) & 0xFu;
     mask = below_hi & from_lo;
+}
+
+// Which elements of slot u of a segment belong to it, when the segment is elements [r, r + len) of
+// the numbering that starts at its first group: bits max(lo, 0) .. min(hi, 4) - 1.
+__device__ __forceinline__ uint32_t ragged_mask(uint32_t r, uint32_t u, uint32_t len)
+{
+    const int32_t lo = (int32_t)r - 4 * (int32_t)u, hi = (int32_t)(len + r) - 4 * (int32_t)u;      // lo < hi
+    const int32_t l = lo < 0 ? 0 : (lo > 4 ? 4 : lo), h = hi < 0 ? 0 : (hi > 4 ? 4 : hi);
+    return ((1u << (h - l)) - 1u) << l;
 }
 
 __device__ __forceinline__ uint32_t ragged_slice_slots(const RaggedClusterGeom& cg, uint32_t s)
@@ -588,32 +650,60 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     const uint32_t nslots = ragged_slice_slots(cg, s);
     const bool short_tail = (cg.n & 3u) != 0u;                     // the array's last group is not whole
 
+    // The block's first segment starts at element sbase = 4 * jbase + e0; a later segment starts
+    // `rel` elements further on.  (Only the last of contiguous blocks may be short.)
+    const uint64_t sbase = (uint64_t)b * cg.inner;
+    const uint64_t jbase = sbase >> 2;
+    const uint32_t e0 = (uint32_t)sbase & 3u;
+    const uint32_t len = cg.block_groups == cg.seg_groups && sbase + cg.inner > cg.n ? (uint32_t)(cg.n - sbase) : cg.inner;
+    uint32_t o = 0u, u = t0 + threadIdx.x;                         // the thread's first slot: slot u of segment o
+    if (cg.block_groups != cg.seg_groups) {                        // (uniform; a contiguous block is one segment)
+        o = __umulhi(u, cg.magic_groups);                          // u / G or one more (u < 2^20)
+        u -= o * cg.seg_groups;
+        if ((int32_t)u < 0) {
+            o -= 1u;
+            u += cg.seg_groups;
+        }
+    }
+    uint32_t rel = o * cg.row_elems;
+
     // Every load is one unconditional dwordx4 inside the array, so that all sixteen are in flight
     // together: an unused slot reads the group before it, and the array's short last group reads
     // the array's last four elements instead (put right below, `shift` elements further on).
     uint4 v[GPT];
+    uint32_t where[GPT];                                           // group of each slot, counted from jbase: kept for the stores
     uint32_t shifts = 0u;
     uint32_t masks[2] = {0u, 0u};                                  // four bits per group
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
         const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
         v[k] = make_uint4(0u, 0u, 0u, 0u);
+        const uint32_t e = e0 + rel;
+        where[k] = (e >> 2) + u;
         if (t < nslots) {
-            uint64_t j;
-            uint32_t mask;
-            ragged_slot(cg, b, t0 + t, j, mask);
+            const uint32_t mask = ragged_mask(e & 3u, u, len);
             masks[k / 8] |= mask << (4 * (k % 8));
-            uint64_t at = 4u * j;
-            if (mask == 0u) at -= 4u;
-            if (at + 4u > cg.n) {
-                if (mask != 0u) shifts |= (uint32_t)(at + 4u - cg.n) << (2 * k);      // 1..3
-                at = cg.n - 4u;
+            const uint64_t j = jbase + where[k];
+            const uint32_t* src = in + 4u * j;
+            if (mask == 0u) src -= 4;
+            if (short_tail) {
+                const uint64_t at = (uint64_t)(src - in);
+                if (at + 4u > cg.n) {
+                    if (mask != 0u) shifts |= (uint32_t)(at + 4u - cg.n) << (2 * k);      // 1..3
+                    src = in + (cg.n - 4u);
+                }
             }
-            v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4_at_dword*>(in + at)));
+            v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4_at_dword*>(src)));
             if (k < PRE) {
                 const Words4 r = random_words(j, key, 0u);
                 parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
             }
+        }
+        u += cg.step_rest;
+        rel += cg.step_elems;
+        if (u >= cg.seg_groups) {
+            u -= cg.seg_groups;
+            rel += cg.row_elems;
         }
     }
     uint32_t m = 0;
@@ -652,17 +742,12 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     });
 
     const GridPlan p = block_plan(bm, wl, symmetric);
+    const bool finite = wave_plans_are_finite<MODE>(p);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        // (the group number is worked out again rather than kept: sixteen of them do not fit the
-        // registers next to sixteen groups; the empty asm keeps the compiler from finding out that it
-        // is the same computation)
-        uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
-        asm volatile("" : "+v"(t));
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
         if (t < nslots) {
-            uint64_t j;
-            uint32_t unused;
-            ragged_slot(cg, b, t0 + t, j, unused);
+            const uint64_t j = jbase + where[k];
             const uint32_t mask = (masks[k / 8] >> (4 * (k % 8))) & 0xFu;
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) {
@@ -671,7 +756,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
             } else if (MODE == QSIM_STOCHASTIC) {
                 r = random_words(j, key, 0u);
             }
-            const uint4 q = quantize_group_to_grid<MODE>(v[k], p, r);
+            const uint4 q = quantize_group_of_block<MODE>(v[k], p, r, finite);
             uint32_t* dst = out + 4u * j;
             if (mask == 0xFu) {
                 __builtin_nontemporal_store(to_u32x4(q), reinterpret_cast<u32x4_at_dword*>(dst));
@@ -756,7 +841,8 @@ __global__ __launch_bounds__(kThreads) void block_strided_packed_kernel(const ui
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (MODE == QSIM_STOCHASTIC) r = words[k];
             const GridPlan p = block_plan(blockmax[owner[k]], wl, symmetric);
-            __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(v[k], p, r)), reinterpret_cast<u32x4*>(out) + where[k]);
+            const bool finite = wave_plans_are_finite<MODE>(p);
+            __builtin_nontemporal_store(to_u32x4(quantize_group_of_block<MODE>(v[k], p, r, finite)), reinterpret_cast<u32x4*>(out) + where[k]);
         }
     }
 }

@@ -129,6 +129,7 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
         m = m > a ? m : a;
     }
     const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
+    const bool finite = wave_plans_are_finite<MODE>(p);
     const uint64_t len = block_length(sg, b);
     const uint64_t t0 = (uint64_t)blockIdx.y * sg.slice_len;
     const uint64_t t1 = (t0 + sg.slice_len < len) ? t0 + sg.slice_len : len;
@@ -138,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
             const uint4 v = load_group<true>(in, j, sg.g.n);
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
-            store_group<true>(out, j, sg.g.n, quantize_group_to_grid<MODE>(v, p, r));
+            store_group<true>(out, j, sg.g.n, quantize_group_of_block<MODE>(v, p, r, finite));
         }
     } else {
         for (uint64_t t = t0 + 4ull * threadIdx.x; t < t1; t += 4ull * kThreads) {
@@ -148,7 +149,7 @@ __global__ __launch_bounds__(kThreads) void block_apply_kernel(const uint32_t* i
                 const u32x4 w = __builtin_nontemporal_load(reinterpret_cast<const u32x4_at_dword*>(in + at));
                 Words4 r = {{0u, 0u, 0u, 0u}};
                 if (MODE == QSIM_STOCHASTIC) r = random_words_at(at, key, 0u);
-                __builtin_nontemporal_store(to_u32x4(quantize_group_to_grid<MODE>(to_uint4(w), p, r)),
+                __builtin_nontemporal_store(to_u32x4(quantize_group_of_block<MODE>(to_uint4(w), p, r, finite)),
                                             reinterpret_cast<u32x4_at_dword*>(out + at));
             } else {
                 for (uint64_t e = t; e < t + 4 && e < t1; ++e) {
@@ -317,6 +318,8 @@ __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint
             p[e] = block_plan(blockmax[col / cg.inner], wl, symmetric);
         }
     }
+    const bool finite = __all(plan_is_finite<MODE>(p[0]) && plan_is_finite<MODE>(p[1]) && plan_is_finite<MODE>(p[2]) &&
+                              plan_is_finite<MODE>(p[3]) ? 1 : 0) != 0;
     for (uint64_t o = o0; o < o1; o += 4) {
         uint4 v[4];
 #pragma unroll
@@ -329,10 +332,17 @@ __global__ __launch_bounds__(kThreads) void block_column_apply_kernel(const uint
                 Words4 r = {{0u, 0u, 0u, 0u}};
                 if (MODE == QSIM_STOCHASTIC) r = ALIGNED ? random_words(at >> 2, key, 0u) : random_words_at_shared(at, key, 0u);
                 uint4 q;
-                q.x = quantize_to_grid<MODE>(v[k].x, p[0], r.w[0]);
-                q.y = quantize_to_grid<MODE>(v[k].y, p[1], r.w[1]);
-                q.z = quantize_to_grid<MODE>(v[k].z, p[2], r.w[2]);
-                q.w = quantize_to_grid<MODE>(v[k].w, p[3], r.w[3]);
+                if (finite) {
+                    q.x = quantize_finite_to_grid<MODE>(v[k].x, p[0], r.w[0]);
+                    q.y = quantize_finite_to_grid<MODE>(v[k].y, p[1], r.w[1]);
+                    q.z = quantize_finite_to_grid<MODE>(v[k].z, p[2], r.w[2]);
+                    q.w = quantize_finite_to_grid<MODE>(v[k].w, p[3], r.w[3]);
+                } else {
+                    q.x = quantize_to_grid<MODE>(v[k].x, p[0], r.w[0]);
+                    q.y = quantize_to_grid<MODE>(v[k].y, p[1], r.w[1]);
+                    q.z = quantize_to_grid<MODE>(v[k].z, p[2], r.w[2]);
+                    q.w = quantize_to_grid<MODE>(v[k].w, p[3], r.w[3]);
+                }
                 if (have >= 4u) {
                     if (ALIGNED) __builtin_nontemporal_store(to_u32x4(q), reinterpret_cast<u32x4*>(out + at));
                     else __builtin_nontemporal_store(to_u32x4(q), reinterpret_cast<u32x4_at_dword*>(out + at));
@@ -366,14 +376,37 @@ struct FlatGeom {
     uint32_t row, inner, nblocks;
     uint32_t magic_row, magic_inner;   // floor(2^32 / d) + 1 (unused when d == 1)
     uint32_t wgs;
-    uint32_t copies;             // copies of the LDS table in pass 1: a power of two, 1..64, copies * nblocks <= 4096
+    uint32_t copies;             // copies of the LDS table in pass 1: a power of two, 1..64; copies * (nblocks rounded up to 4) <= 4096
     uint32_t stream_first;       // pass 1 reads with non-temporal loads (see ColumnGeom)
 };
+
+// Where block t sits in a table in LDS.  A lane's four elements are neighbours, so with inner == 1
+// the lanes of a wavefront ask for entries 4 * lane + e in one instruction: eight LDS banks out of
+// 32.  Moving the entry within its aligned run of four, by bits 5 and 6 of its number, spreads a
+// half-wavefront over all banks.
+__device__ __forceinline__ uint32_t flat_slot(uint32_t t) { return t ^ ((t >> 5) & 3u); }
 
 __device__ __forceinline__ uint32_t flat_block(const FlatGeom& fg, uint32_t pos /* < 2^16 */)
 {
     const uint32_t in_row = fg.row == 1u ? 0u : pos - __umulhi(pos, fg.magic_row) * fg.row;
     return fg.inner == 1u ? in_row : __umulhi(in_row, fg.magic_inner);
+}
+
+// The blocks of the four elements from position pos on: one reduction modulo the row, then steps of one.
+__device__ __forceinline__ void flat_blocks4(const FlatGeom& fg, uint32_t pos /* < 2^16 - 3 */, uint32_t (&b)[4])
+{
+    if (fg.row < 4u) {                                   // (uniform) four elements may wrap around more than once
+#pragma unroll
+        for (uint32_t e = 0; e < 4u; ++e) b[e] = flat_block(fg, pos + e);
+        return;
+    }
+    const uint32_t r0 = pos - __umulhi(pos, fg.magic_row) * fg.row;
+#pragma unroll
+    for (uint32_t e = 0; e < 4u; ++e) {
+        uint32_t r = r0 + e;
+        r = r >= fg.row ? r - fg.row : r;
+        b[e] = fg.inner == 1u ? r : __umulhi(r, fg.magic_inner);
+    }
 }
 
 // The groups of one step.  A step that lies wholly inside the array (all but the last) issues its
@@ -398,56 +431,76 @@ __device__ __forceinline__ void flat_load_step(const uint32_t* in, uint64_t base
     }
 }
 
-__global__ __launch_bounds__(kThreads) void block_flat_max_kernel(const uint32_t* in, uint32_t* partial, FlatGeom fg)
+__global__ __launch_bounds__(kThreads) void block_flat_max_kernel(const uint32_t* in, uint32_t* partial, uint32_t* blockmax,
+                                                                  FlatGeom fg)
 {
+    // (the fold that follows brings its results in with atomic maxima: the table they meet in starts at zero)
+    if (blockIdx.x == 0)
+        for (uint32_t t = threadIdx.x; t < fg.nblocks; t += kThreads) blockmax[t] = 0u;
     // Few blocks mean many lanes per block, and same-address LDS atomics of one instruction are
     // carried out one after the other: so the table is replicated, lane l works on copy l mod copies
-    // (copies * nblocks <= 4096), and the copies are folded at the end.
+    // (copies * nblocks, rounded up to four, <= 4096), and the copies are folded at the end.
     __shared__ uint32_t table[kFlatMaxBlocks];
     const uint32_t copies = fg.copies;
-    for (uint32_t t = threadIdx.x; t < fg.nblocks * copies; t += kThreads) table[t] = 0u;
+    const uint32_t room = (fg.nblocks + 3u) & ~3u;                  // of one copy: flat_slot stays within runs of four
+    for (uint32_t t = threadIdx.x; t < room * copies; t += kThreads) table[t] = 0u;
     __syncthreads();
-    uint32_t* mine = table + (threadIdx.x & (copies - 1u)) * fg.nblocks;
+    uint32_t* mine = table + (threadIdx.x & (copies - 1u)) * room;
     // steps are dealt out round-robin, so that at any moment the workgroups together read one
-    // contiguous front of the tensor
-    const uint64_t g1 = fg.groups;
-    for (uint64_t base = (uint64_t)blockIdx.x * kFlatStepGroups; base < g1; base += (uint64_t)fg.wgs * kFlatStepGroups) {
-        const uint32_t pos0 = (uint32_t)((base * 4) % fg.row);            // wave-uniform
-        uint4 v[kFlatGpt];
-        if (fg.stream_first) flat_load_step<true>(in, base, fg, v);               // wave-uniform
+    // contiguous front of the tensor; the loads of a workgroup's next step are under way while it
+    // works on this one
+    const uint64_t g1 = fg.groups, stride = (uint64_t)fg.wgs * kFlatStepGroups;
+    auto load = [&](uint64_t base, uint4 (&v)[kFlatGpt]) {
+        if (fg.stream_first) flat_load_step<true>(in, base, fg, v);                   // wave-uniform
         else flat_load_step<false>(in, base, fg, v);
+    };
+    auto fold = [&](uint64_t base, const uint4 (&v)[kFlatGpt]) {
+        const uint32_t pos0 = (uint32_t)((base * 4) % fg.row);            // wave-uniform
 #pragma unroll
         for (int k = 0; k < kFlatGpt; ++k) {
             const uint64_t j = base + threadIdx.x + (uint64_t)k * kThreads;
             if (j < g1) {
                 const uint32_t off = (threadIdx.x + (uint32_t)k * kThreads) * 4u;
                 if (fg.inner % 4u == 0u) {                                    // a group never straddles blocks
-                    atomicMax(&mine[flat_block(fg, pos0 + off)], max4_mag(v[k]));
+                    atomicMax(&mine[flat_slot(flat_block(fg, pos0 + off))], max4_mag(v[k]));
                 } else {
                     const uint32_t mag[4] = {v[k].x & 0x7fffffffu, v[k].y & 0x7fffffffu, v[k].z & 0x7fffffffu,
                                              v[k].w & 0x7fffffffu};
-                    uint32_t prev = flat_block(fg, pos0 + off), m = mag[0];
+                    uint32_t b[4];                                            // (elements past the end read as zero; their block number is still a valid one)
+                    flat_blocks4(fg, pos0 + off, b);
+                    uint32_t prev = b[0], m = mag[0];
 #pragma unroll
                     for (uint32_t e = 1; e < 4; ++e) {
-                        // elements past the end read as zero; their block number is still a valid one
-                        const uint32_t b = flat_block(fg, pos0 + off + e);
-                        if (b != prev) {
-                            atomicMax(&mine[prev], m);
+                        if (b[e] != prev) {
+                            atomicMax(&mine[flat_slot(prev)], m);
                             m = 0u;
-                            prev = b;
+                            prev = b[e];
                         }
                         m = m > mag[e] ? m : mag[e];
                     }
-                    atomicMax(&mine[prev], m);
+                    atomicMax(&mine[flat_slot(prev)], m);
                 }
             }
         }
+    };
+    // (two sets of registers take turns, so that nothing waits for the loads of the step ahead)
+    uint64_t base = (uint64_t)blockIdx.x * kFlatStepGroups;
+    uint4 even[kFlatGpt], odd[kFlatGpt];
+    if (base < g1) load(base, even);
+    while (base < g1) {
+        const uint64_t second = base + stride, third = second + stride;
+        if (second < g1) load(second, odd);
+        fold(base, even);
+        if (second >= g1) break;
+        if (third < g1) load(third, even);
+        fold(second, odd);
+        base = third;
     }
     __syncthreads();
     for (uint32_t t = threadIdx.x; t < fg.nblocks; t += kThreads) {
-        uint32_t m = table[t];
+        uint32_t m = table[flat_slot(t)];
         for (uint32_t c = 1; c < copies; ++c) {
-            const uint32_t a = table[c * fg.nblocks + t];
+            const uint32_t a = table[c * room + flat_slot(t)];
             m = m > a ? m : a;
         }
         partial[(uint64_t)blockIdx.x * fg.nblocks + t] = m;
@@ -474,20 +527,59 @@ __global__ __launch_bounds__(kThreads) void block_fold_rows_kernel(const uint32_
     dst[(uint64_t)p * nblocks + b] = m;
 }
 
+// blockmax[b] = max over all `rows` rows k of src[k * nblocks + b] in ONE launch, for any number of
+// rows: workgroup (x, y) takes 32 neighbouring blocks (one cache line of a row) and 64 rows, eight
+// rows per thread, all eight loads in flight; the eight parts meet in LDS and the result joins
+// blockmax[b] by one atomic maximum (rows / 64 of them per block).  blockmax must hold zeros.
+constexpr uint32_t kFoldOnceRows = 64;
+
+__global__ __launch_bounds__(kThreads) void block_fold_rows_once_kernel(const uint32_t* src, uint32_t* blockmax, uint32_t nblocks,
+                                                                        uint32_t rows)
+{
+    __shared__ uint32_t part[kThreads / 32][32];
+    const uint32_t c = threadIdx.x & 31u, p = threadIdx.x >> 5;
+    const uint32_t b = blockIdx.x * 32u + c;
+    const uint32_t k0 = blockIdx.y * kFoldOnceRows + p * 8u;
+    uint32_t a[8];
+#pragma unroll
+    for (uint32_t k = 0; k < 8u; ++k) a[k] = b < nblocks && k0 + k < rows ? src[(uint64_t)(k0 + k) * nblocks + b] : 0u;
+    uint32_t m = 0;
+#pragma unroll
+    for (uint32_t k = 0; k < 8u; ++k) m = m > a[k] ? m : a[k];
+    part[p][c] = m;
+    __syncthreads();
+    if (p == 0u && b < nblocks) {
+#pragma unroll
+        for (uint32_t q = 1; q < kThreads / 32; ++q) m = m > part[q][c] ? m : part[q][c];
+        if (m != 0u) __hip_atomic_fetch_max(&blockmax[b], m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void block_flat_apply_kernel(const uint32_t* in, uint32_t* out, const uint32_t* blockmax,
                                                                     FlatGeom fg, int wl, int symmetric, RngKey key)
 {
     __shared__ uint32_t table[kFlatMaxBlocks];
-    for (uint32_t t = threadIdx.x; t < fg.nblocks; t += kThreads) table[t] = blockmax[t];
-    __syncthreads();
+    int all_finite = 1;
+    for (uint32_t t = threadIdx.x; t < fg.nblocks; t += kThreads) {
+        const uint32_t m = blockmax[t];
+        table[flat_slot(t)] = m;
+        if (!plan_is_finite<MODE>(block_plan(m, wl, symmetric))) all_finite = 0;
+    }
+    // no block of the tensor holds Inf or NaN (nearly always): the table then holds exponent fields,
+    // from which a plan per element is cheap
+    const bool finite = __syncthreads_and(all_finite) != 0;
+    if (finite) {
+        for (uint32_t t = threadIdx.x; t < fg.nblocks; t += kThreads) table[flat_slot(t)] = clamped_field23(table[flat_slot(t)]);
+        __syncthreads();
+    }
+    const FieldPlan fp = field_plan(wl, symmetric);
     // steps are dealt out round-robin, so that at any moment the workgroups together read one
-    // contiguous front of the tensor
-    const uint64_t g1 = fg.groups;
-    for (uint64_t base = (uint64_t)blockIdx.x * kFlatStepGroups; base < g1; base += (uint64_t)fg.wgs * kFlatStepGroups) {
+    // contiguous front of the tensor; the loads of a workgroup's next step are under way while it
+    // works on this one
+    const uint64_t g1 = fg.groups, stride = (uint64_t)fg.wgs * kFlatStepGroups;
+    auto apply = [&](uint64_t base, const uint4 (&v)[kFlatGpt]) {
         const uint32_t pos0 = (uint32_t)((base * 4) % fg.row);            // wave-uniform
-        uint4 v[kFlatGpt];
-        flat_load_step<true>(in, base, fg, v);
 #pragma unroll
         for (int k = 0; k < kFlatGpt; ++k) {
             const uint64_t j = base + threadIdx.x + (uint64_t)k * kThreads;
@@ -497,16 +589,40 @@ __global__ __launch_bounds__(kThreads) void block_flat_apply_kernel(const uint32
                 if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
                 uint4 o;
                 if (fg.inner % 4u == 0u) {
-                    o = quantize_group_to_grid<MODE>(v[k], block_plan(table[flat_block(fg, pos0 + off)], wl, symmetric), r);
+                    const uint32_t entry = table[flat_slot(flat_block(fg, pos0 + off))];
+                    o = finite ? quantize_group_of_block<MODE>(v[k], plan_of_field(entry, fp), r, true)
+                               : quantize_group_to_grid<MODE>(v[k], block_plan(entry, wl, symmetric), r);
                 } else {
-                    o.x = quantize_to_grid<MODE>(v[k].x, block_plan(table[flat_block(fg, pos0 + off)], wl, symmetric), r.w[0]);
-                    o.y = quantize_to_grid<MODE>(v[k].y, block_plan(table[flat_block(fg, pos0 + off + 1u)], wl, symmetric), r.w[1]);
-                    o.z = quantize_to_grid<MODE>(v[k].z, block_plan(table[flat_block(fg, pos0 + off + 2u)], wl, symmetric), r.w[2]);
-                    o.w = quantize_to_grid<MODE>(v[k].w, block_plan(table[flat_block(fg, pos0 + off + 3u)], wl, symmetric), r.w[3]);
+                    uint32_t b[4];
+                    flat_blocks4(fg, pos0 + off, b);
+                    if (finite) {
+                        o.x = quantize_finite_to_grid<MODE>(v[k].x, plan_of_field(table[flat_slot(b[0])], fp), r.w[0]);
+                        o.y = quantize_finite_to_grid<MODE>(v[k].y, plan_of_field(table[flat_slot(b[1])], fp), r.w[1]);
+                        o.z = quantize_finite_to_grid<MODE>(v[k].z, plan_of_field(table[flat_slot(b[2])], fp), r.w[2]);
+                        o.w = quantize_finite_to_grid<MODE>(v[k].w, plan_of_field(table[flat_slot(b[3])], fp), r.w[3]);
+                    } else {
+                        o.x = quantize_to_grid<MODE>(v[k].x, block_plan(table[flat_slot(b[0])], wl, symmetric), r.w[0]);
+                        o.y = quantize_to_grid<MODE>(v[k].y, block_plan(table[flat_slot(b[1])], wl, symmetric), r.w[1]);
+                        o.z = quantize_to_grid<MODE>(v[k].z, block_plan(table[flat_slot(b[2])], wl, symmetric), r.w[2]);
+                        o.w = quantize_to_grid<MODE>(v[k].w, block_plan(table[flat_slot(b[3])], wl, symmetric), r.w[3]);
+                    }
                 }
                 store_group<false>(out, j, fg.n, o);
             }
         }
+    };
+    // (two sets of registers take turns, so that nothing waits for the loads of the step ahead)
+    uint64_t base = (uint64_t)blockIdx.x * kFlatStepGroups;
+    uint4 even[kFlatGpt], odd[kFlatGpt];
+    if (base < g1) flat_load_step<true>(in, base, fg, even);
+    while (base < g1) {
+        const uint64_t second = base + stride, third = second + stride;
+        if (second < g1) flat_load_step<true>(in, second, fg, odd);
+        apply(base, even);
+        if (second >= g1) break;
+        if (third < g1) flat_load_step<true>(in, third, fg, even);
+        apply(second, odd);
+        base = third;
     }
 }
 
@@ -596,6 +712,7 @@ __global__ __launch_bounds__(kThreads) void block_slice_apply_kernel(const uint3
             m = m > a ? m : a;
         }
         const GridPlan p = block_plan(workgroup_max(m, lds), wl, symmetric);
+        const bool finite = wave_plans_are_finite<MODE>(p);
         const SliceView sv = slice_view(sg, b, blockIdx.x);
         for (uint64_t base = threadIdx.x; base < sv.groups; base += kTileGroups) {
             uint4 v[4];
@@ -610,7 +727,7 @@ __global__ __launch_bounds__(kThreads) void block_slice_apply_kernel(const uint3
                 if (t < sv.groups) {
                     Words4 r = {{0u, 0u, 0u, 0u}};
                     if (MODE == QSIM_STOCHASTIC) r = random_words(sv.j0 + t, key, 0u);
-                    store_group<true>(out, sv.j0 + t, sv.end, quantize_group_to_grid<MODE>(v[k], p, r));
+                    store_group<true>(out, sv.j0 + t, sv.end, quantize_group_of_block<MODE>(v[k], p, r, finite));
                 }
             }
         }

@@ -125,6 +125,8 @@ struct GridPlan {
     int q;                // grid step 2^q
     float lo, hi;         // most negative and largest value (grid points), or -Inf / +Inf
     float thr;            // magnitudes not below thr are returned unchanged
+    float anchor;         // 2^(q+23) when every input is known to be finite and that power exists, else 0
+    int finite;           // every input is known to be finite: nothing is returned unchanged
 };
 
 constexpr int kClassNaN = 0x003;
@@ -141,6 +143,35 @@ __device__ __forceinline__ uint32_t quantize_to_grid(uint32_t bits, const GridPl
     return keep ? bits : res;
 }
 
+// The same for inputs that are all finite and a saturating plan (a block whose largest magnitude
+// is finite): no NaN, nothing at or above thr = +Inf, so nothing is returned unchanged.
+// Round to nearest even with an anchor A = 2^(q+23): the clamped magnitude a is at most
+// 2^(q+wl-1) <= A, so a + A lies in [A, 2A], where fp32 numbers are spaced 2^q apart: the addition
+// itself rounds a to the nearest multiple of 2^q, ties to the even multiple (A / 2^q is even), and
+// taking A away again is exact.  Two additions instead of scale, round, scale back.
+template <int MODE>
+__device__ __forceinline__ uint32_t quantize_finite_to_grid(uint32_t bits, const GridPlan& p, uint32_t r)
+{
+    const float x = __uint_as_float(bits);
+    const float a = __builtin_fabsf(__builtin_amdgcn_fmed3f(x, p.lo, p.hi));
+    float v;
+    if (MODE == QSIM_RN_EVEN) {
+        float sum = a + p.anchor;
+        asm("" : "+v"(sum));                        // (the two additions must stay two additions)
+        v = sum - p.anchor;
+    } else {
+        v = __builtin_ldexpf(round_scaled<MODE>(__builtin_ldexpf(a, -p.q), r), p.q);
+    }
+    return (__float_as_uint(v) & 0x7fffffffu) | (bits & 0x80000000u);
+}
+
+// Whether quantize_finite_to_grid may stand in for quantize_to_grid under this plan.
+template <int MODE>
+__device__ __forceinline__ bool plan_is_finite(const GridPlan& p)
+{
+    return MODE == QSIM_RN_EVEN ? p.anchor != 0.0f : p.finite != 0;
+}
+
 // Grid plan of a block from the largest magnitude encoding found in it.
 __device__ __forceinline__ GridPlan block_plan(uint32_t max_mag, int wl, int symmetric)
 {
@@ -154,6 +185,48 @@ __device__ __forceinline__ GridPlan block_plan(uint32_t max_mag, int wl, int sym
     p.hi = __uint_as_float(pos);
     p.lo = __uint_as_float(neg | 0x80000000u);
     p.thr = __builtin_inff();
+    p.finite = max_mag < 0x7f800000u ? 1 : 0;
+    const int anchor_field = p.q + 23 + 127;         // at least 2: q >= 1 - 125 - 24
+    p.anchor = p.finite && anchor_field <= 254 ? __uint_as_float((uint32_t)anchor_field << 23) : 0.0f;
+    return p;
+}
+
+// The same plan for kernels that keep a table of blocks and take a plan per element: every constant
+// of the plan is f23 = (exponent field of the block's largest magnitude, clamped to 1..254) << 23
+// with a constant of the format or'ed or added in, so the table holds f23 and a plan costs three
+// operations.  Only for blocks for which plan_is_finite holds (the anchor exists, nothing is NaN).
+struct FieldPlan {
+    uint32_t hi_or;        // the top wl - 2 fraction bits
+    uint32_t lo_add;       // sign and: the same bits (symmetric), or one more in the exponent field
+    uint32_t anchor_add;   // (25 - wl) << 23
+    int q_add;             // -125 - wl
+};
+
+__device__ __forceinline__ FieldPlan field_plan(int wl, int symmetric)
+{
+    FieldPlan c;
+    c.hi_or = ((1u << (wl - 2)) - 1u) << (25 - wl);
+    c.lo_add = 0x80000000u + (symmetric ? c.hi_or : 0x00800000u);
+    c.anchor_add = (uint32_t)(25 - wl) << 23;
+    c.q_add = -125 - wl;
+    return c;
+}
+
+__device__ __forceinline__ uint32_t clamped_field23(uint32_t max_mag)
+{
+    const uint32_t field = max_mag >> 23;
+    return (field < 1u ? 1u : (field > 254u ? 254u : field)) << 23;
+}
+
+__device__ __forceinline__ GridPlan plan_of_field(uint32_t f23, const FieldPlan& c)
+{
+    GridPlan p;
+    p.q = (int)(f23 >> 23) + c.q_add;
+    p.hi = __uint_as_float(f23 | c.hi_or);
+    p.lo = __uint_as_float(f23 + c.lo_add);
+    p.thr = __builtin_inff();
+    p.anchor = __uint_as_float(f23 + c.anchor_add);
+    p.finite = 1;
     return p;
 }
 

@@ -70,6 +70,8 @@ inline GridPlan fixed_plan(int wl, int fl, uint32_t flags)
         p.lo = -INFINITY;
         p.thr = (p.q + 24 <= 127) ? (float)ldexp(1.0, p.q + 24) : INFINITY;
     }
+    p.anchor = 0.0f;                                  // inputs of an elementwise call may be anything
+    p.finite = 0;
     return p;
 }
 

@@ -92,6 +92,28 @@ __device__ __forceinline__ uint4 quantize_group_to_grid(const uint4& v, const Gr
     return o;
 }
 
+// A block's group under the block's plan.  `finite` says that plan_is_finite holds and must be the
+// same in every lane of the wavefront: blocks without Inf and NaN, all but a few, take the short
+// form of the quantizer.
+template <int MODE>
+__device__ __forceinline__ uint4 quantize_group_of_block(const uint4& v, const GridPlan& p, const Words4& r, bool finite)
+{
+    if (!finite) return quantize_group_to_grid<MODE>(v, p, r);
+    uint4 o;
+    o.x = quantize_finite_to_grid<MODE>(v.x, p, r.w[0]);
+    o.y = quantize_finite_to_grid<MODE>(v.y, p, r.w[1]);
+    o.z = quantize_finite_to_grid<MODE>(v.z, p, r.w[2]);
+    o.w = quantize_finite_to_grid<MODE>(v.w, p, r.w[3]);
+    return o;
+}
+
+// plan_is_finite agreed on by the wavefront (plans may differ from lane to lane).
+template <int MODE>
+__device__ __forceinline__ bool wave_plans_are_finite(const GridPlan& p)
+{
+    return __all(plan_is_finite<MODE>(p) ? 1 : 0) != 0;
+}
+
 // Geometry of the [outer, nblocks, inner] view.  A block's elements are numbered t = o * inner + i;
 // element t of block b sits at flat index (o * nblocks + b) * inner + i.
 struct BlockGeom {

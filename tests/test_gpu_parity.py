@@ -688,6 +688,64 @@ def test_block_with_nonfinite_elements():
     _block_case(x, 1, 1, 4 * 2048, 8, STOCHASTIC)
 
 
+# One view per kernel form of the block quantizer (named by what the form is chosen for).
+BLOCK_FORMS = [
+    (1, 96, 1280),            # contiguous rows, several per workgroup, in registers
+    (1, 600, 7),              # contiguous rows of odd length
+    (1, 3, 70001),            # long odd rows: single pass block by block over odd segments
+    (1, 1, 3000000),          # whole tensor: single pass over resident workgroups
+    (1, 40, 262144),          # long aligned rows: single pass block by block
+    (64, 96, 3136),           # per channel, aligned segments: single pass block by block
+    (40, 64, 3025),           # per channel, odd segments
+    (32, 128, 256),           # per channel, one large workgroup per block
+    (2, 3000, 64),            # short blocks along an inner dimension, packed
+    (3000, 24, 1),            # short rows: the flat form, one element per block and row
+    (3000, 9, 4),             # the flat form, whole groups
+    (700, 13, 3),             # the flat form, odd segments
+    (129, 5000, 1),           # columns
+    (50, 700, 19),            # columns, odd segments
+    (27, 6, 20711),           # the general two passes
+]
+
+
+@pytest.mark.parametrize("rounding", [RN_EVEN, RN_AWAY, STOCHASTIC])
+@pytest.mark.parametrize("shape", BLOCK_FORMS, ids=lambda s: "x".join(map(str, s)))
+def test_block_forms_with_finite_and_with_other_blocks(shape, rounding):
+    """Every form quantizes a block without Inf and NaN by a shorter sequence than one with them
+    (nearest-even additionally needs the block's exponent to leave room for an anchor 2^(q+23)).
+    The same tensor four times: all finite; one NaN; one Inf and one -Inf in different blocks; one
+    block whose largest magnitude is near the top of fp32."""
+    outer, nblocks, inner = shape
+    n = outer * nblocks * inner
+    base = W.normal_tensor(n, seed=n % 1000 + 17)
+    for case in range(4):
+        x = base.copy()
+        if case == 1:
+            x[(2 * n) // 3] = np.nan
+        elif case == 2:
+            x[n // 5] = np.inf
+            x[n - 1 - n // 7] = -np.inf
+        elif case == 3:
+            x[n // 2] = np.float32(-3.1e38)
+            x[n // 2 + 1 if n // 2 + 1 < n else 0] = np.float32(1.7e35)
+        for flags in (0, SYMMETRIC):
+            _block_case(x, outer, nblocks, inner, 8, rounding, flags=flags, seed=77 + case, stream_id=5)
+
+
+@pytest.mark.parametrize("wl,rounding,flags", [(8, RN_EVEN, 0), (24, RN_EVEN, SYMMETRIC)])
+def test_block_every_encoding_below_the_shared_exponent(wl, rounding, flags):
+    """Blocks whose shared exponent is 0 (each row ends in +-1.5 and two more values of that binade)
+    over every non-negative fp32 encoding below 2.0, and a sample of the negative ones: the
+    nearest-even form that rounds by adding and subtracting 2^(q+23), against the oracle."""
+    rows, cols = 64, 1 << 20
+    tail = np.array([1.5, -1.5, 1.0, -1.9999999], dtype=np.float32)
+    starts = list(range(0, 0x40000000, rows * cols)) + [0x80000000, 0xB0000000, 0xBC000000]
+    for start in starts:
+        body = np.arange(start, start + rows * cols, dtype=np.uint64).astype(np.uint32).view(np.float32).reshape(rows, cols)
+        x = np.concatenate([body, np.tile(tail, (rows, 1))], axis=1).reshape(-1)
+        _block_case(x, 1, rows, cols + 4, wl, rounding, flags=flags)
+
+
 # ------------------------------------------------------------------------------------------------
 # fused SGD step
 # ------------------------------------------------------------------------------------------------
