@@ -191,33 +191,44 @@ def block_workspace_bytes(n, outer, nblocks, inner) -> int:
 
 
 _scratch = {}                    # (device index, stream handle) -> uint8 tensor, reused by calls on that stream
-_kept = {}                       # (device index, stream handle, n, outer, nblocks, inner) -> zero-filled uint8 tensor
+_kept = {}                       # (device index, stream handle, n, outer, nblocks, inner) -> what _workspace returns: the
+                                 # pointer, size and tensor of a zero-filled buffer and the flag, or zeros for a shape that needs none
 _SCRATCH_KEEP = 64 << 20         # larger scratch is allocated per call and released with it
 _KEPT_LIMIT = 4 << 20            # a shape whose scratch is larger shares the stream's scratch instead
 
 
-def _workspace(x, outer, nblocks, inner, workspace, may_keep=False):
+def _workspace(x, outer, nblocks, inner, workspace, may_keep=False, stream=None):
     """Scratch for a block call: (pointer, bytes, the tensor that owns them, QSIM_WORKSPACE_KEPT or 0)."""
-    need = block_workspace_bytes(x.numel(), outer, nblocks, inner)
+    n = x.numel()
+    if workspace is None and may_keep:
+        # the common case first: a shape seen before on this stream (a call on a small tensor is bound
+        # by what the host does per call)
+        capturing = torch.cuda.is_current_stream_capturing()
+        key = (x.device.index, _stream() if stream is None else stream, n, outer, nblocks, inner)
+        entry = _kept.get(key)
+        if entry is not None and not capturing:
+            return entry
+    need = block_workspace_bytes(n, outer, nblocks, inner)
     if not need:
+        if workspace is None and may_keep and not capturing:
+            _kept[key] = (0, 0, None, 0)
         return 0, 0, None, 0
     kept = 0
     if workspace is None:
-        capturing = torch.cuda.is_current_stream_capturing()
+        if not may_keep:
+            capturing = torch.cuda.is_current_stream_capturing()
         if may_keep and need <= _KEPT_LIMIT and not capturing:
             # one zero-filled buffer per stream and shape, written by nothing but these calls: the
             # library then keeps its counters in it from call to call and launches no clearing kernel
-            key = (x.device.index, _stream(), x.numel(), outer, nblocks, inner)
-            workspace = _kept.get(key)
-            if workspace is None:
-                workspace = _kept[key] = torch.zeros(need, dtype=torch.uint8, device=x.device)
-            kept = WORKSPACE_KEPT
-        elif need > _SCRATCH_KEEP or capturing:
+            workspace = torch.zeros(need, dtype=torch.uint8, device=x.device)
+            entry = _kept[key] = (workspace.data_ptr(), need, workspace, WORKSPACE_KEPT)
+            return entry
+        if need > _SCRATCH_KEEP or capturing:
             # (memory allocated during a graph capture belongs to the graph: never shared with eager calls)
             workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
         else:
             # calls on one stream run one after the other, so they can share a scratch buffer
-            key = (x.device.index, _stream())
+            key = (x.device.index, _stream() if stream is None else stream)
             workspace = _scratch.get(key)
             if workspace is None or workspace.numel() < need:
                 workspace = torch.empty(max(need, 1 << 20), dtype=torch.uint8, device=x.device)
@@ -237,14 +248,15 @@ def block_quantize(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=0, seed
     ``x`` is a shard of whole blocks (qsim_block_quantize_at)."""
     _device_f32(x, "x")
     out = _out_like(x, out)
-    ws_ptr, ws_bytes, workspace, kept = _workspace(x, outer, nblocks, inner, workspace, may_keep=True)
+    stream = _stream()
+    ws_ptr, ws_bytes, workspace, kept = _workspace(x, outer, nblocks, inner, workspace, may_keep=True, stream=stream)
     flags |= kept
     if index0:
         _check(lib().qsim_block_quantize_at(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, index0, wl,
-                                            rounding, flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
+                                            rounding, flags, seed, stream_id, ws_ptr, ws_bytes, stream))
     else:
         _check(lib().qsim_block_quantize(x.data_ptr(), out.data_ptr(), x.numel(), outer, nblocks, inner, wl, rounding,
-                                         flags, seed, stream_id, ws_ptr, ws_bytes, _stream()))
+                                         flags, seed, stream_id, ws_ptr, ws_bytes, stream))
     return out
 
 
@@ -262,7 +274,8 @@ def block_quantize_static(x, outer, nblocks, inner, wl, rounding=RN_EVEN, flags=
 def kept_workspace(x, outer, nblocks, inner):
     """The zero-filled scratch the binding keeps for block_quantize calls of this shape on the
     current stream (None before the first such call, or when the shape needs none)."""
-    return _kept.get((x.device.index, _stream(), x.numel(), outer, nblocks, inner))
+    entry = _kept.get((x.device.index, _stream(), x.numel(), outer, nblocks, inner))
+    return None if entry is None else entry[2]
 
 
 def workspace_timeouts(workspace) -> int:
