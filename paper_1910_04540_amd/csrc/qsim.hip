@@ -92,6 +92,9 @@ struct BlockSchedule {
     bool cluster;          // many contiguous blocks of up to 64 register-resident slices each: single pass per block
     bool strided_packed;   // outer > 1, whole-group segments, blocks of at most 2048 elements: several per workgroup
     StridedPackedGeom spg;
+    bool ragged_runs;      // the same for segments of any length and alignment (the arrays' own groups, shared edge groups)
+    int ragged_runs_gpt;   // groups per thread: 8, or 16 when a block needs that many
+    RaggedRunsGeom rrg;
     bool strided_cluster;  // outer > 1, aligned segments of >= 64 elements, blocks of up to 256 slices: the same
     StridedClusterGeom scg;
     bool strided_ragged;   // outer > 1, segments of >= 64 elements of any length and alignment: the same
@@ -269,6 +272,32 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         s.spg.blocks_per_wg = 1024u / s.spg.groups_per_block;
     }
     // (these two forms count groups and elements from a block's start in 32 bits)
+    if (outer > 1 && (outer <= 16 || n <= kPackedSmallTensor) && s.sg.block_len <= 2048) {
+        // every run of a workgroup gets (rows * inner + 6) / 4 + 1 group slots; as many blocks as 2048
+        // slots hold, or 4096 when not even one fits
+        for (int gpt = 8; gpt <= 16 && !s.ragged_runs; gpt *= 2) {
+            const uint64_t per_run = (uint64_t)kThreads * gpt / outer;            // slots a run may take
+            if (per_run < 3) continue;
+            uint64_t rows = (4 * (per_run - 1) - 6) / inner;                       // (rows * inner + 6) / 4 + 1 <= per_run
+            if (rows * inner > 65535) rows = 65535 / inner;
+            if (rows > (uint64_t)kRaggedMaxRows) rows = kRaggedMaxRows;
+            if (rows > nblocks) rows = nblocks;
+            if (rows * inner < 64) continue;            // (runs of a few elements: the forms that walk the tensor front to back do better)
+            // a small tensor is spread over at least 1024 workgroups, as long as the runs keep 64 elements
+            const uint64_t fewest = (63 + inner) / inner, spread = nblocks / 1024 > fewest ? nblocks / 1024 : fewest;
+            if (rows > spread) rows = spread;
+            s.ragged_runs = true;
+            s.ragged_runs_gpt = gpt;
+            s.rrg.n = n;
+            s.rrg.nblocks = nblocks;
+            s.rrg.outer = (uint32_t)outer;
+            s.rrg.inner = (uint32_t)inner;
+            s.rrg.rows_per_wg = (uint32_t)rows;
+            s.rrg.run_slots = (uint32_t)((rows * inner + 6) / 4 + 1);
+            s.rrg.magic_slots = (uint32_t)((1ull << 32) / s.rrg.run_slots) + 1u;
+            s.rrg.magic_inner = inner > 1 ? (uint32_t)((1ull << 32) / inner) + 1u : 0u;
+        }
+    }
     if (outer > 1 && inner % 4 == 0 && inner >= 64 && inner <= (1ull << 22) && n < (1ull << 34) &&
         s.sg.block_len <= (uint64_t)kStridedMaxSlices * kStridedSliceLen) {
         const uint64_t slices_each = (s.sg.block_len + kStridedSliceLen - 1) / kStridedSliceLen;
@@ -364,7 +393,7 @@ constexpr int kResidentPerCu = 4;
 template <int MODE, int GPT>
 static uint32_t resident_capacity()
 {
-    static std::atomic<int> cache[64];          // per device; 0 = not asked yet, -1 = unknown
+    static std::atomic<int> cache[64];          // per device; 0 = not known yet
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
     int c = cache[dev].load(std::memory_order_relaxed);
@@ -374,12 +403,17 @@ static uint32_t resident_capacity()
             hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)block_resident_kernel<MODE, GPT>, kThreads,
                                                          0) == hipSuccess &&
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess;
-        if (!ok) (void)hipGetLastError();
+        // (a query that fails, say in a state of the runtime that does not allow it, is asked again by the
+        // next call: this one takes the two-pass form)
+        if (!ok || per_cu <= 0 || cus <= 0) {
+            (void)hipGetLastError();
+            return 0u;
+        }
         if (per_cu > kResidentPerCu) per_cu = kResidentPerCu;
-        c = ok && per_cu > 0 && cus > 0 ? per_cu * cus : -1;
+        c = per_cu * cus;
         cache[dev].store(c, std::memory_order_relaxed);
     }
-    return c > 0 ? (uint32_t)c : 0u;
+    return (uint32_t)c;
 }
 
 // Tries the single-pass form with GPT groups per thread; false = does not fit (nothing launched).
@@ -569,6 +603,15 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         const uint64_t wgs = (g.nblocks + s.spg.blocks_per_wg - 1) / s.spg.blocks_per_wg;
         hipLaunchKernelGGL((block_strided_packed_kernel<MODE>), folded(wgs), dim3(kThreads), 0, stream, pin, pout, s.spg, wl,
                            symmetric, key);
+    } else if (s.ragged_runs) {
+        // the same for segments that are not whole groups, or in arrays that are only dword aligned
+        const uint64_t wgs = (g.nblocks + s.rrg.rows_per_wg - 1) / s.rrg.rows_per_wg;
+        if (s.ragged_runs_gpt == 8)
+            hipLaunchKernelGGL((block_ragged_runs_kernel<MODE, 8>), folded(wgs), dim3(kThreads), 0, stream, pin, pout, s.rrg, wl,
+                               symmetric, key);
+        else
+            hipLaunchKernelGGL((block_ragged_runs_kernel<MODE, 16>), folded(wgs), dim3(kThreads), 0, stream, pin, pout, s.rrg, wl,
+                               symmetric, key);
     } else if (vec && s.strided_cluster && !(short_segments && g.inner % 16 != 0) &&
                resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // single pass, block by block (see the kernel): the workgroups of a block must fit together

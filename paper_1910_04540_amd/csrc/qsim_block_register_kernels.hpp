@@ -200,6 +200,142 @@ __global__ __launch_bounds__(kThreads) void block_ragged_kernel(const uint32_t* 
     }
 }
 
+// The same for SHORT blocks along an inner dimension whose segments are not whole groups, or in arrays
+// that are only dword aligned ([2, 100000, 154] with one block per middle index; per-channel blocks
+// of a small batch of 7 x 7 maps): a workgroup owns `rows_per_wg` consecutive blocks, whose segments
+// are neighbours in memory for a fixed outer index: `outer` contiguous runs, each walked in the
+// array's own groups like the single range of block_ragged_kernel.  Every run is given `run_slots`
+// group slots, the most it can cover at any alignment; slot t of the workgroup is slot t mod
+// run_slots of run t div run_slots (unused when the run covers fewer groups).  One pass, one launch.
+struct RaggedRunsGeom {
+    uint64_t n, nblocks;
+    uint32_t outer, inner;
+    uint32_t rows_per_wg;      // at most kRaggedMaxRows; rows_per_wg * inner < 2^16
+    uint32_t run_slots;        // (rows_per_wg * inner + 6) / 4 + 1 ... outer * run_slots <= kThreads * GPT
+    uint32_t magic_slots;      // floor(2^32 / run_slots) + 1
+    uint32_t magic_inner;      // floor(2^32 / inner) + 1 (any value when inner == 1)
+};
+
+template <int MODE, int GPT>
+__global__ __launch_bounds__(kThreads) void block_ragged_runs_kernel(const uint32_t* in, uint32_t* out, RaggedRunsGeom rg, int wl,
+                                                                     int symmetric, RngKey key)
+{
+    __shared__ uint32_t rowmax[kRaggedMaxRows];
+    const uint64_t r0 = linear_block() * rg.rows_per_wg;
+    if (r0 >= rg.nblocks) return;                     // the whole workgroup leaves together
+    const uint32_t nrows = rg.nblocks - r0 < rg.rows_per_wg ? (uint32_t)(rg.nblocks - r0) : rg.rows_per_wg;
+    const uint32_t span = nrows * rg.inner;           // elements of one run
+    const uint32_t nslots = rg.outer * rg.run_slots;
+    const uint32_t inner = rg.inner;
+
+    for (uint32_t t = threadIdx.x; t < nrows; t += kThreads) rowmax[t] = 0u;
+    __syncthreads();
+
+    // slot t: its group in the array, and how many elements of the run's first group come before the run
+    auto slot = [&](uint32_t t, uint64_t& j, uint32_t& u, uint32_t& lead) {
+        const uint32_t o = __umulhi(t, rg.magic_slots);                  // exact: t < 2^16
+        u = t - o * rg.run_slots;
+        const uint64_t e0 = ((uint64_t)o * rg.nblocks + r0) * inner;    // first element of the run
+        lead = (uint32_t)e0 & 3u;
+        j = (e0 >> 2) + u;
+    };
+
+    uint4 v[GPT];
+    uint32_t rows01[GPT], rows23[GPT];       // block of each element relative to r0, 16 bits each (clamped outside the run)
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 4 ? GPT : 4) : 0;
+    Words4 early[PRE > 0 ? PRE : 1];         // random words of the first groups, drawn while the loads are in flight
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        v[k] = make_uint4(0u, 0u, 0u, 0u);
+        if (t < nslots) {
+            uint64_t j;
+            uint32_t u, lead;
+            slot(t, j, u, lead);
+            if (4u * u < lead + span) v[k] = load_group<false>(in, j, rg.n);
+            if (k < PRE) {
+                early[k < PRE ? k : 0] = random_words(j, key, 0u);
+                asm volatile("" : "+v"(early[k < PRE ? k : 0].w[0]), "+v"(early[k < PRE ? k : 0].w[1]),
+                             "+v"(early[k < PRE ? k : 0].w[2]), "+v"(early[k < PRE ? k : 0].w[3]));
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        rows01[k] = rows23[k] = 0u;
+        if (t < nslots) {
+            uint64_t j;
+            uint32_t u, lead;
+            slot(t, j, u, lead);
+            const uint32_t bits[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+            uint32_t mag[4], row[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t at = u * 4u + (uint32_t)e;                  // offset from the start of the run's first group
+                const bool mine = at >= lead && at - lead < span;
+                const uint32_t off = mine ? at - lead : 0u;
+                const uint32_t r = inner == 1u ? off : __umulhi(off, rg.magic_inner);
+                row[e] = r < nrows ? r : nrows - 1u;
+                mag[e] = mine ? (bits[e] & 0x7fffffffu) : 0u;
+            }
+            rows01[k] = row[0] | (row[1] << 16);
+            rows23[k] = row[2] | (row[3] << 16);
+            uint32_t m = mag[0];
+#pragma unroll
+            for (int e = 1; e < 4; ++e) {
+                if (row[e] != row[e - 1]) {
+                    atomicMax(&rowmax[row[e - 1]], m);
+                    m = 0u;
+                }
+                m = m > mag[e] ? m : mag[e];
+            }
+            atomicMax(&rowmax[row[3]], m);
+        }
+    }
+    __syncthreads();
+    int all_finite = 1;
+    for (uint32_t t = threadIdx.x; t < nrows; t += kThreads)
+        if (!plan_is_finite<MODE>(block_plan(rowmax[t], wl, symmetric))) all_finite = 0;
+    const bool finite = __syncthreads_and(all_finite) != 0;      // as in block_ragged_kernel
+    if (finite) {
+        for (uint32_t t = threadIdx.x; t < nrows; t += kThreads) rowmax[t] = clamped_field23(rowmax[t]);
+        __syncthreads();
+    }
+    const FieldPlan fp = field_plan(wl, symmetric);
+#pragma unroll
+    for (int k = 0; k < GPT; ++k) {
+        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        if (t < nslots) {
+            uint64_t j;
+            uint32_t u, lead;
+            slot(t, j, u, lead);
+            const uint32_t at = u * 4u;
+            if (at < lead + span) {                                       // (a slot past the run's last group holds nothing)
+                Words4 r = {{0u, 0u, 0u, 0u}};
+                if (k < PRE) r = early[k < PRE ? k : 0];
+                else if (MODE == QSIM_STOCHASTIC) r = random_words(j, key, 0u);
+                const uint32_t bits[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
+                const uint32_t row[4] = {rows01[k] & 0xffffu, rows01[k] >> 16, rows23[k] & 0xffffu, rows23[k] >> 16};
+                uint32_t o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t entry = rowmax[row[e]];
+                    o[e] = finite ? quantize_finite_to_grid<MODE>(bits[e], plan_of_field(entry, fp), r.w[e])
+                                  : quantize_to_grid<MODE>(bits[e], block_plan(entry, wl, symmetric), r.w[e]);
+                }
+                if (at >= lead && at + 3u - lead < span) {
+                    store_group<false>(out, j, rg.n, make_uint4(o[0], o[1], o[2], o[3]));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (at + (uint32_t)e >= lead && at + (uint32_t)e - lead < span) out[j * 4 + (uint64_t)e] = o[e];
+                }
+            }
+        }
+    }
+}
+
 // One contiguous block of up to 16,384 elements per workgroup (outer == 1) when the arrays are not
 // aligned or the block length is not a multiple of four: dword accesses; the block is read twice by
 // the same workgroup, the second time out of cache.

@@ -462,6 +462,33 @@ def test_block_short_blocks_along_an_inner_dimension(shape, rounding):
     assert_bit_equal(host(d), want, f"{shape} in place")
 
 
+@pytest.mark.parametrize("rounding", [RN_EVEN, RN_ZERO, STOCHASTIC])
+@pytest.mark.parametrize("shape", [(2, 30000, 154), (2, 1000, 77), (16, 300, 49), (5, 700, 33), (3, 10, 682), (2, 4, 1001), (16, 2048, 49),
+                                   (4, 5, 50), (2, 3000, 64), (7, 1, 99), (2, 70000, 9), (12, 4097, 13), (3, 2, 683), (2, 1, 1023),
+                                   (16, 9, 127), (2, 100, 1024)])
+def test_block_short_blocks_of_odd_segments_along_an_inner_dimension(shape, rounding):
+    """Blocks of at most 2048 elements along an inner dimension whose segments are not whole groups,
+    or that lie in arrays that start at any element: several blocks per workgroup, each outer index
+    one contiguous run walked in the arrays' own groups; one pass.  Every alignment of the arrays;
+    neighbouring blocks differ in scale by up to 2^24 and every block's largest value sits at an edge
+    of one of its segments, next to a neighbour's elements."""
+    outer, nblocks, inner = shape
+    g = np.random.Generator(np.random.PCG64(sum(shape)))
+    scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
+    x = (g.standard_normal(shape, dtype=np.float32) * scale[None, :, None]).astype(np.float32)
+    x[g.integers(0, outer, size=nblocks), np.arange(nblocks), (g.integers(0, 2, size=nblocks) * (inner - 1))] *= np.float32(9.0)
+    want = R.block_quantize(x, outer, nblocks, inner, 8, rounding, 0, 6, 1).reshape(-1)
+    n = x.size
+    pad = dev(np.concatenate([np.zeros(3, np.float32), x.reshape(-1), np.full(5, 1e30, np.float32)]))
+    for off in (3, 2, 1, 0):
+        view = pad[off:off + n]
+        view.copy_(torch.from_numpy(x.reshape(-1)))
+        assert_bit_equal(host(Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 6, 1)), want, f"{shape} offset {off}")
+    Q.block_quantize(view, outer, nblocks, inner, 8, rounding, 0, 6, 1, out=view)
+    assert_bit_equal(host(view), want, f"{shape} in place")
+    assert np.all(host(pad[3 + n:]) == np.float32(1e30))             # nothing written behind the arrays
+
+
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
 @pytest.mark.parametrize("shape", [(4, 100003, 1), (46, 5743, 1), (71, 6029, 7), (22, 10601, 14), (631, 3035, 1), (9, 6, 20714),
                                    (5, 3, 4098), (77, 1, 43577), (3, 4, 279622), (40, 72, 1165), (300, 5000, 3),
@@ -699,6 +726,7 @@ BLOCK_FORMS = [
     (40, 64, 3025),           # per channel, odd segments
     (32, 128, 256),           # per channel, one large workgroup per block
     (2, 3000, 64),            # short blocks along an inner dimension, packed
+    (2, 3000, 154),           # the same with odd segments
     (3000, 24, 1),            # short rows: the flat form, one element per block and row
     (3000, 9, 4),             # the flat form, whole groups
     (700, 13, 3),             # the flat form, odd segments
