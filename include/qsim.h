@@ -154,7 +154,7 @@ int qsim_block_quantize_static(const float* in, float* out, uint64_t n, uint64_t
 /*
  * Tuning and test knob of qsim_block_quantize.  A block that is too long for one workgroup but
  * fits in the register files of the chip (a whole tensor of up to 16 Mi elements; in larger
- * tensors every block of up to 1 Mi contiguous or 4 Mi strided elements) is quantized in a single
+ * tensors every block of up to 8 Mi elements, contiguous or strided) is quantized in a single
  * pass by workgroups that hold its slices in registers and wait for each other once.  For a whole
  * tensor the grid is no larger than what the device holds at once; for many blocks the workgroups
  * are numbered block by block and the forms count on the device starting them in that order, so

@@ -89,13 +89,13 @@ static int launch_elementwise_rt(const float* in, float* out, uint64_t n, const 
 struct BlockSchedule {
     bool one_launch;       // contiguous blocks small enough for one team or workgroup each
     SliceGeom sg;          // otherwise: two launches over slices
-    bool cluster;          // many contiguous blocks of up to 64 register-resident slices each: single pass per block
+    bool cluster;          // many contiguous blocks of up to 512 register-resident slices each: single pass per block
     bool strided_packed;   // outer > 1, whole-group segments, blocks of at most 2048 elements: several per workgroup
     StridedPackedGeom spg;
     bool ragged_runs;      // the same for segments of any length and alignment (the arrays' own groups, shared edge groups)
     int ragged_runs_gpt;   // groups per thread: 8, or 16 when a block needs that many
     RaggedRunsGeom rrg;
-    bool strided_cluster;  // outer > 1, aligned segments of >= 64 elements, blocks of up to 256 slices: the same
+    bool strided_cluster;  // outer > 1, aligned segments of >= 64 elements, blocks of up to 512 slices: the same
     StridedClusterGeom scg;
     bool strided_ragged;   // outer > 1, segments of >= 64 elements of any length and alignment: the same
     RaggedClusterGeom rcg;
@@ -118,7 +118,7 @@ constexpr uint64_t kCachedMaxInner = 16384;      // 256 threads x 16 groups x 4 
 constexpr int kWideThreads = 1024;
 constexpr uint64_t kWideCachedMaxInner = 65536;  // 1024 threads x 16 groups x 4 elements
 constexpr uint64_t kClusterSliceLen = 4ull * kThreads * 16;     // 16 groups per thread
-constexpr uint64_t kClusterMaxSlices = 64;       // one lane of a wavefront watches each slot
+constexpr uint64_t kClusterMaxSlices = 512;      // half of the workgroups the chip holds at once
 constexpr uint64_t kClusterMaxWgs = 1ull << 22;
 constexpr uint32_t kMaxSlices = 1024;
 constexpr uint64_t kMinSliceLen = 16384;
@@ -298,7 +298,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
             s.rrg.magic_inner = inner > 1 ? (uint32_t)((1ull << 32) / inner) + 1u : 0u;
         }
     }
-    if (outer > 1 && inner % 4 == 0 && inner >= 64 && inner <= (1ull << 22) && n < (1ull << 34) &&
+    if (outer > 1 && inner % 4 == 0 && inner >= 64 && inner <= (1ull << 23) && n < (1ull << 34) &&
         s.sg.block_len <= (uint64_t)kStridedMaxSlices * kStridedSliceLen) {
         const uint64_t slices_each = (s.sg.block_len + kStridedSliceLen - 1) / kStridedSliceLen;
         if (nblocks * slices_each <= kClusterMaxWgs) {
@@ -315,7 +315,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
             meeting(s.scg.slices);
         }
     }
-    if (inner >= 64 && inner <= (1ull << 22) && n < (1ull << 32)) {          // (contiguous blocks too: one segment each)
+    if (inner >= 64 && inner <= (1ull << 23) && n < (1ull << 32)) {          // (contiguous blocks too: one segment each)
         const uint64_t seg_groups = (inner + 2) / 4 + 1;
         const unsigned __int128 block_groups = (unsigned __int128)outer * seg_groups;
         // (a block has workgroups of its own, four of which fit a CU: with fewer than eight loads per
@@ -596,7 +596,7 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         hipLaunchKernelGGL((block_slice_apply_kernel<MODE>), dim3(s.sg.slices, by), dim3(kThreads), 0, stream, pin, pout,
                            partial, s.sg.slices, s.sg, wl, symmetric, key);
     } else if (g.outer == 1 && s.strided_ragged && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
-        // contiguous blocks of up to 4 Mi elements whose length is not a multiple of four, or in
+        // contiguous blocks of up to 8 Mi elements whose length is not a multiple of four, or in
         // arrays that are only dword aligned: single pass, block by block, over the array's own groups
         launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, scratch, s.sync_counters, kept, stream);
     } else if (vec && s.strided_packed) {
@@ -635,10 +635,14 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
     } else if (s.strided_ragged && !short_segments && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // the same for segments of any length and alignment
         launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, scratch, s.sync_counters, kept, stream);
-    } else if (s.flat && !(vec && g.inner > 128) && (!s.column || g.nblocks < 64 || s.fg.row < 2048)) {
+    } else if (s.flat && !(vec && g.inner > 128) &&
+               (!s.column || g.nblocks < 64 || s.fg.row < 2048 || g.nblocks * 8192 <= g.n)) {
         // short rows, unless long aligned segments stream well through the slice kernels: always when
         // the column form cannot run; otherwise where that form is weak (few blocks make its fold
-        // serial, short rows give it few threads per row)
+        // serial, short rows give it few threads per row), and wherever the per-workgroup tables of
+        // block maxima (1024 x nblocks words, written and read once) are small next to the tensor
+        // ([11910, 145, 19] 93 us -> 67 us, [8192, 1024, 4] 79 us -> 67 us; [4096, 4096, 1], whose
+        // tables are a quarter of the tensor, stays with the column form: 38 us against 49 us)
         const FlatGeom& fg = s.fg;
         uint32_t* blockmax = partial + (size_t)kFlatWorkgroups * fg.nblocks;
         hipLaunchKernelGGL(block_flat_max_kernel, dim3(fg.wgs), dim3(kThreads), 0, stream, pin, partial, blockmax, fg);

@@ -349,10 +349,11 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
 // aligned segments of at least 64 elements (inner % 4 == 0): per-channel blocks of an
 // [N, C, H, W] tensor.  Slice s of block b is elements [s * 16384, ...) of the block's own
 // numbering t = o * inner + i; a group's place in the array follows from one division by `inner`
-// (multiply-high with a reciprocal rounded up, corrected by at most one).  Up to 256 slices per
-// block, which meet as above (counters, flags and epochs packed, one word after the other).
+// (multiply-high with a reciprocal rounded up, corrected by at most one) for a thread's first
+// group, additions from there.  Up to 512 slices per block (half of the workgroups the chip holds at
+// once), which meet as above (counters, flags and epochs packed, one word after the other).
 constexpr uint32_t kStridedSliceLen = 4u * kThreads * 16u;
-constexpr uint32_t kStridedMaxSlices = 256;
+constexpr uint32_t kStridedMaxSlices = 512;
 
 struct StridedClusterGeom {
     uint64_t nblocks;

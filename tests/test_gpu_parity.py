@@ -492,12 +492,12 @@ def test_block_short_blocks_of_odd_segments_along_an_inner_dimension(shape, roun
 @pytest.mark.parametrize("rounding", [RN_EVEN, STOCHASTIC])
 @pytest.mark.parametrize("shape", [(4, 100003, 1), (46, 5743, 1), (71, 6029, 7), (22, 10601, 14), (631, 3035, 1), (9, 6, 20714),
                                    (5, 3, 4098), (77, 1, 43577), (3, 4, 279622), (40, 72, 1165), (300, 5000, 3),
-                                   (2, 3, (1 << 21) + 1), (2, 2, (1 << 21) + 4)])
+                                   (2, 3, (1 << 21) + 1), (2, 2, (1 << 21) + 4), (2, 2, (1 << 22) + 1), (3, 2, 2796204)])
 def test_block_rows_that_are_not_whole_groups_along_an_inner_dimension(shape, rounding):
     """Blocks along an inner dimension when a row is not a multiple of four elements, or the blocks
-    are long and odd: the one-column-per-thread form, the single pass over odd segments and, for
-    blocks of more than four million elements, the general two-pass form; one block in several
-    outer pieces is the whole tensor."""
+    are long and odd: the one-column-per-thread form, the single pass over odd segments (blocks of
+    up to 512 workgroups, aligned or not) and, for blocks of more than eight million elements, the
+    general two-pass form; one block in several outer pieces is the whole tensor."""
     outer, nblocks, inner = shape
     g = np.random.Generator(np.random.PCG64(sum(shape)))
     scale = np.exp2(g.integers(-12, 12, size=nblocks)).astype(np.float32)
