@@ -61,6 +61,8 @@ def _time_launches(fn, steps, warmup, torch):
     for k in range(steps):
         fn(k)
     stop.record()
+    while not stop.query():         # (polled, so that the host clock stops within microseconds of the last launch's
+        pass                        # end; the synchronize below then finds the device idle)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     return wall, start.elapsed_time(stop) * 1e-3
