@@ -715,24 +715,27 @@ def test_block_with_nonfinite_elements():
     _block_case(x, 1, 1, 4 * 2048, 8, STOCHASTIC)
 
 
-# One view per kernel form of the block quantizer (named by what the form is chosen for).
+# One view per kernel form of the block quantizer, named by the kernel it is served by (checked with a
+# kernel trace of this test).
 BLOCK_FORMS = [
-    (1, 96, 1280),            # contiguous rows, several per workgroup, in registers
-    (1, 600, 7),              # contiguous rows of odd length
-    (1, 3, 70001),            # long odd rows: single pass block by block over odd segments
-    (1, 1, 3000000),          # whole tensor: single pass over resident workgroups
-    (1, 40, 262144),          # long aligned rows: single pass block by block
-    (64, 96, 3136),           # per channel, aligned segments: single pass block by block
-    (40, 64, 3025),           # per channel, odd segments
-    (32, 128, 256),           # per channel, one large workgroup per block
-    (2, 3000, 64),            # short blocks along an inner dimension, packed
-    (2, 3000, 154),           # the same with odd segments
-    (3000, 24, 1),            # short rows: the flat form, one element per block and row
-    (3000, 9, 4),             # the flat form, whole groups
-    (700, 13, 3),             # the flat form, odd segments
-    (129, 5000, 1),           # columns
-    (50, 700, 19),            # columns, odd segments
-    (27, 6, 20711),           # the general two passes
+    (1, 96, 1280),            # block_cached_kernel: contiguous rows, several per workgroup, in registers
+    (1, 600, 7),              # block_ragged_kernel: contiguous rows of odd length
+    (1, 40, 16381),           # block_rows_kernel: odd rows just under 16 Ki elements
+    (1, 3, 70001),            # block_cluster_ragged_kernel: long odd rows, single pass block by block
+    (1, 1, 3000000),          # block_resident_kernel: whole tensor, single pass over resident workgroups
+    (1, 80, 262144),          # block_resident_kernel block by block: more aligned rows than the chip holds
+    (64, 96, 3136),           # block_cluster_strided_kernel: per channel, aligned segments
+    (40, 64, 3025),           # block_cluster_ragged_kernel: per channel, odd segments
+    (32, 128, 1024),          # block_strided_wide_kernel: per channel, one large workgroup per block
+    (2, 3000, 64),            # block_strided_packed_kernel: short blocks along an inner dimension
+    (2, 3000, 154),           # block_ragged_runs_kernel: the same with odd segments
+    (129, 5000, 1),           # block_ragged_runs_kernel with 16 groups per thread
+    (300000, 24, 1),          # block_flat_*: short rows, one element per block and row
+    (300000, 9, 4),           # block_flat_*: whole groups
+    (70000, 13, 11),          # block_flat_*: odd segments
+    (129, 70000, 1),          # block_column_*: one column per block
+    (600, 9000, 3),           # block_column_*: odd segments, rows of 27,000
+    (2, 2, 4194305),          # block_partial_max_kernel + block_apply_kernel: blocks beyond eight million elements
 ]
 
 
