@@ -616,14 +616,18 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
                resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // single pass, block by block (see the kernel): the workgroups of a block must fit together
         StridedClusterGeom cg = s.scg;
-        if (cg.slices > 1u && cg.block_len <= 4u * 1024u * 16u) {
-            // two to four workgroups per block: one large workgroup holds it alone, with nobody to meet
+        // two to four workgroups per block: one large workgroup holds it alone, with nobody to meet
+        // (not with stochastic rounding when blocks of more than 32 Ki elements are fewer than the
+        // CUs: sixteen Philox blocks per thread on a quarter of the chip then take longer than a
+        // meeting does; 64 blocks of 64 Ki elements 17.2 us against 11.9 us)
+        const bool few_large = MODE == QSIM_STOCHASTIC && cg.block_len > 4u * 512u * 16u && cg.nblocks < 256;
+        if (cg.slices > 1u && cg.block_len <= 4u * 1024u * 16u && !few_large) {
             strided_steps(cg, cg.block_len <= 4u * 512u * 16u ? 512u : 1024u);
             if (cg.block_len <= 4u * 512u * 16u)
-                hipLaunchKernelGGL((block_strided_wide_kernel<MODE, 512>), folded(cg.nblocks), dim3(512), 0, stream, pin, pout, cg, wl,
+                hipLaunchKernelGGL((block_strided_wide_kernel<MODE, 512, 16>), folded(cg.nblocks), dim3(512), 0, stream, pin, pout, cg, wl,
                                    symmetric, key);
             else
-                hipLaunchKernelGGL((block_strided_wide_kernel<MODE, 1024>), folded(cg.nblocks), dim3(1024), 0, stream, pin, pout, cg,
+                hipLaunchKernelGGL((block_strided_wide_kernel<MODE, 1024, 16>), folded(cg.nblocks), dim3(1024), 0, stream, pin, pout, cg,
                                    wl, symmetric, key);
             return launch_status();
         }

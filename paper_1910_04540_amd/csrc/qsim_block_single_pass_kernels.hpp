@@ -501,12 +501,11 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
 // reduction through LDS.  For the small activation tensors of a network on small images
 // ([128, 128, 16, 16] per channel: blocks of 32 Ki elements), where two workgroups of 256 threads
 // per block would spend more time finding each other than moving the data.
-template <int MODE, int THREADS>
+template <int MODE, int THREADS, int GPT>
 __global__ __launch_bounds__(THREADS) void block_strided_wide_kernel(const uint32_t* in, uint32_t* out, StridedClusterGeom cg, int wl,
                                                                      int symmetric, RngKey key)
 {
-    constexpr int GPT = 16;
-    constexpr int PRE = MODE == QSIM_STOCHASTIC ? 9 : 0;          // random words parked in LDS while the loads are in flight
+    constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 9 ? GPT : 9) : 0;   // random words parked in LDS while the loads are in flight
     __shared__ uint4 parked[PRE > 0 ? PRE * THREADS : 1];
     __shared__ uint32_t lds[THREADS / 64];
     const uint32_t b = (uint32_t)linear_block();
