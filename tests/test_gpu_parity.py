@@ -763,11 +763,12 @@ def test_block_forms_with_finite_and_with_other_blocks(shape, rounding):
             _block_case(x, outer, nblocks, inner, 8, rounding, flags=flags, seed=77 + case, stream_id=5)
 
 
-@pytest.mark.parametrize("wl,rounding,flags", [(8, RN_EVEN, 0), (24, RN_EVEN, SYMMETRIC)])
+@pytest.mark.parametrize("wl,rounding,flags", [(8, RN_EVEN, 0), (24, RN_EVEN, SYMMETRIC), (24, RN_EVEN, 0)])
 def test_block_every_encoding_below_the_shared_exponent(wl, rounding, flags):
     """Blocks whose shared exponent is 0 (each row ends in +-1.5 and two more values of that binade)
     over every non-negative fp32 encoding below 2.0, and a sample of the negative ones: the
-    nearest-even form that rounds by adding and subtracting 2^(q+23), against the oracle."""
+    nearest-even form that rounds by adding and subtracting 2^(q+23), against the oracle.  With 24
+    bits and the most negative code allowed, the tail's -1.9999999 ties up to -2.0 = -2^(q+23) itself."""
     rows, cols = 64, 1 << 20
     tail = np.array([1.5, -1.5, 1.0, -1.9999999], dtype=np.float32)
     starts = list(range(0, 0x40000000, rows * cols)) + [0x80000000, 0xB0000000, 0xBC000000]
