@@ -210,6 +210,18 @@ static void clear_scratch(uint64_t* scratch, const MeetLayout& l, hipStream_t st
     hipLaunchKernelGGL(block_sync_clear_kernel, folded((words + kThreads - 1) / kThreads), dim3(kThreads), 0, stream, scratch, words);
 }
 
+// How a block's slots are dealt out to workgroups of `threads` threads, 16 slots per thread (see RaggedClusterGeom).
+static void ragged_workgroups(RaggedClusterGeom& cg, uint32_t threads)
+{
+    const uint32_t per_wg = threads * 16u;
+    cg.threads = threads;
+    cg.slices = (cg.block_groups + per_wg - 1u) / per_wg;
+    cg.slice_groups = (cg.block_groups + cg.slices - 1u) / cg.slices;
+    cg.total_wgs = (uint32_t)(cg.nblocks * cg.slices);
+    cg.step_rest = threads % cg.seg_groups;
+    cg.step_elems = (threads / cg.seg_groups) * cg.row_elems;
+}
+
 // The walk of a thread over its groups when the workgroup has `threads` threads (see StridedClusterGeom).
 static void strided_steps(StridedClusterGeom& cg, uint32_t threads)
 {
@@ -251,7 +263,8 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
     partial_needs((size_t)(nblocks * slices * sizeof(uint32_t)));
     // the single-pass form over resident workgroups
     if (outer == 1) sync_needs(kResidentCounterWords, kResidentTaggedWords);
-    // the same kernel meeting block by block: workgroups of 16,384 elements
+    // the same kernel meeting block by block (the scratch is sized for workgroups of 16,384 elements;
+    // the launch uses half as many of 32,768)
     const uint64_t cluster_slices = (inner + kClusterSliceLen - 1) / kClusterSliceLen;
     if (outer == 1 && inner > kWideCachedMaxInner && cluster_slices <= kClusterMaxSlices &&
         nblocks * cluster_slices <= kClusterMaxWgs) {
@@ -300,18 +313,22 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
     }
     if (outer > 1 && inner % 4 == 0 && inner >= 64 && inner <= (1ull << 23) && n < (1ull << 34) &&
         s.sg.block_len <= (uint64_t)kStridedMaxSlices * kStridedSliceLen) {
-        const uint64_t slices_each = (s.sg.block_len + kStridedSliceLen - 1) / kStridedSliceLen;
+        // a block that one workgroup of 256 threads holds keeps that workgroup; larger blocks are shared
+        // by workgroups of 512 threads, 32 Ki elements each
+        const uint64_t slice_len = s.sg.block_len <= kStridedSliceLen ? kStridedSliceLen : 2 * kStridedSliceLen;
+        const uint64_t slices_each = (s.sg.block_len + slice_len - 1) / slice_len;
         if (nblocks * slices_each <= kClusterMaxWgs) {
             s.strided_cluster = true;
             s.scg.nblocks = nblocks;
             s.scg.block_len = (uint32_t)s.sg.block_len;
+            s.scg.slice_len = (uint32_t)slice_len;
             s.scg.slices = (uint32_t)slices_each;
             s.scg.inner = (uint32_t)inner;
             s.scg.magic_inner = (uint32_t)((1ull << 32) / inner) + 1u;
             s.scg.total_wgs = (uint32_t)(nblocks * slices_each);
             s.scg.row_groups = (uint32_t)(nblocks * inner / 4);
             s.scg.wrap_groups = s.scg.row_groups - (uint32_t)(inner / 4);
-            strided_steps(s.scg, kThreads);
+            strided_steps(s.scg, (uint32_t)(slice_len / 64));
             meeting(s.scg.slices);
         }
     }
@@ -321,6 +338,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
         // (a block has workgroups of its own, four of which fit a CU: with fewer than eight loads per
         // thread in flight they do not keep the memory busy, and the column form measured faster)
         if (block_groups >= kRaggedMinGroups && block_groups <= (uint64_t)kStridedMaxSlices * kRaggedSliceGroups) {
+            // (sized for workgroups of 256 threads; the launch may share a block among half as many of 512)
             const uint64_t slices_each = ((uint64_t)block_groups + kRaggedSliceGroups - 1) / kRaggedSliceGroups;
             if (nblocks * slices_each <= kClusterMaxWgs) {
                 s.strided_ragged = true;
@@ -330,12 +348,8 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
                 s.rcg.seg_groups = (uint32_t)seg_groups;
                 s.rcg.magic_groups = (uint32_t)((1ull << 32) / seg_groups) + 1u;
                 s.rcg.block_groups = (uint32_t)block_groups;
-                s.rcg.slices = (uint32_t)slices_each;
-                s.rcg.slice_groups = (uint32_t)(((uint64_t)block_groups + slices_each - 1) / slices_each);
-                s.rcg.total_wgs = (uint32_t)(nblocks * slices_each);
                 s.rcg.row_elems = outer > 1 ? (uint32_t)(nblocks * inner) : 0u;
-                s.rcg.step_rest = (uint32_t)(kThreads % seg_groups);
-                s.rcg.step_elems = (uint32_t)((kThreads / seg_groups) * s.rcg.row_elems);
+                ragged_workgroups(s.rcg, kThreads);
                 meeting(s.rcg.slices);
             }
         }
@@ -390,7 +404,7 @@ static BlockSchedule block_schedule(uint64_t n, uint64_t outer, uint64_t nblocks
 // scalar register file.
 constexpr int kResidentPerCu = 4;
 
-template <int MODE, int GPT>
+template <int MODE, int GPT, int THREADS = kThreads>
 static uint32_t resident_capacity()
 {
     static std::atomic<int> cache[64];          // per device; 0 = not known yet
@@ -400,8 +414,8 @@ static uint32_t resident_capacity()
     if (c == 0) {
         int per_cu = 0, cus = 0;
         const bool ok =
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)block_resident_kernel<MODE, GPT>, kThreads,
-                                                         0) == hipSuccess &&
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void*)block_resident_kernel<MODE, GPT, false, THREADS>,
+                                                         THREADS, 0) == hipSuccess &&
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess;
         // (a query that fails, say in a state of the runtime that does not allow it, is asked again by the
         // next call: this one takes the two-pass form)
@@ -409,7 +423,7 @@ static uint32_t resident_capacity()
             (void)hipGetLastError();
             return 0u;
         }
-        if (per_cu > kResidentPerCu) per_cu = kResidentPerCu;
+        if (per_cu > kResidentPerCu * kThreads / THREADS) per_cu = kResidentPerCu * kThreads / THREADS;
         c = per_cu * cus;
         cache[dev].store(c, std::memory_order_relaxed);
     }
@@ -420,14 +434,14 @@ static uint32_t resident_capacity()
 // The launch is an ordinary one: the grid is no larger than what the device holds at once, and a
 // workgroup that waits in vain (the device is shared with other work) falls back to an exact slow
 // path, so residency is a matter of speed, not of correctness or termination.
-template <int MODE, int GPT>
+template <int MODE, int GPT, int THREADS = kThreads>
 static bool try_resident(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
                          uint64_t* scratch, uint64_t tagged, bool kept, hipStream_t stream)
 {
-    const uint64_t slice_len = 4ull * kThreads * GPT;
+    const uint64_t slice_len = 4ull * THREADS * GPT;
     const uint64_t slices = (g.inner + slice_len - 1) / slice_len;
     const uint64_t total = slices * g.nblocks;
-    if (total > kMaxResidentWgs || total > resident_capacity<MODE, GPT>()) return false;
+    if (total > kMaxResidentWgs || total > resident_capacity<MODE, GPT, THREADS>()) return false;
     // a line for every counter, flag and epoch while they are few; packed otherwise (many small blocks)
     const uint64_t groups = g.nblocks * ((slices + kMeetGroup - 1) / kMeetGroup);
     const MeetLayout meet = meet_layout(g.nblocks, (uint32_t)slices, groups <= kMaxResidentGroups ? kMeetLine : 1u, false, tagged);
@@ -440,8 +454,8 @@ static bool try_resident(const uint32_t* in, uint32_t* out, const BlockGeom& g, 
     rg.total_wgs = (uint32_t)total;
     rg.meet = meet.geom;
     if (!kept) clear_scratch(scratch, meet, stream);
-    hipLaunchKernelGGL((block_resident_kernel<MODE, GPT>), dim3((unsigned)total), dim3(kThreads), 0, stream, in, out, scratch, rg,
-                       wl, symmetric, key);
+    hipLaunchKernelGGL((block_resident_kernel<MODE, GPT, false, THREADS>), dim3((unsigned)total), dim3(THREADS), 0, stream, in, out,
+                       scratch, rg, wl, symmetric, key);
     return true;
 }
 
@@ -450,19 +464,22 @@ template <int MODE>
 static bool try_cluster(const uint32_t* in, uint32_t* out, const BlockGeom& g, int wl, int symmetric, const RngKey& key,
                         uint64_t* scratch, uint64_t tagged, bool kept, hipStream_t stream)
 {
-    const uint64_t slices = (g.inner + kClusterSliceLen - 1) / kClusterSliceLen;
+    // workgroups of 512 threads, 32 Ki elements each: half as many to meet as with 256 threads
+    // (64 rows of 1 Mi elements 107 us -> 97 us)
+    const uint64_t slice_len = 2 * kClusterSliceLen;
+    const uint64_t slices = (g.inner + slice_len - 1) / slice_len;
     if (resident_capacity<MODE, 16>() < kClusterMaxSlices) return false;     // a block's workgroups must fit together
     const MeetLayout meet = meet_layout(g.nblocks, (uint32_t)slices, 1u, true, tagged);
     ResidentGeom rg;
     rg.sg.g = g;
     rg.sg.block_len = g.inner;
-    rg.sg.slice_len = kClusterSliceLen;
+    rg.sg.slice_len = slice_len;
     rg.sg.slices = (uint32_t)slices;
     rg.total_wgs = (uint32_t)(slices * g.nblocks);
     rg.meet = meet.geom;
     if (!kept) clear_scratch(scratch, meet, stream);
-    hipLaunchKernelGGL((block_resident_kernel<MODE, 16, true>), folded(rg.total_wgs), dim3(kThreads), 0, stream, in, out, scratch,
-                       rg, wl, symmetric, key);
+    hipLaunchKernelGGL((block_resident_kernel<MODE, 16, true, 2 * kThreads>), folded(rg.total_wgs), dim3(2 * kThreads), 0, stream, in,
+                       out, scratch, rg, wl, symmetric, key);
     return true;
 }
 
@@ -522,11 +539,19 @@ static void launch_block_cluster_ragged(const uint32_t* in, uint32_t* out, const
                                         const RngKey& key, uint64_t* scratch, uint64_t tagged, bool kept, hipStream_t stream)
 {
     RaggedClusterGeom cg = geom;
+    // A block of more slots than 256 threads hold is shared by workgroups of 512 threads, half as many
+    // to meet ([128, 64, 55 x 55] nearest 45.3 us -> 43.6 us); not with stochastic rounding, whose
+    // arithmetic wants four independent workgroups per CU (47.9 us -> 50.2 us with two).
+    if (MODE != QSIM_STOCHASTIC && cg.block_groups > kRaggedSliceGroups) ragged_workgroups(cg, 2 * kThreads);
     const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, true, tagged);
     cg.meet = meet.geom;
     if (!kept && cg.slices > 1u) clear_scratch(scratch, meet, stream);       // (one workgroup per block: nothing meets)
-    hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, in, out, scratch, cg,
-                       wl, symmetric, key);
+    if (cg.threads == (uint32_t)kThreads)
+        hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE, kThreads>), folded(cg.total_wgs), dim3(kThreads), 0, stream, in, out,
+                           scratch, cg, wl, symmetric, key);
+    else
+        hipLaunchKernelGGL((block_cluster_ragged_kernel<MODE, 2 * kThreads>), folded(cg.total_wgs), dim3(2 * kThreads), 0, stream, in,
+                           out, scratch, cg, wl, symmetric, key);
 }
 
 template <int MODE>
@@ -634,8 +659,14 @@ static int launch_block_mode(const float* in, float* out, const BlockSchedule& s
         const MeetLayout meet = meet_layout(cg.nblocks, cg.slices, 1u, true, s.sync_counters);
         cg.meet = meet.geom;
         if (!kept && cg.slices > 1u) clear_scratch(scratch, meet, stream);   // (one workgroup per block: nothing meets)
-        hipLaunchKernelGGL((block_cluster_strided_kernel<MODE>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin, pout,
-                           scratch, cg, wl, symmetric, key);
+        if (cg.slice_len == kStridedSliceLen) {
+            hipLaunchKernelGGL((block_cluster_strided_kernel<MODE, kThreads>), folded(cg.total_wgs), dim3(kThreads), 0, stream, pin,
+                               pout, scratch, cg, wl, symmetric, key);
+        } else {
+            strided_steps(cg, 2 * kThreads);
+            hipLaunchKernelGGL((block_cluster_strided_kernel<MODE, 2 * kThreads>), folded(cg.total_wgs), dim3(2 * kThreads), 0, stream,
+                               pin, pout, scratch, cg, wl, symmetric, key);
+        }
     } else if (s.strided_ragged && !short_segments && resident_capacity<MODE, 16>() >= kStridedMaxSlices) {
         // the same for segments of any length and alignment
         launch_block_cluster_ragged<MODE>(pin, pout, s.rcg, wl, symmetric, key, scratch, s.sync_counters, kept, stream);

@@ -95,7 +95,7 @@ __device__ __forceinline__ uint32_t meet_tag(const uint64_t* scratch)
 // a few hundred workgroups per block: a workgroup publishes its slot and the first wavefront polls the
 // block's slots until all carry the tag; nothing is waited for but the slots themselves.  The
 // block's counter then only counts, after the meeting, who has been there.
-template <bool POLL_SLOTS, class SliceMax>
+template <bool POLL_SLOTS, int THREADS = kThreads, class SliceMax>
 __device__ __forceinline__ uint32_t meet_in_block(uint64_t* scratch, const MeetGeom& mg, uint64_t b, uint32_t s, uint32_t tag,
                                                   uint32_t m, uint32_t* lds, uint32_t& shared_word, uint32_t& ticket,
                                                   SliceMax slice_max)
@@ -188,7 +188,7 @@ __device__ __forceinline__ uint32_t meet_in_block(uint64_t* scratch, const MeetG
         if (!(a & kPublished)) {
             // the owner of slice i has not published, so it has not written any output yet:
             // read its input; if the slot is still unpublished afterwards, the read was clean
-            const uint32_t own = workgroup_max(slice_max(i), lds);
+            const uint32_t own = workgroup_max<THREADS>(slice_max(i), lds);
             __syncthreads();
             if (threadIdx.x == 0) {
                 const uint64_t again = __hip_atomic_load(&slots[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -251,13 +251,13 @@ __device__ __forceinline__ void meet_leave(uint64_t* scratch, const MeetGeom& mg
 // block after block; should the dispatcher ever do otherwise, the bounded wait and the exact
 // fallback still end every workgroup with the right result.
 struct ResidentGeom {
-    SliceGeom sg;            // slice_len = 1024 * GPT elements; slices = workgroups per block
+    SliceGeom sg;            // slice_len = 4 * THREADS * GPT elements; slices = workgroups per block
     uint32_t total_wgs;      // nblocks * slices
     MeetGeom meet;
 };
 
-template <int MODE, int GPT, bool CLUSTER = false>
-__global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
+template <int MODE, int GPT, bool CLUSTER = false, int THREADS = kThreads>
+__global__ __launch_bounds__(THREADS, (GPT >= 16 ? 1024 / THREADS : 1)) void block_resident_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
                                                                   ResidentGeom rg, int wl, int symmetric, RngKey key)
 {
     // Stochastic rounding: the random words of the first PRE groups are drawn while the loads are
@@ -265,9 +265,9 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
     // HELD more groups stay in registers; after the wait only the remaining groups pay for Philox,
     // and the arithmetic hides behind the stores.
     constexpr int PRE = MODE == QSIM_STOCHASTIC ? (GPT < 9 ? GPT : 9) : 0;
-    constexpr int HELD = MODE == QSIM_STOCHASTIC && GPT >= 16 && !CLUSTER ? 1 : 0;
-    __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
-    __shared__ uint32_t lds[kThreads / 64];
+    constexpr int HELD = MODE == QSIM_STOCHASTIC && GPT >= 16 && !CLUSTER && THREADS == kThreads ? 1 : 0;
+    __shared__ uint4 parked[PRE > 0 ? PRE * THREADS : 1];
+    __shared__ uint32_t lds[THREADS / 64];
     __shared__ uint32_t shared_word;
     const uint32_t wg = CLUSTER ? (uint32_t)linear_block() : blockIdx.x;
     if (CLUSTER && wg >= rg.total_wgs) return;                   // the whole workgroup leaves together
@@ -281,33 +281,33 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
     uint32_t* sout = out + sv.j0 * 4;
     const uint64_t slice_end = sv.end - sv.j0 * 4;               // elements reachable from the base
     const int ngroups = (int)sv.groups;
-    const bool full = ngroups == kThreads * GPT && slice_end >= 4ull * kThreads * GPT;
+    const bool full = ngroups == THREADS * GPT && slice_end >= 4ull * THREADS * GPT;
 
     uint4 v[GPT];
     uint32_t m = 0;
     if (full) {
 #pragma unroll
         for (int k = 0; k < GPT; ++k) {
-            const int t = (int)threadIdx.x + k * kThreads;
+            const int t = (int)threadIdx.x + k * THREADS;
             v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(sin) + t));
         }
     } else {
 #pragma unroll
         for (int k = 0; k < GPT; ++k) {
-            const int t = (int)threadIdx.x + k * kThreads;
+            const int t = (int)threadIdx.x + k * THREADS;
             v[k] = make_uint4(0u, 0u, 0u, 0u);
             if (t < ngroups) v[k] = load_group<true>(sin, (uint64_t)t, slice_end);
         }
     }
 #pragma unroll
     for (int k = 0; k < PRE; ++k) {
-        const Words4 r = random_words(sv.j0 + (uint64_t)((int)threadIdx.x + k * kThreads), key, 0u);
-        parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+        const Words4 r = random_words(sv.j0 + (uint64_t)((int)threadIdx.x + k * THREADS), key, 0u);
+        parked[k * THREADS + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
     }
     Words4 held[HELD > 0 ? HELD : 1];
 #pragma unroll
     for (int k = 0; k < HELD; ++k) {
-        held[k] = random_words(sv.j0 + (uint64_t)((int)threadIdx.x + (PRE + k) * kThreads), key, 0u);
+        held[k] = random_words(sv.j0 + (uint64_t)((int)threadIdx.x + (PRE + k) * THREADS), key, 0u);
         // (pinned here: left alone, the compiler sinks the computation below the wait to save registers)
         asm volatile("" : "+v"(held[k].w[0]), "+v"(held[k].w[1]), "+v"(held[k].w[2]), "+v"(held[k].w[3]));
     }
@@ -316,21 +316,21 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
         const uint32_t gm = max4_mag(v[k]);
         m = m > gm ? m : gm;
     }
-    m = workgroup_max(m, lds);
+    m = workgroup_max<THREADS>(m, lds);
 
     uint32_t ticket;
-    const uint32_t bm = meet_in_block<CLUSTER>(scratch, rg.meet, b, s, tag, m, lds, shared_word, ticket,
+    const uint32_t bm = meet_in_block<CLUSTER, THREADS>(scratch, rg.meet, b, s, tag, m, lds, shared_word, ticket,
                                                [&](uint32_t i) { return slice_max_frugal(in, slice_view(rg.sg, b, i)); });
 
     const GridPlan p = block_plan(bm, wl, symmetric);
     const bool finite = wave_plans_are_finite<MODE>(p);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        const int t = (int)threadIdx.x + k * kThreads;
+        const int t = (int)threadIdx.x + k * THREADS;
         if (full || t < ngroups) {
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) {
-                const uint4 w = parked[k * kThreads + threadIdx.x];
+                const uint4 w = parked[k * THREADS + threadIdx.x];
                 r = Words4{{w.x, w.y, w.z, w.w}};
             } else if (k < PRE + HELD) {
                 r = held[k - PRE < 0 ? 0 : k - PRE];
@@ -347,8 +347,10 @@ __global__ __launch_bounds__(kThreads, (GPT >= 16 ? 4 : 1)) void block_resident_
 
 // The same block-by-block single pass for blocks along an inner dimension (outer > 1) made of
 // aligned segments of at least 64 elements (inner % 4 == 0): per-channel blocks of an
-// [N, C, H, W] tensor.  Slice s of block b is elements [s * 16384, ...) of the block's own
-// numbering t = o * inner + i; a group's place in the array follows from one division by `inner`
+// [N, C, H, W] tensor.  Slice s of block b is elements [s * slice_len, ...) of the block's own
+// numbering t = o * inner + i (slice_len = 64 elements per thread: a block of up to 16 Ki elements is
+// one workgroup of 256 threads, larger ones are shared by workgroups of 512, two of which fit a CU:
+// half as many to meet, [128, 64, 112 x 112] 174.5 us -> 160.1 us); a group's place in the array follows from one division by `inner`
 // (multiply-high with a reciprocal rounded up, corrected by at most one) for a thread's first
 // group, additions from there.  Up to 512 slices per block (half of the workgroups the chip holds at
 // once), which meet as above (counters, flags and epochs packed, one word after the other).
@@ -357,8 +359,9 @@ constexpr uint32_t kStridedMaxSlices = 512;
 
 struct StridedClusterGeom {
     uint64_t nblocks;
-    uint32_t block_len;      // outer * inner, at most kStridedMaxSlices * kStridedSliceLen
-    uint32_t slices;
+    uint32_t block_len;      // outer * inner
+    uint32_t slice_len;      // 64 elements per thread of the workgroups that share a block: 16 Ki or 32 Ki
+    uint32_t slices;         // at most kStridedMaxSlices
     uint32_t inner;          // a multiple of 4, at least 64
     uint32_t magic_inner;    // floor(2^32 / inner) + 1
     uint32_t total_wgs;
@@ -414,26 +417,26 @@ __device__ __forceinline__ uint64_t strided_group(const StridedClusterGeom& cg, 
 
 __device__ __forceinline__ uint32_t strided_slice_groups(const StridedClusterGeom& cg, uint32_t s)
 {
-    const uint32_t t0 = s * kStridedSliceLen;
-    const uint32_t t1 = (cg.block_len - t0 < kStridedSliceLen) ? cg.block_len : t0 + kStridedSliceLen;
+    const uint32_t t0 = s * cg.slice_len;
+    const uint32_t t1 = (cg.block_len - t0 < cg.slice_len) ? cg.block_len : t0 + cg.slice_len;
     return (t1 - t0) / 4u;
 }
 
-template <int MODE>
-__global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
+template <int MODE, int THREADS>
+__global__ __launch_bounds__(THREADS, 1024 / THREADS) void block_cluster_strided_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
                                                                             StridedClusterGeom cg, int wl, int symmetric,
                                                                             RngKey key)
 {
     constexpr int GPT = 16;
     constexpr int PRE = MODE == QSIM_STOCHASTIC ? 9 : 0;          // random words parked in LDS, as in the kernel above
-    __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
-    __shared__ uint32_t lds[kThreads / 64];
+    __shared__ uint4 parked[PRE > 0 ? PRE * THREADS : 1];
+    __shared__ uint32_t lds[THREADS / 64];
     __shared__ uint32_t shared_word;
     const uint32_t wg = (uint32_t)linear_block();
     if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
     const uint32_t b = wg / cg.slices, s = wg - b * cg.slices;
     const uint32_t tag = cg.slices == 1u ? 0u : meet_tag(scratch);
-    const uint32_t t0 = s * kStridedSliceLen;
+    const uint32_t t0 = s * cg.slice_len;
     const uint32_t ngroups = strided_slice_groups(cg, s);
 
     const uint64_t jbase = (uint64_t)b * (cg.inner / 4u);           // the block's first group
@@ -442,7 +445,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     uint32_t where[GPT];                                           // kept for the stores
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        const uint32_t t = threadIdx.x + (uint32_t)k * THREADS;
         v[k] = make_uint4(0u, 0u, 0u, 0u);
         where[k] = walk.off;
         if (t < ngroups) {
@@ -450,7 +453,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
             v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in) + j));
             if (k < PRE) {
                 const Words4 r = random_words(j, key, 0u);
-                parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+                parked[k * THREADS + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
             }
         }
         strided_step(cg, walk);
@@ -461,15 +464,15 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
         const uint32_t gm = max4_mag(v[k]);
         m = m > gm ? m : gm;
     }
-    m = workgroup_max(m, lds);
+    m = workgroup_max<THREADS>(m, lds);
 
     // (a block that one workgroup holds alone has nobody to meet and leaves the scratch alone)
     uint32_t ticket = ~0u;
-    const uint32_t bm = cg.slices == 1u ? m : meet_in_block<true>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
+    const uint32_t bm = cg.slices == 1u ? m : meet_in_block<true, THREADS>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
         uint32_t own = 0;
         const uint32_t count = strided_slice_groups(cg, i);
-        for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
-            const uint4 w = *(reinterpret_cast<const uint4*>(in) + strided_group(cg, b, i * kStridedSliceLen + 4u * t));
+        for (uint32_t t = threadIdx.x; t < count; t += THREADS) {
+            const uint4 w = *(reinterpret_cast<const uint4*>(in) + strided_group(cg, b, i * cg.slice_len + 4u * t));
             const uint32_t gm = max4_mag(w);
             own = own > gm ? own : gm;
         }
@@ -480,12 +483,12 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_strided_kernel(cons
     const bool finite = wave_plans_are_finite<MODE>(p);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        const uint32_t t = threadIdx.x + (uint32_t)k * THREADS;
         if (t < ngroups) {
             const uint64_t j = jbase + where[k];
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) {
-                const uint4 w = parked[k * kThreads + threadIdx.x];
+                const uint4 w = parked[k * THREADS + threadIdx.x];
                 r = Words4{{w.x, w.y, w.z, w.w}};
             } else if (MODE == QSIM_STOCHASTIC) {
                 r = random_words(j, key, 0u);
@@ -565,7 +568,9 @@ __global__ __launch_bounds__(THREADS) void block_strided_wide_kernel(const uint3
 // dwordx4 load at a dword-aligned address is still the cheapest, then masked out of the maximum and
 // never stored).  Every segment is given G = (inner + 2) / 4 + 1 group slots, the most it can
 // cover; slot t of a block is slot u = t % G of segment o = t / G, unused when that segment covers
-// fewer groups.  The slots of a block are dealt out evenly to its slices, at most 4096 each.
+// fewer groups.  The slots of a block are dealt out evenly to its slices, at most 16 per thread:
+// 4096 each for workgroups of 256 threads, 8192 for workgroups of 512 (THREADS; two of those share
+// a CU where four of the smaller do: half as many workgroups have to meet per block).
 struct RaggedClusterGeom {
     uint64_t n;
     uint64_t nblocks;
@@ -576,11 +581,12 @@ struct RaggedClusterGeom {
     uint32_t slices;         // ceil(block_groups / 4096)
     uint32_t slice_groups;   // ceil(block_groups / slices): the slots are dealt out evenly
     uint32_t total_wgs;
-    // A thread's slots are kThreads apart: from one to its next, u grows by step_rest and the
+    // A thread's slots are one workgroup's threads apart: from one to its next, u grows by step_rest and the
     // segment's first element by step_elems, and by row_elems more when u passes G.
     uint32_t row_elems;      // nblocks * inner: from a segment of a block to its next (0 for a contiguous block)
-    uint32_t step_rest;      // kThreads % G
-    uint32_t step_elems;     // (kThreads / G) * row_elems
+    uint32_t threads;        // of a workgroup: 256, or 512 when a block has more slots than 256 threads hold
+    uint32_t step_rest;      // threads % G
+    uint32_t step_elems;     // (threads / G) * row_elems
     MeetGeom meet;
 };
 
@@ -632,15 +638,15 @@ __device__ __forceinline__ uint4 keep_masked(const uint4& v, uint32_t mask)
     return make_uint4((mask & 1u) ? v.x : 0u, (mask & 2u) ? v.y : 0u, (mask & 4u) ? v.z : 0u, (mask & 8u) ? v.w : 0u);
 }
 
-template <int MODE>
-__global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
+template <int MODE, int THREADS>
+__global__ __launch_bounds__(THREADS, 1024 / THREADS) void block_cluster_ragged_kernel(const uint32_t* in, uint32_t* out, uint64_t* scratch,
                                                                            RaggedClusterGeom cg, int wl, int symmetric,
                                                                            RngKey key)
 {
     constexpr int GPT = 16;
     constexpr int PRE = MODE == QSIM_STOCHASTIC ? 9 : 0;          // random words parked in LDS, as in the kernels above
-    __shared__ uint4 parked[PRE > 0 ? PRE * kThreads : 1];
-    __shared__ uint32_t lds[kThreads / 64];
+    __shared__ uint4 parked[PRE > 0 ? PRE * THREADS : 1];
+    __shared__ uint32_t lds[THREADS / 64];
     __shared__ uint32_t shared_word;
     const uint32_t wg = (uint32_t)linear_block();
     if (wg >= cg.total_wgs) return;                                // the whole workgroup leaves together
@@ -676,7 +682,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     uint32_t masks[2] = {0u, 0u};                                  // four bits per group
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        const uint32_t t = threadIdx.x + (uint32_t)k * THREADS;
         v[k] = make_uint4(0u, 0u, 0u, 0u);
         const uint32_t e = e0 + rel;
         where[k] = (e >> 2) + u;
@@ -696,7 +702,7 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
             v[k] = to_uint4(__builtin_nontemporal_load(reinterpret_cast<const u32x4_at_dword*>(src)));
             if (k < PRE) {
                 const Words4 r = random_words(j, key, 0u);
-                parked[k * kThreads + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
+                parked[k * THREADS + threadIdx.x] = make_uint4(r.w[0], r.w[1], r.w[2], r.w[3]);
             }
         }
         u += cg.step_rest;
@@ -719,14 +725,14 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
         const uint32_t gm = max4_mag(keep_masked(v[k], mask));       // strangers stay in v[k]: quantized below, never stored
         m = m > gm ? m : gm;
     }
-    m = workgroup_max(m, lds);
+    m = workgroup_max<THREADS>(m, lds);
 
     uint32_t ticket = ~0u;
-    const uint32_t bm = cg.slices == 1u ? m : meet_in_block<true>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
+    const uint32_t bm = cg.slices == 1u ? m : meet_in_block<true, THREADS>(scratch, cg.meet, b, s, tag, m, lds, shared_word, ticket, [&](uint32_t i) {
         // slice i of this block from memory, element by element where a group is shared
         uint32_t own = 0;
         const uint32_t count = ragged_slice_slots(cg, i);
-        for (uint32_t t = threadIdx.x; t < count; t += kThreads) {
+        for (uint32_t t = threadIdx.x; t < count; t += THREADS) {
             uint64_t j;
             uint32_t mask;
             ragged_slot(cg, b, i * cg.slice_groups + t, j, mask);
@@ -745,13 +751,13 @@ __global__ __launch_bounds__(kThreads, 4) void block_cluster_ragged_kernel(const
     const bool finite = wave_plans_are_finite<MODE>(p);
 #pragma unroll
     for (int k = 0; k < GPT; ++k) {
-        const uint32_t t = threadIdx.x + (uint32_t)k * kThreads;
+        const uint32_t t = threadIdx.x + (uint32_t)k * THREADS;
         if (t < nslots) {
             const uint64_t j = jbase + where[k];
             const uint32_t mask = (masks[k / 8] >> (4 * (k % 8))) & 0xFu;
             Words4 r = {{0u, 0u, 0u, 0u}};
             if (k < PRE) {
-                const uint4 w = parked[k * kThreads + threadIdx.x];
+                const uint4 w = parked[k * THREADS + threadIdx.x];
                 r = Words4{{w.x, w.y, w.z, w.w}};
             } else if (MODE == QSIM_STOCHASTIC) {
                 r = random_words(j, key, 0u);

@@ -684,7 +684,7 @@ __device__ __forceinline__ uint32_t slice_max(const uint32_t* in, const SliceVie
 __device__ __forceinline__ uint32_t slice_max_frugal(const uint32_t* in, const SliceView& sv)
 {
     uint32_t m = 0;
-    for (uint64_t t = threadIdx.x; t < sv.groups; t += kThreads) {
+    for (uint64_t t = threadIdx.x; t < sv.groups; t += blockDim.x) {       // (workgroups of 256 or 512 threads)
         const uint32_t gm = max4_mag(load_group<false>(in, sv.j0 + t, sv.end));
         m = m > gm ? m : gm;
     }
